@@ -1,0 +1,283 @@
+/*
+ * opevo.h -- C ABI of the MI355X (gfx950) trial-evaluation library for OpEvo.
+ *
+ * The library solves   x* = argmax_{x in X} f(x),  X = prod_i X_i   (Sec. 3, Eq. 1)
+ * where f(x) is the measured TFLOP/s of one tensor operator compiled under
+ * configuration x (Sec. 1, Sec. 3), by the evolutionary loop of Alg. 1 (Sec. 4.4).
+ * It holds: the configuration-space encoder (Sec. 3), the q-random-walk mutation
+ * (Sec. 4.3, Eq. 3; App. A), selection + recombination (Sec. 4.2, Eq. 2), HIP kernel
+ * templates for MatMul / BatchMatMul / Conv2d (App. B.1-B.3) instantiated per
+ * configuration through hipRTC, and a hipEvent measurement harness.
+ *
+ * Conventions
+ *  - Every call returns an int status: OPEVO_OK (0) or a negative OPEVO_E_* code.
+ *    Nothing throws or aborts.  opevo_last_error() returns a thread-local text for
+ *    the last failing call on this thread (hipRTC log included).
+ *  - Handles (opevo_space, opevo_rng, opevo_tuner, opevo_op, opevo_kernel) are owned by
+ *    the library from *_create until *_destroy.  All arrays are caller-owned HOST memory
+ *    unless the argument is documented as a DEVICE pointer.  Device pointers and the
+ *    stream are borrowed for the duration of the call; the library never frees them.
+ *  - Flat configuration encoding (int32): parameters in declaration order; a FACTOR
+ *    parameter takes nu slots (its factors, outermost first, product == C); a
+ *    PERMUTATION of n items takes n slots (the order, items 0..n-1); DISCRETE and
+ *    CATEGORICAL take one slot (index into the value list).
+ *  - "Illegal" = not a member of the space: an error of the caller (OPEVO_E_ILLEGAL).
+ *    "Invalid" = a member the kernel templates or the hardware cannot run (too many
+ *    threads, LDS or registers; compile failure): such a trial is still an evaluation,
+ *    with fitness 0 (Sec. 4.2), and the reason is reported as OPEVO_E_INVALID.
+ *  - Random numbers: SplitMix64 (state += 0x9E3779B97F4A7C15, then the two
+ *    multiply-xorshift rounds), double = (u64 >> 11) * 2^-53, integer below n =
+ *    ((u64 >> 32) * n) >> 32.  The order in which each routine draws is stated at
+ *    the routine, so a run is reproducible from its seed alone.
+ */
+#ifndef OPEVO_H
+#define OPEVO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OPEVO_OK            0
+#define OPEVO_E_ARG        -1   /* null pointer, bad enum, size or capacity too small            */
+#define OPEVO_E_ILLEGAL    -2   /* configuration / vertex is not in the space                     */
+#define OPEVO_E_INVALID    -3   /* legal configuration that cannot run (fitness 0, Sec. 4.2)      */
+#define OPEVO_E_HIPRTC     -4   /* hipRTC failure (log in opevo_last_error)                       */
+#define OPEVO_E_HIP        -5   /* HIP runtime failure, or no usable GPU                          */
+#define OPEVO_E_PARITY     -6   /* result disagrees with the supplied reference tensor            */
+#define OPEVO_E_TOO_LARGE  -7   /* feasible set too large to enumerate / solve exactly            */
+#define OPEVO_E_STATE      -8   /* call sequence error (e.g. best() before any tell())            */
+
+typedef struct opevo_space  opevo_space;
+typedef struct opevo_rng    opevo_rng;
+typedef struct opevo_tuner  opevo_tuner;
+typedef struct opevo_op     opevo_op;
+typedef struct opevo_kernel opevo_kernel;
+
+const char *opevo_last_error(void);
+const char *opevo_status_name(int status);
+/* Library version as a static string. */
+const char *opevo_version(void);
+
+/* ------------------------------------------------------------------ random numbers */
+int opevo_rng_create(uint64_t seed, opevo_rng **out);
+int opevo_rng_destroy(opevo_rng *rng);
+int opevo_rng_next_u64(opevo_rng *rng, uint64_t *out);
+int opevo_rng_next_double(opevo_rng *rng, double *out);          /* [0,1)            */
+int opevo_rng_next_below(opevo_rng *rng, uint32_t n, uint32_t *out); /* [0,n), n > 0 */
+
+/* ------------------------------------------------- configuration space (Sec. 3, Eq. 1) */
+typedef enum {
+    OPEVO_FACTOR      = 0,  /* nu ordered positive factors with product C; adjacency: move one
+                               prime from one factor to another (Sec. 3)                        */
+    OPEVO_PERMUTATION = 1,  /* orders of n items; adjacency: one transposition (Sec. 3)         */
+    OPEVO_DISCRETE    = 2,  /* strictly ascending reals; adjacency: neighbours in value order   */
+    OPEVO_CATEGORICAL = 3   /* J unordered choices; adjacency: complete graph (Sec. 3)          */
+} opevo_ptype;
+
+typedef struct {
+    int32_t       type;      /* opevo_ptype                                                     */
+    int32_t       nu;        /* FACTOR: number of factors (>= 1)                                */
+    int64_t       C;         /* FACTOR: the product (>= 1)                                      */
+    int32_t       n_values;  /* PERMUTATION: n items; DISCRETE: value count; CATEGORICAL: J     */
+    int32_t       reserved;
+    const double *values;    /* DISCRETE: n_values strictly ascending numbers (copied); else NULL */
+    const char   *name;      /* optional label (copied), may be NULL                            */
+} opevo_param_desc;
+
+/* Builds X = prod X_i.  OPEVO_E_ARG for a malformed descriptor, OPEVO_E_TOO_LARGE if a single
+ * feasible set has more than 2^24 vertices. */
+int opevo_space_create(const opevo_param_desc *params, int n_params, opevo_space **out);
+int opevo_space_destroy(opevo_space *space);
+int opevo_space_num_params(const opevo_space *space, int *n_params);
+int opevo_space_width(const opevo_space *space, int *n_int32);             /* flat length     */
+int opevo_space_param_slice(const opevo_space *space, int param, int *offset, int *width);
+int opevo_space_param_name(const opevo_space *space, int param, const char **name);
+int opevo_space_param_size(const opevo_space *space, int param, int64_t *n_vertices);
+int opevo_space_size(const opevo_space *space, double *n_configs);         /* prod |X_i|      */
+/* OPEVO_OK if cfg (flat, width ints) is a member of X, else OPEVO_E_ILLEGAL. */
+int opevo_space_is_legal(const opevo_space *space, const int32_t *cfg);
+/* All vertices of X_param in the canonical order (FACTOR and PERMUTATION: lexicographic;
+ * DISCRETE / CATEGORICAL: index order), each `width(param)` ints, into out[cap_vertices*width].
+ * *n receives the vertex count; OPEVO_E_ARG if cap_vertices is too small (*n still set). */
+int opevo_space_enumerate(const opevo_space *space, int param, int32_t *out,
+                          int64_t cap_vertices, int64_t *n);
+/* S(v): the vertices adjacent to v in X_param, in the canonical order (FACTOR: source
+ * position ascending, then prime ascending, then target position ascending; PERMUTATION:
+ * position pairs i<j lexicographic; DISCRETE: lower then upper; CATEGORICAL: index order). */
+int opevo_space_neighbors(const opevo_space *space, int param, const int32_t *v,
+                          int32_t *out, int cap_vertices, int *n);
+/* Mixed-radix index of a configuration: parameter 0 most significant, digit = position of
+ * the parameter's vertex in enumerate order.  Only for spaces with fewer than 2^62 members. */
+int opevo_space_rank(const opevo_space *space, const int32_t *cfg, int64_t *rank);
+int opevo_space_unrank(const opevo_space *space, int64_t rank, int32_t *cfg_out);
+/* Uniform member of X: per parameter, in order, vertex index = next_below(|X_i|). */
+int opevo_space_random(const opevo_space *space, opevo_rng *rng, int32_t *cfg_out);
+/* One q-random walk (Sec. 4.3) on parameter `param`, in place on that parameter's slots of
+ * v (a vertex, width(param) ints).  Per step: if S(u) is empty return (no draw); draw
+ * next_double(), stop unless it is < q; else u = S(u)[next_below(|S(u)|)].  0 <= q < 1. */
+int opevo_space_walk(const opevo_space *space, int param, double q, opevo_rng *rng, int32_t *v);
+/* Mutation of a whole configuration: an independent walk on every parameter, in order. */
+int opevo_space_mutate(const opevo_space *space, double q, opevo_rng *rng, int32_t *cfg_inout);
+/* Exact q-random-walk distribution from `start` (App. A: S = (1-q)(I-Q)^-1 p0) by a dense
+ * fp64 solve; probs_out[i] belongs to vertex i of enumerate order.  For feasible sets of at
+ * most 2048 vertices (else OPEVO_E_TOO_LARGE).  An isolated start gives the point mass. */
+int opevo_qrw_exact(const opevo_space *space, int param, const int32_t *start, double q,
+                    double *probs_out, int64_t cap);
+
+/* ------------------------------------- selection, recombination, Alg. 1 (Sec. 4.2, 4.4) */
+/* One child by Eq. 2: parents are given best first (n_parents configs, flat) with their
+ * fitness (negative / NaN count as 0).  Per parameter, in order: if the fitness total is > 0,
+ * t = next_double()*total and the parent is the first j with t < f_1+..+f_j; else
+ * j = next_below(n_parents).  The parameter is copied whole from that parent. */
+int opevo_recombine(const opevo_space *space, const int32_t *parents, const double *fitness,
+                    int n_parents, opevo_rng *rng, int32_t *child_out);
+
+/* Alg. 1 in ask/tell form.  lambda = parents, rho = children per generation, 0 <= q < 1.
+ * The tuner keeps the space pointer: destroy the tuner first. */
+int opevo_tuner_create(const opevo_space *space, int lambda, int rho, double q, uint64_t seed,
+                       opevo_tuner **out);
+int opevo_tuner_destroy(opevo_tuner *tuner);
+/* Next configurations to evaluate, at most max_n (max_n <= 0: no cap): the first call gives
+ * lambda random members, later calls give rho children of the top-lambda of everything told
+ * so far (ties: earlier trial first).  No configuration is ever returned twice, whether it was
+ * told or is still pending: a duplicate child is mutated again from where it stands, up to 100
+ * times, then replaced by a uniformly random unsampled member.  *n_out == 0: space exhausted.
+ * cfgs_out holds max(lambda, rho) * width ints. */
+int opevo_tuner_ask(opevo_tuner *tuner, int32_t *cfgs_out, int max_n, int *n_out);
+/* Enqueue n evaluated configurations with their fitness (TFLOP/s; 0 for invalid ones). */
+int opevo_tuner_tell(opevo_tuner *tuner, const int32_t *cfgs, const double *fitness, int n);
+int opevo_tuner_num_trials(const opevo_tuner *tuner, int *n);
+/* Best configuration so far, its fitness and its 0-based trial index. */
+int opevo_tuner_best(const opevo_tuner *tuner, int32_t *cfg_out, double *fitness, int *trial);
+/* The whole history in trial order. */
+int opevo_tuner_history(const opevo_tuner *tuner, int32_t *cfgs_out, double *fitness_out,
+                        int cap_trials, int *n);
+
+/* --------------------------------------------------------- operators (App. B.1 - B.3) */
+typedef enum { OPEVO_MATMUL = 0, OPEVO_BMM = 1, OPEVO_CONV2D = 2 } opevo_op_kind;
+typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
+
+/* Which configuration space / kernel template family an operator is tuned in.
+ *  TILE2: every loop axis split in two (outer = workgroups or steps, inner = tile); one
+ *         scalar-FMA template that runs every member.  MatMul only.
+ *         params: M(2) N(2) K(2).
+ *  TILE4: output axes split in four (workgroups, waves per workgroup, basic tiles per wave,
+ *         basic tile), reduction axis in two (steps, LDS tile), plus one binary flag:
+ *         MatMul  M(4) N(4) K(2) unroll{0,1}        (double-buffered, unrolled main loop)
+ *         BMM     B(2) M(4) N(4) K(2) lds{0,1}      (stage operands through LDS or not)
+ *         Conv2d  B(2) Cout(4) H(4) W(4) R(2) unroll{0,1},  R = Cin*Hk*Wk
+ *         MFMA kernels (bf16/fp16 inputs) where the per-wave tile is made of 32x32 or 16x16
+ *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1 } opevo_variant;
+
+/* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
+ *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
+ *        CONV2D {B, Cin, H, W, Cout, Hk, Wk, stride, pad}  NCHW image, OIHW kernel,
+ *               out[B,Cout,Hout,Wout], Hout = floor((H+2*pad-Hk)/stride)+1 (App. B.3).
+ * All tensors dense row-major.  `in` is the element type of both inputs; accumulation and
+ * the output are always fp32. */
+int opevo_op_create(int kind, const int64_t *dims, int n_dims, int in_dtype, opevo_op **out);
+int opevo_op_destroy(opevo_op *op);
+int opevo_op_flops(const opevo_op *op, double *flops);     /* 2*MACs, padding taps counted  */
+int opevo_op_bytes(const opevo_op *op, double *bytes);     /* read A, B once + write C once */
+int opevo_op_sizes(const opevo_op *op, int64_t *a_elems, int64_t *b_elems, int64_t *c_elems);
+/* The operator's configuration space for a variant (caller destroys it). */
+int opevo_op_space(const opevo_op *op, int variant, opevo_space **out);
+
+typedef struct {
+    int32_t status;        /* OPEVO_OK or OPEVO_E_INVALID                                      */
+    int32_t path;          /* 0 scalar FMA, 1 MFMA 32x32x16, 2 MFMA 16x16x32                   */
+    int32_t grid[3];
+    int32_t block;         /* threads per workgroup                                            */
+    int32_t lds_bytes;
+    int32_t acc_per_lane;  /* fp32 accumulators each lane holds                                */
+    int32_t tile[3];       /* workgroup tile BM, BN, BK                                        */
+    int32_t wave_tile[2];  /* per-wave tile                                                    */
+    char    reason[96];    /* why invalid, else empty                                          */
+} opevo_plan;
+
+/* Decode + validate (host only, no GPU): OPEVO_E_ILLEGAL if cfg is not in the space;
+ * otherwise OPEVO_OK with plan->status telling valid / invalid. */
+int opevo_kernel_plan(const opevo_op *op, int variant, const int32_t *cfg, opevo_plan *plan);
+/* The hipRTC option string ("-DBM=.. ...") and template name the configuration renders to. */
+int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg,
+                         char *buf, size_t cap);
+/* Instantiate: render + hipRTC-compile for gfx950 (works without a GPU).  Returns
+ * OPEVO_E_INVALID for an invalid configuration (no kernel), OPEVO_E_HIPRTC on a compile
+ * failure.  The module is loaded on the first launch. */
+int opevo_kernel_build(const opevo_op *op, int variant, const int32_t *cfg,
+                       opevo_kernel **out, double *compile_ms);
+int opevo_kernel_destroy(opevo_kernel *kernel);
+int opevo_kernel_code_size(const opevo_kernel *kernel, size_t *bytes);
+/* Registers / scratch the compiler used (available after the first launch loaded it). */
+int opevo_kernel_resources(opevo_kernel *kernel, int *vgprs, int *sgprs, int *spill_bytes,
+                           int *static_lds);
+/* One launch on `stream` (a hipStream_t, NULL = default stream).  a, b, c are DEVICE
+ * pointers: the two inputs in the operator's input dtype and the fp32 output, sized as
+ * opevo_op_sizes says, 16-byte aligned.  MatMul / BMM: a = A, b = B.  Conv2d: a = the kernel
+ * tensor [Cout,Cin,Hk,Wk], b = the image [B,Cin,H,W].  Asynchronous. */
+int opevo_kernel_launch(opevo_kernel *kernel, const void *a, const void *b, void *c, void *stream);
+/* Timing (Sec. 3: f = TFLOP/s): `warmup` untimed launches (the first of them is itself
+ * timed, to size a sample), then `samples` samples of `launches_per_sample` back-to-back
+ * launches bracketed by two hipEvents on `stream`; ms per launch of each sample into
+ * samples_ms (may be NULL), median into *median_ms.  launches_per_sample <= 0: chosen so that
+ * one sample spans at least 200 us.  A launch of 50 ms or more is taken as the measurement
+ * on its own.  timeout_ms > 0 gives scalar-template kernels a deadline per sample: one that
+ * is still running then winds down by itself (every workgroup leaves at its next K slab) and
+ * the call returns OPEVO_E_INVALID; 0 = no deadline.  Synchronises `stream`. */
+int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *c, void *stream,
+                      int warmup, int launches_per_sample, int samples, double timeout_ms,
+                      double *median_ms, double *samples_ms);
+
+/* Parity gate: c and ref are DEVICE fp32 arrays of n elements.
+ * max_scaled = max |c-ref| / (|ref|+1), rel_fro = ||c-ref||_F / ||ref||_F (0 if both 0).
+ * Uses a library-owned device workspace allocated on first use. Synchronises `stream`. */
+int opevo_compare_f32(const float *c, const float *ref, int64_t n, void *stream,
+                      double *max_scaled, double *rel_fro);
+
+/* -------------------------------------------------------- whole tuning run (Alg. 1) */
+typedef struct {
+    const void *a, *b;         /* DEVICE inputs                                                  */
+    void       *c;             /* DEVICE fp32 output, overwritten by every trial                 */
+    const float *ref;          /* DEVICE fp32 reference tensor for the parity gate, or NULL      */
+    void       *stream;        /* hipStream_t                                                    */
+    int32_t     trials;        /* evaluation budget, the initial lambda included                 */
+    int32_t     lambda, rho;   /* Alg. 1                                                         */
+    double      q;
+    uint64_t    seed;
+    int32_t     compile_threads;   /* concurrent hipRTC instantiations per generation (>= 1)     */
+    int32_t     warmup, launches_per_sample, samples;   /* as opevo_kernel_time                  */
+    double      trial_timeout_ms;                       /* as opevo_kernel_time, 0 = none        */
+    double      tol_max_scaled, tol_rel_fro;            /* parity gate thresholds                */
+    /* optional per-trial logs, each `trials` long (cfg_log: trials*width), may be NULL */
+    int32_t    *cfg_log;
+    double     *fitness_log;   /* TFLOP/s, 0 for invalid / failed                                */
+    int32_t    *status_log;    /* OPEVO_OK, OPEVO_E_INVALID, OPEVO_E_HIPRTC, OPEVO_E_PARITY, ... */
+    double     *compile_ms_log;
+    double     *run_ms_log;    /* median ms per launch                                           */
+    double     *wall_s_log;    /* seconds since the start of the run when the trial finished     */
+} opevo_tune_args;
+
+typedef struct {
+    int32_t n_trials;          /* evaluated (may be < trials if the space was exhausted)         */
+    int32_t best_trial;        /* index of the best trial, -1 if none had fitness > 0            */
+    double  best_tflops;
+    double  best_ms;
+    int32_t n_invalid, n_compile_fail, n_parity_fail;
+    double  wall_s, compile_s, run_s;   /* total, hipRTC (wall, overlapped), GPU measurement     */
+} opevo_tune_result;
+
+/* Runs Alg. 1 on the GPU: ask -> instantiate the generation's children concurrently ->
+ * time each -> parity gate -> tell.  best_cfg_out receives the best configuration
+ * (width ints).  A parity failure gives that trial fitness 0 and is counted; it does not
+ * stop the run. */
+int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args *args,
+               int32_t *best_cfg_out, opevo_tune_result *result);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPEVO_H */

@@ -1,0 +1,147 @@
+// Precompiled device helpers of the harness.
+//
+// Parity gate: compares a trial's fp32 output with a reference tensor on the device.
+//   max_scaled = max_i |c_i - ref_i| / (|ref_i| + 1),   rel_fro = ||c - ref||_F / ||ref||_F.
+// Any NaN in c makes max_scaled infinite, so a broken kernel can never pass.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <mutex>
+#include <vector>
+
+#include "kernel.hpp"
+
+namespace {
+
+constexpr int kBlocks = 1024;
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads)
+void compare_partial(const float *__restrict__ c, const float *__restrict__ ref, long n, double *__restrict__ part)
+{
+    double mx = 0.0, se = 0.0, sr = 0.0;
+    for (long i = (long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long)gridDim.x * kThreads) {
+        const double r = ref[i], d = (double)c[i] - r;
+        const double s = fabs(d) / (fabs(r) + 1.0);
+        mx = (s <= mx) ? mx : (s == s ? s : INFINITY);   // NaN -> inf
+        se += d * d;
+        sr += r * r;
+    }
+    __shared__ double smx[kThreads], sse[kThreads], ssr[kThreads];
+    smx[threadIdx.x] = mx; sse[threadIdx.x] = se; ssr[threadIdx.x] = sr;
+    __syncthreads();
+    for (int s = kThreads / 2; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            smx[threadIdx.x] = fmax(smx[threadIdx.x], smx[threadIdx.x + s]);
+            sse[threadIdx.x] += sse[threadIdx.x + s];
+            ssr[threadIdx.x] += ssr[threadIdx.x + s];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        part[blockIdx.x * 3 + 0] = smx[0];
+        part[blockIdx.x * 3 + 1] = sse[0];
+        part[blockIdx.x * 3 + 2] = ssr[0];
+    }
+}
+
+// Deadline control block of the scalar template: {start tick, allowed ticks, expired flag}.
+__global__ void stamp_deadline(unsigned long long *ctl, unsigned long long ticks)
+{
+    ctl[0] = wall_clock64();
+    ctl[1] = ticks;
+    ctl[2] = 0;
+}
+
+std::mutex g_ws_mutex;
+double *g_ws[64] = {nullptr};   // one workspace per device, kept until the process ends
+unsigned long long *g_ctl[64] = {nullptr};
+double g_ticks_per_ms[64] = {0.0};
+
+}  // namespace
+
+namespace opevo {
+
+int compare_f32(const float *c, const float *ref, int64_t n, hipStream_t stream, double *max_scaled, double *rel_fro)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return fail(OPEVO_E_HIP, "device index %d out of range", dev);
+    double *ws;
+    {
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        if (!g_ws[dev]) {
+            e = hipMalloc(&g_ws[dev], sizeof(double) * 3 * kBlocks);
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(compare workspace)");
+        }
+        ws = g_ws[dev];
+    }
+    int blocks = int(std::min<int64_t>(kBlocks, (n + kThreads - 1) / kThreads));
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(compare_partial, dim3(blocks), dim3(kThreads), 0, stream, c, ref, (long)n, ws);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "compare_partial launch");
+    std::vector<double> host(size_t(3) * blocks);
+    e = hipMemcpyAsync(host.data(), ws, sizeof(double) * 3 * blocks, hipMemcpyDeviceToHost, stream);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
+    e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    double mx = 0.0, se = 0.0, sr = 0.0;
+    for (int b = 0; b < blocks; ++b) {
+        mx = std::fmax(mx, host[b * 3 + 0]);
+        se += host[b * 3 + 1];
+        sr += host[b * 3 + 2];
+    }
+    if (max_scaled) *max_scaled = mx;
+    if (rel_fro) *rel_fro = sr > 0.0 ? std::sqrt(se / sr) : (se > 0.0 ? INFINITY : 0.0);
+    return OPEVO_OK;
+}
+
+int deadline_ctl(unsigned long long **ctl)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return fail(OPEVO_E_HIP, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (!g_ctl[dev]) {
+        int khz = 0;
+        e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+        if (e != hipSuccess || khz <= 0) khz = 100000;   // 100 MHz constant clock
+        g_ticks_per_ms[dev] = double(khz);
+        e = hipMalloc(&g_ctl[dev], 4 * sizeof(unsigned long long));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(deadline control)");
+    }
+    *ctl = g_ctl[dev];
+    return OPEVO_OK;
+}
+
+int deadline_arm(unsigned long long *ctl, double timeout_ms, hipStream_t stream)
+{
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const unsigned long long ticks = (unsigned long long)(timeout_ms * g_ticks_per_ms[dev]) + 1ull;
+    hipLaunchKernelGGL(stamp_deadline, dim3(1), dim3(1), 0, stream, ctl, ticks);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? OPEVO_OK : hip_fail(e, "stamp_deadline launch");
+}
+
+int deadline_expired(unsigned long long *ctl, hipStream_t stream, bool *expired)
+{
+    unsigned long long flag = 0;
+    hipError_t e = hipMemcpyAsync(&flag, ctl + 2, sizeof flag, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail(e, "reading the deadline flag");
+    *expired = flag != 0;
+    return OPEVO_OK;
+}
+
+}  // namespace opevo
+
+extern "C" int opevo_compare_f32(const float *c, const float *ref, int64_t n, void *stream,
+                                 double *max_scaled, double *rel_fro)
+{
+    if (!c || !ref || n < 1) return opevo::fail(OPEVO_E_ARG, "compare_f32: bad arguments");
+    return opevo::compare_f32(c, ref, n, static_cast<hipStream_t>(stream), max_scaled, rel_fro);
+}

@@ -1,0 +1,291 @@
+// Operator descriptors, configuration spaces and the configuration decoder.
+#include "op.hpp"
+
+#include <cstring>
+#include <new>
+#include <sstream>
+
+using namespace opevo;
+
+static const int kMaxThreads = 1024;            // threads per workgroup on gfx950
+static const int kMaxLds = 160 * 1024;          // LDS bytes per workgroup on gfx950
+static const int kMaxAcc = 256;                 // fp32 accumulators per lane kept in registers
+static const int kPad = 8;                      // LDS row padding of the MFMA template (elements)
+
+int64_t opevo_op::a_elems() const
+{
+    return kind == OPEVO_CONV2D ? M * K : batch * M * K;   // conv: kernel tensor [Cout][Cin*Hk*Wk]
+}
+
+int64_t opevo_op::b_elems() const
+{
+    return kind == OPEVO_CONV2D ? nimg * cin * hin * win : batch * K * N;
+}
+
+namespace opevo {
+
+static opevo_param_desc factor(const char *name, int64_t C, int nu)
+{
+    opevo_param_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.type = OPEVO_FACTOR; d.C = C; d.nu = nu; d.name = name;
+    return d;
+}
+
+static opevo_param_desc flag(const char *name)
+{
+    opevo_param_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.type = OPEVO_CATEGORICAL; d.n_values = 2; d.name = name;
+    return d;
+}
+
+int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc> &descs)
+{
+    descs.clear();
+    if (variant == OPEVO_TILE2) {
+        if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the two-level space exists for MatMul only");
+        descs = {factor("M", op.M, 2), factor("N", op.N, 2), factor("K", op.K, 2)};
+        return OPEVO_OK;
+    }
+    if (variant != OPEVO_TILE4) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
+    switch (op.kind) {
+    case OPEVO_MATMUL:
+        descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 2), flag("unroll")};
+        break;
+    case OPEVO_BMM:
+        descs = {factor("B", op.batch, 2), factor("M", op.M, 4), factor("N", op.N, 4),
+                 factor("K", op.K, 2), flag("lds")};
+        break;
+    case OPEVO_CONV2D:
+        descs = {factor("B", op.nimg, 2), factor("Cout", op.M, 4), factor("H", op.hout, 4),
+                 factor("W", op.wout, 4), factor("R", op.K, 2), flag("unroll")};
+        break;
+    default:
+        return fail(OPEVO_E_ARG, "unknown operator kind %d", op.kind);
+    }
+    return OPEVO_OK;
+}
+
+static void invalid(opevo_plan &p, const char *fmt, long a = 0, long b = 0)
+{
+    p.status = OPEVO_E_INVALID;
+    snprintf(p.reason, sizeof p.reason, fmt, a, b);
+}
+
+int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
+{
+    std::vector<opevo_param_desc> descs;
+    if (int rc = op_param_descs(op, variant, descs)) return rc;
+    // legality: every factor tuple multiplies back to its axis, flags in range
+    {
+        int off = 0;
+        for (const auto &d : descs) {
+            if (d.type == OPEVO_FACTOR) {
+                int64_t prod = 1;
+                for (int j = 0; j < d.nu; ++j) {
+                    if (cfg[off + j] < 1) return fail(OPEVO_E_ILLEGAL, "factor %d of %s is < 1", j, d.name);
+                    prod *= cfg[off + j];
+                    if (prod > d.C) break;
+                }
+                if (prod != d.C)
+                    return fail(OPEVO_E_ILLEGAL, "factors of %s do not multiply to %lld", d.name, (long long)d.C);
+                off += d.nu;
+            } else {
+                if (cfg[off] < 0 || cfg[off] >= d.n_values)
+                    return fail(OPEVO_E_ILLEGAL, "flag %s out of range", d.name);
+                off += 1;
+            }
+        }
+    }
+
+    opevo_plan &p = out.plan;
+    std::memset(&p, 0, sizeof p);
+    p.status = OPEVO_OK;
+    std::ostringstream D;
+
+    // ---- common GEMM-view quantities filled by each variant
+    int64_t m1 = 1, n1 = 1, b1 = 1, binner = 1;
+    int64_t BM = 1, BN = 1, BK = 1, ksteps = 1, WM = 1, WN = 1, TM = 1, TN = 1, FM = 1, FN = 1;
+    int flagv = 0;
+    int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
+    bool four_level = (variant == OPEVO_TILE4);
+
+    if (!four_level) {
+        m1 = cfg[0]; BM = cfg[1]; n1 = cfg[2]; BN = cfg[3]; ksteps = cfg[4]; BK = cfg[5];
+        flagv = 1;
+    } else if (op.kind == OPEVO_MATMUL || op.kind == OPEVO_BMM) {
+        const int32_t *c = cfg;
+        if (op.kind == OPEVO_BMM) { b1 = c[0]; binner = c[1]; c += 2; }
+        m1 = c[0]; WM = c[1]; TM = int64_t(c[2]) * c[3]; FM = c[3];
+        n1 = c[4]; WN = c[5]; TN = int64_t(c[6]) * c[7]; FN = c[7];
+        ksteps = c[8]; BK = c[9]; flagv = c[10];
+        BM = WM * TM; BN = WN * TN;
+    } else {   // conv: B(2) Cout(4) H(4) W(4) R(2) flag
+        const int32_t *c = cfg;
+        const int64_t nb1 = c[0]; nb2 = c[1];
+        m1 = c[2]; WM = c[3]; TM = int64_t(c[4]) * c[5]; FM = c[5];
+        const int32_t *h = c + 6, *w = c + 10;
+        h1 = h[0]; w1 = w[0];
+        BH = int64_t(h[1]) * h[2] * h[3]; BW = int64_t(w[1]) * w[2] * w[3];
+        WN = int64_t(h[1]) * w[1];
+        TN = nb2 * h[2] * h[3] * w[2] * w[3];
+        FN = nb2 * h[3] * w[3];
+        n1 = nb1 * h1 * w1;
+        ksteps = c[14]; BK = c[15]; flagv = c[16];
+        BM = WM * TM; BN = WN * TN;
+    }
+
+    // ---- template choice
+    int path = 0;   // scalar
+    if (four_level && op.dtype != OPEVO_F32) {
+        const bool align_ok = (op.K % 8 == 0) && (op.kind == OPEVO_CONV2D || op.N % 8 == 0);
+        if (align_ok && TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0) path = 1;
+        else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
+    }
+    const bool stage_lds = !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
+
+    int64_t NT;
+    if (four_level) NT = 64 * WM * WN;
+    else {
+        NT = ((BM * BN + 63) / 64) * 64;
+        if (NT > 256) NT = 256;
+    }
+    int64_t acc = (path == 0) ? (BM * BN + NT - 1) / NT : (TM * TN) / 64;
+    const int nstage = (path != 0 && flagv && ksteps > 1) ? 2 : 1;
+    int64_t lds = 0;
+    if (path == 0) lds = (BM * BK + BK * BN) * 4;
+    else if (stage_lds) lds = nstage * (BM + BN) * (BK + kPad) * 2;
+
+    p.path = path;
+    p.grid[0] = int32_t(n1); p.grid[1] = int32_t(m1); p.grid[2] = int32_t(b1);
+    p.block = int32_t(NT > INT32_MAX ? INT32_MAX : NT);
+    p.lds_bytes = int32_t(lds > INT32_MAX ? INT32_MAX : lds);
+    p.acc_per_lane = int32_t(acc > INT32_MAX ? INT32_MAX : acc);
+    p.tile[0] = int32_t(BM); p.tile[1] = int32_t(BN); p.tile[2] = int32_t(BK);
+    p.wave_tile[0] = int32_t(four_level ? TM : BM); p.wave_tile[1] = int32_t(four_level ? TN : BN);
+
+    // ---- black-box constraints made explicit: such members get fitness 0 (Sec. 4.2)
+    if (NT > kMaxThreads) invalid(p, "%ld threads per workgroup > %ld", long(NT), long(kMaxThreads));
+    else if (acc > kMaxAcc) invalid(p, "%ld accumulators per lane > %ld", long(acc), long(kMaxAcc));
+    else if (lds + (path == 0 ? 16 : 0) > kMaxLds)   // the scalar template adds a static flag word
+        invalid(p, "%ld bytes of LDS > %ld", long(lds), long(kMaxLds));
+    else if (m1 > 65535 || b1 > 65535) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
+    else if (path != 0 && stage_lds) {
+        // register budget of the slab in flight: 16-byte pieces per thread
+        const int64_t a_chunks = (BM * (BK / 8) + NT - 1) / NT;
+        const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BK / 8) + NT - 1) / NT
+                                                           : 8 * (((BK / 8) * (BN / 8) + NT - 1) / NT);
+        if ((a_chunks + b_chunks) * 4 > 256)
+            invalid(p, "%ld staging registers per lane > 256", long((a_chunks + b_chunks) * 4));
+    }
+
+    out.tmpl = path == 0 ? "gemm_scalar" : "gemm_mfma";
+    D << "-DOP=" << op.kind << " -DIN_DTYPE=" << op.dtype << " -DM=" << op.M << " -DN=" << op.N
+      << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
+      << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv;
+    if (path != 0) {
+        D << " -DATOM=" << (path == 1 ? 32 : 16) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
+          << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
+          << " -DNSTAGE=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
+    }
+    if (op.kind == OPEVO_CONV2D) {
+        D << " -DCIN=" << op.cin << " -DHIN=" << op.hin << " -DWIN=" << op.win << " -DHK=" << op.hk
+          << " -DWK=" << op.wk << " -DSTRIDE=" << op.stride << " -DPAD_CONV=" << op.pad
+          << " -DHOUT=" << op.hout << " -DWOUT=" << op.wout << " -DNB2=" << nb2 << " -DBH=" << BH
+          << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1;
+    }
+    out.defines = D.str();
+    return OPEVO_OK;
+}
+
+}  // namespace opevo
+
+extern "C" {
+
+int opevo_op_create(int kind, const int64_t *dims, int n_dims, int in_dtype, opevo_op **out)
+{
+    if (!dims || !out) return fail(OPEVO_E_ARG, "op_create: NULL argument");
+    if (in_dtype < OPEVO_F32 || in_dtype > OPEVO_F16) return fail(OPEVO_E_ARG, "op_create: unknown dtype %d", in_dtype);
+    opevo_op op;
+    op.kind = kind; op.dtype = in_dtype;
+    const int need = kind == OPEVO_MATMUL ? 3 : kind == OPEVO_BMM ? 4 : kind == OPEVO_CONV2D ? 9 : -1;
+    if (need < 0) return fail(OPEVO_E_ARG, "op_create: unknown operator kind %d", kind);
+    if (n_dims != need) return fail(OPEVO_E_ARG, "op_create: operator needs %d dims, got %d", need, n_dims);
+    for (int i = 0; i < n_dims; ++i) {
+        const bool may_be_zero = (kind == OPEVO_CONV2D && i == 8);   // padding
+        if (dims[i] < (may_be_zero ? 0 : 1) || dims[i] > (int64_t(1) << 30))
+            return fail(OPEVO_E_ARG, "op_create: dims[%d] = %lld out of range", i, (long long)dims[i]);
+    }
+    if (kind == OPEVO_MATMUL) { op.M = dims[0]; op.N = dims[1]; op.K = dims[2]; }
+    else if (kind == OPEVO_BMM) { op.batch = dims[0]; op.M = dims[1]; op.N = dims[2]; op.K = dims[3]; }
+    else {
+        op.nimg = dims[0]; op.cin = dims[1]; op.hin = dims[2]; op.win = dims[3];
+        op.M = dims[4]; op.hk = dims[5]; op.wk = dims[6]; op.stride = dims[7]; op.pad = dims[8];
+        const int64_t sh = op.hin + 2 * op.pad - op.hk, sw = op.win + 2 * op.pad - op.wk;
+        if (sh < 0 || sw < 0) return fail(OPEVO_E_ARG, "op_create: kernel larger than the padded image");
+        op.hout = sh / op.stride + 1;    // App. B.3
+        op.wout = sw / op.stride + 1;
+        op.K = op.cin * op.hk * op.wk;
+        op.N = op.nimg * op.hout * op.wout;
+    }
+    if (double(op.batch) * double(op.M) * double(op.N) > 4.0e18 || op.a_elems() < 0 || op.b_elems() < 0)
+        return fail(OPEVO_E_ARG, "op_create: tensor too large");
+    *out = new (std::nothrow) opevo_op(op);
+    return *out ? OPEVO_OK : fail(OPEVO_E_ARG, "out of memory");
+}
+
+int opevo_op_destroy(opevo_op *op) { delete op; return OPEVO_OK; }
+
+int opevo_op_flops(const opevo_op *op, double *flops)
+{
+    if (!op || !flops) return fail(OPEVO_E_ARG, "op_flops: NULL argument");
+    *flops = op->flops();
+    return OPEVO_OK;
+}
+
+int opevo_op_bytes(const opevo_op *op, double *bytes)
+{
+    if (!op || !bytes) return fail(OPEVO_E_ARG, "op_bytes: NULL argument");
+    *bytes = double(op->a_elems() + op->b_elems()) * op->elem_size() + double(op->c_elems()) * 4.0;
+    return OPEVO_OK;
+}
+
+int opevo_op_sizes(const opevo_op *op, int64_t *a_elems, int64_t *b_elems, int64_t *c_elems)
+{
+    if (!op) return fail(OPEVO_E_ARG, "op_sizes: NULL argument");
+    if (a_elems) *a_elems = op->a_elems();
+    if (b_elems) *b_elems = op->b_elems();
+    if (c_elems) *c_elems = op->c_elems();
+    return OPEVO_OK;
+}
+
+int opevo_op_space(const opevo_op *op, int variant, opevo_space **out)
+{
+    if (!op || !out) return fail(OPEVO_E_ARG, "op_space: NULL argument");
+    std::vector<opevo_param_desc> descs;
+    if (int rc = op_param_descs(*op, variant, descs)) return rc;
+    return opevo_space_create(descs.data(), int(descs.size()), out);
+}
+
+int opevo_kernel_plan(const opevo_op *op, int variant, const int32_t *cfg, opevo_plan *plan)
+{
+    if (!op || !cfg || !plan) return fail(OPEVO_E_ARG, "kernel_plan: NULL argument");
+    Decoded d;
+    if (int rc = decode(*op, variant, cfg, d)) return rc;
+    *plan = d.plan;
+    return OPEVO_OK;
+}
+
+int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg, char *buf, size_t cap)
+{
+    if (!op || !cfg || !buf) return fail(OPEVO_E_ARG, "kernel_defines: NULL argument");
+    Decoded d;
+    if (int rc = decode(*op, variant, cfg, d)) return rc;
+    const std::string s = d.tmpl + ": " + d.defines;
+    if (s.size() + 1 > cap) return fail(OPEVO_E_ARG, "kernel_defines: buffer too small (%zu needed)", s.size() + 1);
+    std::memcpy(buf, s.c_str(), s.size() + 1);
+    return OPEVO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Shared prologue of the kernel templates: operator geometry.
+//
+// Every name in capitals is a compile-time constant supplied per configuration as a -D
+// option by the host (see the plan/define renderer): the kernels contain no run-time
+// shape arguments, so each configuration is its own specialised program (Sec. 1: "compile
+// a device code with a specific configuration and run it on real hardware").
+//
+// All three operators are run as one batched GEMM view  C[b][m][n] = sum_k A[b][m][k] B[b][k][n]:
+//   OP 0  MatMul       (App. B.1)  batch = 1
+//   OP 1  BatchMatMul  (App. B.2)  grid z = batch / BATCH_INNER, BATCH_INNER batches per workgroup
+//   OP 2  Conv2d       (App. B.3, Eq. 5 with stride and padding) as an implicit GEMM:
+//         m = output channel, k = (ci, r, s) flattened as the OIHW kernel tensor stores it,
+//         n = output pixel (image, y, x); B[k][n] is gathered from the NCHW image on the fly
+//         and is zero where the tap falls outside the image.
+//
+// Workgroup (bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z) owns rows [by*BM, +BM) and
+// columns "bx-th block of BN columns".  For conv a block of columns is a box of
+// NB2 images x BH rows x BW pixels; column c of the block is image c/(BH*BW), row (c/BW)%BH,
+// pixel c%BW of that box.
+
+#define OP_MATMUL 0
+#define OP_BMM 1
+#define OP_CONV 2
+
+typedef unsigned short u16;
+typedef unsigned int u32;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+#if IN_DTYPE == 0
+typedef float in_t;
+__device__ __forceinline__ float to_f32(in_t x) { return x; }
+#elif IN_DTYPE == 1
+typedef u16 in_t;   // bf16 bits
+__device__ __forceinline__ float to_f32(in_t x) { return __builtin_bit_cast(float, (u32)x << 16); }
+#else
+typedef u16 in_t;   // fp16 bits
+__device__ __forceinline__ float to_f32(in_t x) { return (float)__builtin_bit_cast(_Float16, x); }
+#endif
+
+#if OP == OP_CONV
+struct ColBlock { int nb0, y0, x0; };
+__device__ __forceinline__ ColBlock col_block(int bx)
+{
+    ColBlock cb;
+    cb.x0 = (bx % W1) * BW;
+    cb.y0 = ((bx / W1) % H1) * BH;
+    cb.nb0 = (bx / (W1 * H1)) * NB2;
+    return cb;
+}
+// B[k][c] of the implicit GEMM: image value under tap k for column c of the block.
+__device__ __forceinline__ in_t conv_b(const in_t *__restrict__ img, const ColBlock &cb, int k, int c)
+{
+    const int ci = k / (HK * WK), r = (k / WK) % HK, s = k % WK;
+    const int nb = cb.nb0 + c / (BH * BW);
+    const int y = (cb.y0 + (c / BW) % BH) * STRIDE + r - PAD_CONV;
+    const int x = (cb.x0 + c % BW) * STRIDE + s - PAD_CONV;
+    if (y < 0 || y >= HIN || x < 0 || x >= WIN) return (in_t)0;
+    return img[(((long)nb * CIN + ci) * HIN + y) * WIN + x];
+}
+__device__ __forceinline__ long conv_c_index(const ColBlock &cb, int m, int c)
+{
+    const int nb = cb.nb0 + c / (BH * BW);
+    const int y = cb.y0 + (c / BW) % BH;
+    const int x = cb.x0 + c % BW;
+    return (((long)nb * M + m) * HOUT + y) * WOUT + x;
+}
+#endif

@@ -1,0 +1,285 @@
+// MFMA kernel template (bf16 / fp16 inputs, fp32 accumulation) for gfx950.
+//
+// Roles of the tiling factors of one output axis (outermost first):
+//   f1 workgroups along the axis (grid), f2 waves of the workgroup along the axis,
+//   f3 basic tiles per wave, f4 basic tile.  Workgroup tile BM x BN = (f2 f3 f4 of M) x
+//   (f2 f3 f4 of N); WM x WN waves, each owning a TM x TN = (f3 f4) x (f3 f4) tile made of
+//   ATOM x ATOM MFMA atoms (32x32x16 or 16x16x32); a basic tile of FMI x FNI atoms is computed
+//   as an outer product of FMI A-fragments and FNI B-fragments held in registers.
+//   The reduction axis is split in KSTEPS slabs of BK, each staged in LDS.
+//
+// LDS layout (16-bit elements): As[stage][BM][BK+PAD] and Bs[stage][BN][BK+PAD], both with
+// the reduction index contiguous, which is the order an MFMA lane wants its 8 operand values
+// in.  A rows arrive that way from global memory; B arrives with n contiguous, so each
+// thread loads an 8(k) x 8(n) block, transposes it in registers and writes 8 rows of 16 B.
+//
+// FLAG = 1: two LDS stages; the global loads of slab kt+1 are issued before the MFMAs of
+//           slab kt and written to the other stage afterwards (one barrier per slab); the
+//           MFMA K loop is fully unrolled.
+// FLAG = 0: one stage, load -> barrier -> compute -> barrier; K loop not unrolled.
+// BMM only, STAGE_LDS = 0: no LDS at all, fragments are read straight from global memory.
+
+#if IN_DTYPE == 1
+typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
+#define MFMA_32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#define MFMA_16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0)
+#else
+typedef __attribute__((ext_vector_type(8))) _Float16 frag_t;
+#define MFMA_32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+#define MFMA_16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0)
+#endif
+
+#if ATOM == 32
+typedef f32x16 acc_t;
+#define KA 16
+#define MFMA(a, b, c) MFMA_32(a, b, c)
+#else
+typedef f32x4 acc_t;
+#define KA 32
+#define MFMA(a, b, c) MFMA_16(a, b, c)
+#endif
+
+constexpr int MI = TM / ATOM, NI = TN / ATOM;                 // atoms per wave tile
+constexpr int FMI = (FM % ATOM == 0) ? FM / ATOM : 1;         // atoms per basic tile
+constexpr int FNI = (FN % ATOM == 0) ? FN / ATOM : 1;
+constexpr int LDA = BK + PAD, LDB = BK + PAD;
+constexpr int A_STAGE = BM * LDA, B_STAGE = BN * LDB;
+constexpr int A_CHUNKS = BM * (BK / 8);                       // 16-byte pieces of the A slab
+constexpr int NA = (A_CHUNKS + NT - 1) / NT;
+#if OP == OP_CONV
+constexpr int B_CHUNKS = BN * (BK / 8);                       // (column, 8 taps) gathers
+#else
+constexpr int B_CHUNKS = (BK / 8) * (BN / 8);                 // 8x8 blocks of the B slab
+#endif
+constexpr int NB = (B_CHUNKS + NT - 1) / NT;
+
+struct Slab {
+    u32x4 a[NA];
+#if OP == OP_CONV
+    u32x4 b[NB];
+#else
+    u32x4 b[NB][8];
+#endif
+};
+
+__device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, const u16 *__restrict__ Bb,
+                                          int m0, int k0, int tid
+#if OP == OP_CONV
+                                          , const ColBlock &cb
+#else
+                                          , int n0
+#endif
+)
+{
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int q = tid + i * NT;
+        if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
+            const int row = q / (BK / 8), kc = q % (BK / 8);
+            s.a[i] = *(const u32x4 *)(Ab + (long)(m0 + row) * K + k0 + kc * 8);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int q = tid + i * NT;
+        if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
+#if OP == OP_CONV
+            const int c = q % BN, kc = q / BN;
+            u32 h[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) h[t] = conv_b(Bb, cb, k0 + kc * 8 + t, c);
+            u32x4 v;
+            v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
+            v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            s.b[i] = v;
+#else
+            const int kb = q / (BN / 8), nb = q % (BN / 8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                s.b[i][j] = *(const u32x4 *)(Bb + (long)(k0 + kb * 8 + j) * N + n0 + nb * 8);
+#endif
+        }
+    }
+}
+
+__device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int q = tid + i * NT;
+        if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
+            const int row = q / (BK / 8), kc = q % (BK / 8);
+            *(u32x4 *)(As + row * LDA + kc * 8) = s.a[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int q = tid + i * NT;
+        if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
+#if OP == OP_CONV
+            const int c = q % BN, kc = q / BN;
+            *(u32x4 *)(Bs + c * LDB + kc * 8) = s.b[i];
+#else
+            const int kb = q / (BN / 8), nb = q % (BN / 8);
+            // 8x8 transpose: row j of the block is k = kb*8+j holding n = nb*8 .. +7
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                u32x4 o;
+                const int d = c / 2;
+                if (c % 2 == 0) {
+                    o.x = (s.b[i][0][d] & 0xffffu) | (s.b[i][1][d] << 16);
+                    o.y = (s.b[i][2][d] & 0xffffu) | (s.b[i][3][d] << 16);
+                    o.z = (s.b[i][4][d] & 0xffffu) | (s.b[i][5][d] << 16);
+                    o.w = (s.b[i][6][d] & 0xffffu) | (s.b[i][7][d] << 16);
+                } else {
+                    o.x = (s.b[i][0][d] >> 16) | (s.b[i][1][d] & 0xffff0000u);
+                    o.y = (s.b[i][2][d] >> 16) | (s.b[i][3][d] & 0xffff0000u);
+                    o.z = (s.b[i][4][d] >> 16) | (s.b[i][5][d] & 0xffff0000u);
+                    o.w = (s.b[i][6][d] >> 16) | (s.b[i][7][d] & 0xffff0000u);
+                }
+                *(u32x4 *)(Bs + (nb * 8 + c) * LDB + kb * 8) = o;
+            }
+#endif
+        }
+    }
+}
+
+// MFMAs of one LDS-resident slab.  Lane l of a wave supplies, for atom row/column l % ATOM,
+// the 8 reduction values starting at 8*(l / ATOM) of each KA-wide step.
+__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *Bs,
+                                             int a_row0, int b_row0, int lk)
+{
+#if FLAG
+#pragma unroll
+#else
+#pragma unroll 1
+#endif
+    for (int kk = 0; kk < BK / KA; ++kk) {
+#pragma unroll
+        for (int i0 = 0; i0 < MI; i0 += FMI) {
+#pragma unroll
+            for (int j0 = 0; j0 < NI; j0 += FNI) {
+                frag_t af[FMI], bf[FNI];
+#pragma unroll
+                for (int i = 0; i < FMI; ++i)
+                    af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + (a_row0 + (i0 + i) * ATOM) * LDA + kk * KA + lk));
+#pragma unroll
+                for (int j = 0; j < FNI; ++j)
+                    bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(Bs + (b_row0 + (j0 + j) * ATOM) * LDB + kk * KA + lk));
+#pragma unroll
+                for (int i = 0; i < FMI; ++i)
+#pragma unroll
+                    for (int j = 0; j < FNI; ++j)
+                        acc[i0 + i][j0 + j] = MFMA(af[i], bf[j], acc[i0 + i][j0 + j]);
+            }
+        }
+    }
+}
+
+extern "C" __global__ __launch_bounds__(NT)
+void opevo_kernel(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
+                  unsigned long long *ctl /* deadline control, used by the scalar template only */)
+{
+    extern __shared__ __attribute__((aligned(16))) u16 smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane % ATOM, lk = (lane / ATOM) * 8;
+    const int m0 = blockIdx.y * BM;
+#if OP == OP_CONV
+    const ColBlock cb = col_block(blockIdx.x);
+#else
+    const int n0 = blockIdx.x * BN;
+#endif
+
+    for (int bi = 0; bi < BATCH_INNER; ++bi) {
+#if OP == OP_CONV
+        const u16 *Ab = A, *Bb = B;
+#else
+        const long batch = (long)blockIdx.z * BATCH_INNER + bi;
+        const u16 *Ab = A + batch * M * K;
+        const u16 *Bb = B + batch * K * N;
+        float *Cb = C + batch * M * N;
+#endif
+        acc_t acc[MI][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < (ATOM == 32 ? 16 : 4); ++r) acc[i][j][r] = 0.f;
+
+#if STAGE_LDS
+        u16 *As = smem, *Bs = smem + NSTAGE * A_STAGE;
+        Slab slab;
+#if OP == OP_CONV
+#define LOAD_SLAB(kt) load_slab(slab, Ab, Bb, m0, (kt) * BK, tid, cb)
+#else
+#define LOAD_SLAB(kt) load_slab(slab, Ab, Bb, m0, (kt) * BK, tid, n0)
+#endif
+#if FLAG
+        if (bi > 0) __syncthreads();
+        LOAD_SLAB(0);
+        store_slab(slab, As, Bs, tid);
+        __syncthreads();
+        for (int kt = 0; kt < KSTEPS; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < KSTEPS) LOAD_SLAB(kt + 1);
+            compute_slab(acc, As + cur * A_STAGE, Bs + cur * B_STAGE, wm * TM + lrow, wn * TN + lrow, lk);
+            if (kt + 1 < KSTEPS) store_slab(slab, As + (cur ^ 1) * A_STAGE, Bs + (cur ^ 1) * B_STAGE, tid);
+            __syncthreads();
+        }
+#else
+        for (int kt = 0; kt < KSTEPS; ++kt) {
+            LOAD_SLAB(kt);
+            __syncthreads();
+            store_slab(slab, As, Bs, tid);
+            __syncthreads();
+            compute_slab(acc, As, Bs, wm * TM + lrow, wn * TN + lrow, lk);
+        }
+        __syncthreads();
+#endif
+#else  // no LDS staging (BMM, STAGE_LDS = 0): fragments straight from global memory
+        for (int k0 = 0; k0 < K; k0 += KA) {
+            frag_t af[MI], bf[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(Ab + (long)(m0 + wm * TM + i * ATOM + lrow) * K + k0 + lk));
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const u16 *p = Bb + (long)(k0 + lk) * N + n0 + wn * TN + j * ATOM + lrow;
+                u32x4 v;
+                v.x = (u32)p[0] | ((u32)p[(long)N] << 16);
+                v.y = (u32)p[2L * N] | ((u32)p[3L * N] << 16);
+                v.z = (u32)p[4L * N] | ((u32)p[5L * N] << 16);
+                v.w = (u32)p[6L * N] | ((u32)p[7L * N] << 16);
+                bf[j] = __builtin_bit_cast(frag_t, v);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[i], bf[j], acc[i][j]);
+        }
+#endif
+
+        // Epilogue.  An atom's result sits with column (l % ATOM) in lane l; 32x32: register r
+        // is row 8*(r/4) + 4*(l/32) + r%4; 16x16: register r is row 4*(l/16) + r.
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+#pragma unroll
+                for (int r = 0; r < (ATOM == 32 ? 16 : 4); ++r) {
+                    const int row = (ATOM == 32) ? 8 * (r / 4) + 4 * (lane / 32) + r % 4 : 4 * (lane / 16) + r;
+                    const int gm = m0 + wm * TM + i * ATOM + row;
+                    const int cn = wn * TN + j * ATOM + lrow;   // column inside the workgroup tile
+#if OP == OP_CONV
+                    C[conv_c_index(cb, gm, cn)] = acc[i][j][r];
+#else
+                    Cb[(long)gm * N + n0 + cn] = acc[i][j][r];
+#endif
+                }
+            }
+        }
+    }
+}

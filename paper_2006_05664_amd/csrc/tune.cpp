@@ -1,0 +1,154 @@
+// A whole tuning run on the GPU (Alg. 1): ask -> instantiate the generation concurrently on
+// host threads -> time each child on the one GPU -> parity gate -> tell.
+#include <atomic>
+#include <chrono>
+#include <cmath>
+#include <condition_variable>
+#include <cstring>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "kernel.hpp"
+#include "tuner.hpp"
+
+using namespace opevo;
+
+namespace {
+
+struct Child {
+    opevo_kernel *kernel = nullptr;
+    int status = OPEVO_OK;
+    double compile_ms = 0.0;
+    std::string error;
+    bool done = false;
+};
+
+double seconds_since(std::chrono::steady_clock::time_point t0)
+{
+    return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+}
+
+}  // namespace
+
+extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args *args,
+                          int32_t *best_cfg_out, opevo_tune_result *result)
+{
+    if (!op || !args || !result) return fail(OPEVO_E_ARG, "tune: NULL argument");
+    if (!args->a || !args->b || !args->c) return fail(OPEVO_E_ARG, "tune: device pointers a, b, c are required");
+    if (args->trials < 1 || args->lambda < 1 || args->rho < 1 || args->samples < 1 || args->warmup < 0)
+        return fail(OPEVO_E_ARG, "tune: trials, lambda, rho, samples must be >= 1");
+    std::memset(result, 0, sizeof *result);
+    result->best_trial = -1;
+
+    opevo_space *space = nullptr;
+    if (int rc = opevo_op_space(op, variant, &space)) return rc;
+    opevo_tuner *tuner = nullptr;
+    if (int rc = opevo_tuner_create(space, args->lambda, args->rho, args->q, args->seed, &tuner)) {
+        opevo_space_destroy(space);
+        return rc;
+    }
+    const int w = space->width;
+    const int gen_cap = std::max(args->lambda, args->rho);
+    const int n_threads = std::max(1, args->compile_threads);
+    hipStream_t stream = static_cast<hipStream_t>(args->stream);
+    const auto t_start = std::chrono::steady_clock::now();
+    std::vector<int32_t> cfgs(size_t(gen_cap) * w);
+    std::vector<double> fit(gen_cap);
+    int done = 0, rc_final = OPEVO_OK;
+    double best = 0.0;
+
+    while (done < args->trials) {
+        const int n = tuner->ask(cfgs.data(), args->trials - done);
+        if (n == 0) break;   // space exhausted
+
+        // ---- instantiate the children concurrently (host threads), consume them in order
+        std::vector<Child> kids(n);
+        std::mutex mu;
+        std::condition_variable cv;
+        std::atomic<int> next(0);
+        const auto t_compile = std::chrono::steady_clock::now();
+        auto worker = [&]() {
+            for (;;) {
+                const int i = next.fetch_add(1);
+                if (i >= n) return;
+                Child c;
+                c.status = build_kernel(*op, variant, cfgs.data() + size_t(i) * w, &c.kernel, &c.compile_ms);
+                if (c.status != OPEVO_OK) c.error = last_error();
+                c.done = true;
+                {
+                    std::lock_guard<std::mutex> lock(mu);
+                    kids[i] = std::move(c);
+                }
+                cv.notify_all();
+            }
+        };
+        std::vector<std::thread> pool;
+        for (int t = 0; t < std::min(n_threads, n); ++t) pool.emplace_back(worker);
+
+        for (int i = 0; i < n; ++i) {
+            {
+                std::unique_lock<std::mutex> lock(mu);
+                cv.wait(lock, [&] { return kids[i].done; });
+            }
+            Child &c = kids[i];
+            double tflops = 0.0, ms = 0.0;
+            int status = c.status;
+            if (status == OPEVO_OK && rc_final == OPEVO_OK) {
+                const auto t_run = std::chrono::steady_clock::now();
+                status = time_kernel(c.kernel, args->a, args->b, args->c, stream, args->warmup,
+                                     args->launches_per_sample, args->samples, args->trial_timeout_ms, &ms, nullptr);
+                if (status == OPEVO_OK && args->ref) {
+                    double mx = 0.0, fro = 0.0;
+                    status = compare_f32(static_cast<const float *>(args->c), args->ref, op->c_elems(), stream, &mx, &fro);
+                    if (status == OPEVO_OK && !(mx <= args->tol_max_scaled && fro <= args->tol_rel_fro)) {
+                        status = OPEVO_E_PARITY;
+                        set_error("parity: max scaled error %.3g, relative Frobenius error %.3g [%s]", mx, fro,
+                                  c.kernel->defines.c_str());
+                    }
+                }
+                result->run_s += seconds_since(t_run);
+                if (status == OPEVO_OK && ms > 0.0) tflops = op->flops() / (ms * 1e-3) * 1e-12;
+                if (status == OPEVO_E_HIP) {
+                    // a failed launch is a property of the configuration; a dead device is not
+                    (void)hipGetLastError();
+                    if (hipStreamSynchronize(stream) != hipSuccess) rc_final = OPEVO_E_HIP;
+                    else status = OPEVO_E_INVALID;
+                }
+            }
+            if (status == OPEVO_E_INVALID) result->n_invalid++;
+            else if (status == OPEVO_E_HIPRTC) result->n_compile_fail++;
+            else if (status == OPEVO_E_PARITY) result->n_parity_fail++;
+            fit[i] = tflops;
+            const int t = done + i;
+            if (args->cfg_log) std::memcpy(args->cfg_log + size_t(t) * w, cfgs.data() + size_t(i) * w, sizeof(int32_t) * w);
+            if (args->fitness_log) args->fitness_log[t] = tflops;
+            if (args->status_log) args->status_log[t] = status;
+            if (args->compile_ms_log) args->compile_ms_log[t] = c.compile_ms;
+            if (args->run_ms_log) args->run_ms_log[t] = ms;
+            if (args->wall_s_log) args->wall_s_log[t] = seconds_since(t_start);
+            if (tflops > best) {
+                best = tflops;
+                result->best_trial = t;
+                result->best_tflops = tflops;
+                result->best_ms = ms;
+                if (best_cfg_out) std::memcpy(best_cfg_out, cfgs.data() + size_t(i) * w, sizeof(int32_t) * w);
+            }
+            opevo_kernel_destroy(c.kernel);
+            c.kernel = nullptr;
+        }
+        for (auto &th : pool) th.join();
+        result->compile_s += seconds_since(t_compile);
+        if (rc_final != OPEVO_OK) break;
+        tuner->tell(cfgs.data(), fit.data(), n);
+        done += n;
+    }
+    // compile_s was measured around the whole generation; what is left after the GPU share
+    result->compile_s = std::max(0.0, result->compile_s - result->run_s);
+    result->n_trials = done;
+    result->wall_s = seconds_since(t_start);
+    opevo_tuner_destroy(tuner);
+    opevo_space_destroy(space);
+    if (rc_final != OPEVO_OK) return fail(rc_final, "tune: the device stopped responding after a failed launch");
+    return OPEVO_OK;
+}

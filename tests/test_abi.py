@@ -1,0 +1,35 @@
+"""The C-ABI library loads and exports every symbol include/opevo.h declares (no GPU)."""
+import ctypes
+import os
+import re
+
+import paper_2006_05664_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "opevo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(opevo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    names = _declared()
+    assert len(names) >= 45
+    lib = ctypes.CDLL(P.binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "library does not export " + n
+        assert callable(getattr(P, n, None)), "binding lacks " + n
+    assert sorted(P.binding.EXPORTED) == names
+
+
+def test_status_names_and_error_text():
+    assert P.opevo_status_name(0) == "OK" and P.opevo_status_name(-3) == "E_INVALID"
+    try:
+        P.opevo_op_create(99, (1, 1, 1), P.OPEVO_BF16)
+    except P.OpevoError as e:
+        assert e.status == P.OPEVO_E_ARG and "kind" in e.message
+    else:
+        raise AssertionError("bad operator kind accepted")
+    assert "opevo" in P.opevo_version()

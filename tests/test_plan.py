@@ -1,0 +1,125 @@
+"""Configuration decoder: legality, validity, launch geometry, and that representative
+members of every template family compile for gfx950 through hipRTC (no GPU needed)."""
+import numpy as np
+import pytest
+
+import paper_2006_05664_amd as P
+
+MM1 = (P.OPEVO_MATMUL, (512, 1024, 1024))
+MM8K = (P.OPEVO_MATMUL, (8192, 8192, 8192))
+BMM = (P.OPEVO_BMM, (128, 128, 128, 64))
+CONV56 = (P.OPEVO_CONV2D, (1, 64, 56, 56, 64, 3, 3, 1, 1))
+CONV14 = (P.OPEVO_CONV2D, (32, 256, 14, 14, 256, 3, 3, 1, 1))
+
+
+def _op(kd, dtype=P.OPEVO_BF16):
+    return P.opevo_op_create(kd[0], kd[1], dtype)
+
+
+def test_flops_bytes_sizes():
+    op = _op(MM1)
+    assert P.opevo_op_flops(op) == 2.0 * 512 * 1024 * 1024
+    assert P.opevo_op_bytes(op) == 2 * (512 * 1024 + 1024 * 1024) + 4 * 512 * 1024 == 5242880
+    op = _op(BMM)
+    assert P.opevo_op_flops(op) == 2.0 * 128 * 128 * 128 * 64 and P.opevo_op_bytes(op) == 12582912
+    op = _op(CONV56)
+    assert P.opevo_op_flops(op) == 2.0 * 64 * 56 * 56 * 64 * 9     # padding taps counted
+    assert P.opevo_op_sizes(op) == (64 * 64 * 9, 64 * 56 * 56, 64 * 56 * 56)
+    assert P.opevo_op_bytes(op) == 1277952
+    op = _op(CONV14)
+    assert P.opevo_op_flops(op) == 2.0 * 32 * 256 * 14 * 14 * 256 * 9 and P.opevo_op_bytes(op) == 10813440
+    # App. B.3 output extents: C1 -> 55, C2 -> 27
+    assert P.opevo_op_sizes(P.opevo_op_create(P.OPEVO_CONV2D, (2, 3, 227, 227, 64, 11, 11, 4, 0), 1))[2] == 2 * 64 * 55 * 55
+    assert P.opevo_op_sizes(P.opevo_op_create(P.OPEVO_CONV2D, (2, 64, 27, 27, 192, 5, 5, 1, 2), 1))[2] == 2 * 192 * 27 * 27
+
+
+def test_illegal_configurations_are_errors_not_trials():
+    op = _op(MM1)
+    good = [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1]
+    assert P.opevo_kernel_plan(op, P.OPEVO_TILE4, good).status == P.OPEVO_OK
+    for bad in ([2, 2, 2, 32, 8, 2, 2, 32, 16, 64, 1], [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 2],
+                [0, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1], [2, 2, 2, 64, 8, 2, 2, 32, 16, 32, 1],
+                [-2, -2, 2, 64, 8, 2, 2, 32, 16, 64, 1]):
+        for call in (P.opevo_kernel_plan, P.opevo_kernel_build, P.opevo_kernel_defines):
+            with pytest.raises(P.OpevoError) as ei:
+                call(op, P.OPEVO_TILE4, bad)
+            assert ei.value.status == P.OPEVO_E_ILLEGAL
+
+
+def test_invalid_members_report_the_resource_and_build_refuses_them():
+    op = _op(MM1)
+    cases = {"threads": [1, 32, 1, 16, 1, 32, 1, 32, 16, 64, 1],       # 32*32 waves
+             "accumulators": [1, 1, 8, 64, 2, 1, 8, 64, 16, 64, 1],    # 512x512 per wave
+             "LDS": [2, 2, 2, 64, 8, 2, 2, 32, 1, 1024, 1]}            # 1024-deep slab
+    for word, cfg in cases.items():
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_E_INVALID and word in plan.reason.decode(), plan.reason
+        with pytest.raises(P.OpevoError) as ei:
+            P.opevo_kernel_build(op, P.OPEVO_TILE4, cfg)
+        assert ei.value.status == P.OPEVO_E_INVALID
+
+
+def test_two_level_space_has_no_invalid_member():
+    op = _op((P.OPEVO_MATMUL, (64, 64, 64)), P.OPEVO_F32)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE2)
+    for r in range(343):
+        cfg = P.opevo_space_unrank(sp, r)
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE2, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == 0
+        assert plan.grid[0] * plan.tile[1] == 64 and plan.grid[1] * plan.tile[0] == 64
+        assert 64 <= plan.block <= 256 and plan.block % 64 == 0 and plan.lds_bytes <= 32768
+    P.opevo_space_destroy(sp)
+
+
+@pytest.mark.parametrize("kd", [MM1, MM8K, BMM, CONV56, CONV14])
+def test_four_level_spaces_cover_the_output_once_and_are_not_mostly_invalid(kd):
+    op = _op(kd)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4)
+    rng = P.opevo_rng_create(11)
+    a, b, c = P.opevo_op_sizes(op)
+    n_valid = n_mfma = 0
+    total = 1500
+    for _ in range(total):
+        cfg = P.opevo_space_random(sp, rng)
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        binner = cfg[1] if kd[0] == P.OPEVO_BMM else 1
+        # workgroups x workgroup tile = the whole output, exactly once (App. B.1 roles of the factors)
+        assert plan.grid[0] * plan.grid[1] * plan.grid[2] * binner * plan.tile[0] * plan.tile[1] == c
+        assert plan.block % 64 == 0
+        if plan.status == P.OPEVO_OK:
+            n_valid += 1
+            n_mfma += plan.path != 0
+            assert plan.block <= 1024 and plan.lds_bytes <= 160 * 1024 and plan.acc_per_lane <= 256
+            if plan.path:
+                atom = 32 if plan.path == 1 else 16
+                assert plan.wave_tile[0] % atom == 0 and plan.wave_tile[1] % atom == 0
+        else:
+            assert plan.reason
+    assert n_valid > 0.04 * total, "space almost entirely invalid: Eq. 2 would have nothing to select"
+    assert n_mfma > 0.005 * total
+    P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+
+
+COMPILE_CASES = [
+    ("scalar f32 two-level", (P.OPEVO_MATMUL, (64, 64, 64)), P.OPEVO_F32, P.OPEVO_TILE2, [8, 8, 4, 16, 2, 32], 0),
+    ("mfma 32x32 double-buffered", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1], 1),
+    ("mfma 16x16 single stage", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 0], 2),
+    ("mfma fp16", MM1, P.OPEVO_F16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 32, 32, 1], 1),
+    ("scalar fallback bf16", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1], 0),
+    ("bmm lds", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1], 1),
+    ("bmm direct", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0], 1),
+    ("conv mfma", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1], 2),
+    ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
+    ("conv batch mfma", CONV14, P.OPEVO_BF16, P.OPEVO_TILE4, [8, 4, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 36, 64, 1], 2),
+]
+
+
+@pytest.mark.parametrize("label,kd,dtype,variant,cfg,path", COMPILE_CASES, ids=[c[0] for c in COMPILE_CASES])
+def test_templates_compile_for_gfx950(label, kd, dtype, variant, cfg, path):
+    op = _op(kd, dtype)
+    plan = P.opevo_kernel_plan(op, variant, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, ms = P.opevo_kernel_build(op, variant, cfg)
+    assert P.opevo_kernel_code_size(kernel) > 1000 and ms > 0
+    assert "-DBM=%d" % plan.tile[0] in P.opevo_kernel_defines(op, variant, cfg)
+    P.opevo_kernel_destroy(kernel)

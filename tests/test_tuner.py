@@ -1,0 +1,120 @@
+"""The library's OpEvo loop (Alg. 1) against the oracle: same seed and same fitness replies
+must give the same trajectory, configuration for configuration (CPU)."""
+import math
+
+import numpy as np
+import pytest
+
+import paper_2006_05664_amd as P
+from oracle import search as S
+
+
+def _fitness(target):
+    def f(flat):
+        d = sum((math.log2(a + 1) - math.log2(b + 1)) ** 2 for a, b in zip(flat, target))
+        return 100.0 / (1.0 + d)
+    return f
+
+
+CASES = [
+    # (library descriptors, oracle params, target, lambda, rho, q, budget)
+    ([dict(type=P.OPEVO_FACTOR, C=64, nu=2)] * 3, [S.Factor(64, 2)] * 3, (8, 8, 4, 16, 2, 32), 8, 8, 0.5, 1000),
+    ([dict(type=P.OPEVO_FACTOR, C=512, nu=4), dict(type=P.OPEVO_FACTOR, C=1024, nu=4),
+      dict(type=P.OPEVO_FACTOR, C=1024, nu=2), dict(type=P.OPEVO_CATEGORICAL, n_values=2)],
+     [S.Factor(512, 4), S.Factor(1024, 4), S.Factor(1024, 2), S.Categorical(2)],
+     (2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1), 8, 8, 0.5, 500),
+    ([dict(type=P.OPEVO_FACTOR, C=56, nu=4), dict(type=P.OPEVO_PERMUTATION, n_values=3),
+      dict(type=P.OPEVO_DISCRETE, values=[1, 2, 4, 8])],
+     [S.Factor(56, 4), S.Permutation(3), S.Discrete([1, 2, 4, 8])], (7, 2, 2, 2, 2, 0, 1, 3), 3, 5, 0.7, 300),
+    ([dict(type=P.OPEVO_CATEGORICAL, n_values=3), dict(type=P.OPEVO_FACTOR, C=4, nu=2)],
+     [S.Categorical(3), S.Factor(4, 2)], (1, 2, 2), 4, 4, 0.3, 100),
+]
+
+
+@pytest.mark.parametrize("descs,oparams,target,lam,rho,q,budget", CASES)
+@pytest.mark.parametrize("seed", [0, 7])
+def test_trajectory_equals_oracle(descs, oparams, target, lam, rho, q, budget, seed):
+    f = _fitness(target)
+    osp = S.Space(oparams)
+    want = S.run_opevo(osp, lambda x: f(osp.flat(x)), budget, lam, rho, q, seed)
+    sp = P.opevo_space_create(descs)
+    tuner = P.opevo_tuner_create(sp, lam, rho, q, seed)
+    got = []
+    while len(got) < budget:
+        xs = P.opevo_tuner_ask(tuner, budget - len(got))
+        if len(xs) == 0:
+            break
+        fit = [f(list(x)) for x in xs]
+        P.opevo_tuner_tell(tuner, xs, fit)
+        got += [(tuple(int(a) for a in x), fx) for x, fx in zip(xs, fit)]
+    assert len(got) == len(want)
+    assert got == [(tuple(osp.flat(x)), fx) for x, fx in want]
+    assert len({x for x, _ in got}) == len(got)                      # never sampled twice (Sec. 4.4)
+    assert all(P.opevo_space_is_legal(sp, x) for x, _ in got)
+    if osp.size() <= budget:
+        assert len(got) == osp.size() and len(P.opevo_tuner_ask(tuner)) == 0   # exhausted
+    cfg, best, trial = P.opevo_tuner_best(tuner)
+    fits = [fx for _, fx in got]
+    assert best == max(fits) and trial == fits.index(max(fits)) and tuple(cfg) == got[trial][0]
+    hc, hf = P.opevo_tuner_history(tuner)
+    assert [tuple(r) for r in hc] == [x for x, _ in got] and list(hf) == fits
+    assert P.opevo_tuner_num_trials(tuner) == len(got)
+    P.opevo_tuner_destroy(tuner); P.opevo_space_destroy(sp)
+
+
+def test_zero_and_bad_fitness_trajectory_equals_oracle():
+    descs, oparams = CASES[0][0], CASES[0][1]
+    osp = S.Space(oparams)
+    replies = lambda flat: [0.0, float("nan"), -3.0, 0.0, 2.5][sum(flat) % 5]
+    want = S.run_opevo(osp, lambda x: replies(osp.flat(x)), 120, 8, 8, 0.5, 3)
+    sp = P.opevo_space_create(descs)
+    tuner = P.opevo_tuner_create(sp, 8, 8, 0.5, 3)
+    got = []
+    while len(got) < 120:
+        xs = P.opevo_tuner_ask(tuner, 120 - len(got))
+        P.opevo_tuner_tell(tuner, xs, [replies(list(x)) for x in xs])
+        got += [tuple(int(a) for a in x) for x in xs]
+    assert got == [tuple(osp.flat(x)) for x, _ in want]
+    _, hf = P.opevo_tuner_history(tuner)
+    assert list(hf) == [fx for _, fx in want] and min(hf) == 0.0   # clamped at 0, NaN -> 0
+    P.opevo_tuner_destroy(tuner); P.opevo_space_destroy(sp)
+
+
+def test_recombine_equals_oracle_and_eq2_frequencies():
+    descs = [dict(type=P.OPEVO_CATEGORICAL, n_values=3), dict(type=P.OPEVO_CATEGORICAL, n_values=3)]
+    sp = P.opevo_space_create(descs)
+    osp = S.Space([S.Categorical(3), S.Categorical(3)])
+    parents = np.array([[0, 0], [1, 1], [2, 2]], dtype=np.int32)
+    for fit in ([3.0, 1.0, 0.0], [0.0, 0.0, 0.0], [1e-300, 5.0, 1.0]):
+        rng, orng = P.opevo_rng_create(9), S.SplitMix64(9)
+        opar = [(osp.unflat(list(p)), f) for p, f in zip(parents, fit)]
+        counts = np.zeros(3)
+        for _ in range(4000):
+            c = P.opevo_recombine(sp, parents, fit, rng)
+            assert list(c) == osp.flat(S.recombine(osp, opar, orng))
+            counts[c[0]] += 1
+        probs = np.array(S.recombine_probs(fit))      # Eq. 2
+        assert np.all(np.abs(counts / 4000 - probs) < 0.03)
+        P.opevo_rng_destroy(rng)
+    P.opevo_space_destroy(sp)
+
+
+def test_tuner_error_paths():
+    sp = P.opevo_space_create([dict(type=P.OPEVO_FACTOR, C=8, nu=3)])
+    for args in ((0, 8, 0.5), (8, 0, 0.5), (8, 8, 1.0), (8, 8, -0.5)):
+        with pytest.raises(P.OpevoError) as ei:
+            P.opevo_tuner_create(sp, args[0], args[1], args[2], 0)
+        assert ei.value.status == P.OPEVO_E_ARG
+    t = P.opevo_tuner_create(sp, 2, 2, 0.5, 0)
+    with pytest.raises(P.OpevoError) as ei:
+        P.opevo_tuner_best(t)
+    assert ei.value.status == P.OPEVO_E_STATE
+    xs = P.opevo_tuner_ask(t)
+    with pytest.raises(P.OpevoError) as ei:
+        P.opevo_tuner_ask(t)                 # asked again before telling the first generation
+    assert ei.value.status == P.OPEVO_E_STATE
+    with pytest.raises(P.OpevoError) as ei:
+        P.opevo_tuner_tell(t, [[3, 1, 1]], [1.0])
+    assert ei.value.status == P.OPEVO_E_ILLEGAL
+    P.opevo_tuner_tell(t, xs, [1.0] * len(xs))
+    P.opevo_tuner_destroy(t); P.opevo_space_destroy(sp)
