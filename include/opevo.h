@@ -205,6 +205,14 @@ int opevo_kernel_plan(const opevo_op *op, int variant, const int32_t *cfg, opevo
 /* The hipRTC option string ("-DBM=.. ...") and template name the configuration renders to. */
 int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg,
                          char *buf, size_t cap);
+/* hipRTC serialises compilations inside one process, so concurrent instantiation (the paper
+ * compiles on 8 CPU threads, Sec. 6) runs on worker processes forked from the caller.  Start
+ * the pool early, ideally before the process first touches the GPU; workers keep no device
+ * file open and only run hipRTC.  Idempotent; *n_running (may be NULL) = workers alive.
+ * Without a pool every instantiation compiles in the calling process. */
+int opevo_compile_pool_start(int n_workers, int *n_running);
+int opevo_compile_pool_stop(void);
+
 /* Instantiate: render + hipRTC-compile for gfx950 (works without a GPU).  Returns
  * OPEVO_E_INVALID for an invalid configuration (no kernel), OPEVO_E_HIPRTC on a compile
  * failure.  The module is loaded on the first launch. */

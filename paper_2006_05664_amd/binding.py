@@ -66,7 +66,7 @@ class opevo_tune_result(C.Structure):
 
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError("%s is missing: build it with `python -m paper_2006_05664_amd.build`" % LIB_PATH)
+        raise ImportError("%s is missing: build it with `python paper_2006_05664_amd/build.py`" % LIB_PATH)
     return C.CDLL(LIB_PATH)
 
 
@@ -110,6 +110,8 @@ _SIGNATURES = {
     "opevo_op_bytes": [_vp, _f64p],
     "opevo_op_sizes": [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
     "opevo_op_space": [_vp, C.c_int, C.POINTER(_vp)],
+    "opevo_compile_pool_start": [C.c_int, C.POINTER(C.c_int)],
+    "opevo_compile_pool_stop": [],
     "opevo_kernel_plan": [_vp, C.c_int, _i32p, C.POINTER(opevo_plan)],
     "opevo_kernel_defines": [_vp, C.c_int, _i32p, C.c_char_p, C.c_size_t],
     "opevo_kernel_build": [_vp, C.c_int, _i32p, C.POINTER(_vp), _f64p],
@@ -422,6 +424,16 @@ def opevo_op_space(op, variant: int):
     h = _vp()
     _check(lib.opevo_op_space(op, variant, C.byref(h)))
     return h
+
+
+def opevo_compile_pool_start(n_workers: int) -> int:
+    n = C.c_int()
+    _check(lib.opevo_compile_pool_start(n_workers, C.byref(n)))
+    return n.value
+
+
+def opevo_compile_pool_stop() -> None:
+    _check(lib.opevo_compile_pool_stop())
 
 
 def opevo_kernel_plan(op, variant: int, cfg) -> opevo_plan:

@@ -9,7 +9,7 @@
 #include <new>
 #include <sstream>
 
-#include <hip/hiprtc.h>
+#include "pool.hpp"
 
 namespace opevo {
 
@@ -24,54 +24,18 @@ int hip_fail(hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail(e_, #call);         \
     } while (0)
 
-static std::vector<std::string> split(const std::string &s)
-{
-    std::vector<std::string> out;
-    std::istringstream is(s);
-    std::string t;
-    while (is >> t) out.push_back(t);
-    return out;
-}
-
 int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kernel **out, double *compile_ms)
 {
     Decoded d;
     if (int rc = decode(op, variant, cfg, d)) return rc;
     if (d.plan.status != OPEVO_OK) return fail(OPEVO_E_INVALID, "invalid configuration: %s", d.plan.reason);
-
-    const char *prologue = template_source("common");
-    const char *body = template_source(d.tmpl.c_str());
-    if (!prologue || !body) return fail(OPEVO_E_ARG, "template %s is not built into the library", d.tmpl.c_str());
-    const std::string src = std::string(prologue) + "\n" + body;
-
     const auto t0 = std::chrono::steady_clock::now();
-    hiprtcProgram prog;
-    hiprtcResult r = hiprtcCreateProgram(&prog, src.c_str(), (d.tmpl + ".hip").c_str(), 0, nullptr, nullptr);
-    if (r != HIPRTC_SUCCESS) return fail(OPEVO_E_HIPRTC, "hiprtcCreateProgram: %s", hiprtcGetErrorString(r));
-
-    std::vector<std::string> opts = split(d.defines);
-    opts.insert(opts.end(), {"--offload-arch=gfx950", "-O3", "-std=c++17",
-                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"});
-    std::vector<const char *> optv;
-    for (const auto &o : opts) optv.push_back(o.c_str());
-    r = hiprtcCompileProgram(prog, int(optv.size()), optv.data());
-    if (r != HIPRTC_SUCCESS) {
-        size_t n = 0;
-        hiprtcGetProgramLogSize(prog, &n);
-        std::string log(n, '\0');
-        if (n) hiprtcGetProgramLog(prog, &log[0]);
-        hiprtcDestroyProgram(&prog);
-        if (log.size() > 1500) log.resize(1500);
-        return fail(OPEVO_E_HIPRTC, "hipRTC failed for [%s]: %s\n%s", d.defines.c_str(),
-                    hiprtcGetErrorString(r), log.c_str());
-    }
-    size_t code_size = 0;
-    hiprtcGetCodeSize(prog, &code_size);
+    CompileResult r = pool_compile(d.tmpl, d.defines);
+    if (r.status != OPEVO_OK)
+        return fail(r.status, "hipRTC failed for [%s]: %s", d.defines.c_str(), r.log.c_str());
     opevo_kernel *k = new (std::nothrow) opevo_kernel;
-    if (!k) { hiprtcDestroyProgram(&prog); return fail(OPEVO_E_ARG, "out of memory"); }
-    k->code.resize(code_size);
-    hiprtcGetCode(prog, k->code.data());
-    hiprtcDestroyProgram(&prog);
+    if (!k) return fail(OPEVO_E_ARG, "out of memory");
+    k->code = std::move(r.code);
     k->plan = d.plan;
     k->flops = op.flops();
     k->tmpl = d.tmpl;
@@ -88,7 +52,7 @@ int load_kernel(opevo_kernel *k)
     HIP_TRY(hipModuleLoadData(&k->module, k->code.data()));
     hipError_t e = hipModuleGetFunction(&k->fn, k->module, "opevo_kernel");
     if (e != hipSuccess) {
-        hipModuleUnload(k->module);
+        (void)hipModuleUnload(k->module);
         k->module = nullptr; k->fn = nullptr;
         return hip_fail(e, "hipModuleGetFunction");
     }
@@ -123,7 +87,7 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
     hipEvent_t e0 = nullptr, e1 = nullptr;
     HIP_TRY(hipEventCreate(&e0));
     hipError_t e = hipEventCreate(&e1);
-    if (e != hipSuccess) { hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
     int rc = OPEVO_OK;
     std::vector<double> ms(samples, 0.0);
     // n back-to-back launches between two events on the caller's stream -> ms per launch
@@ -166,8 +130,8 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
         }
         for (int s = 0; s < samples && rc == OPEVO_OK; ++s) rc = timed(n, &ms[s]);
     } while (0);
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     if (rc) return rc;
     if (samples_ms) std::memcpy(samples_ms, ms.data(), sizeof(double) * samples);
     std::sort(ms.begin(), ms.end());

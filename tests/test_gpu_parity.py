@@ -1,0 +1,393 @@
+"""GPU parity: every kernel the library instantiates is compared, element by element, with the
+fp64 CPU oracle on the same seeded inputs (through the C ABI; needs an MI355X).
+
+Tolerances (written out here): bf16/fp16 inputs, fp32 accumulate:
+    max_i |c_i - ref_i| / (|ref_i| + 1) <= 2e-2   and   ||c - ref||_F / ||ref||_F <= 5e-3
+fp32 inputs:  both quantities <= 1e-4.
+"""
+import os
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import paper_2006_05664_amd as P
+from paper_2006_05664_amd import synth
+from oracle import tensor as T
+
+pytestmark = pytest.mark.gpu
+
+TOL16 = (2e-2, 5e-3)
+TOL32 = (1e-4, 1e-4)
+KIND = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "conv2d": P.OPEVO_CONV2D}
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _pool():
+    P.opevo_compile_pool_start(8)      # before the first GPU call of this module
+    yield
+    P.opevo_compile_pool_stop()
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def errors(c: np.ndarray, ref: np.ndarray):
+    c = c.astype(np.float64).ravel()
+    ref = ref.astype(np.float64).ravel()
+    d = np.abs(c - ref)
+    if not np.all(np.isfinite(c)):
+        return np.inf, np.inf
+    return float(np.max(d / (np.abs(ref) + 1.0))), float(np.linalg.norm(c - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+class Workload:
+    """Seeded inputs on host (rounded to the input dtype) and device, oracle result, op handle."""
+
+    def __init__(self, torch, kind, dims, dtype, seed, dist="normal", oracle=True):
+        self.torch, self.kind, self.dims, self.dtype = torch, kind, tuple(dims), dtype
+        if kind == "matmul":
+            M, N, K = dims
+            a, b = synth.matmul_inputs(M, N, K, dtype, seed, dist)
+            self.ref = T.matmul(a, b) if oracle else None
+        elif kind == "bmm":
+            B, M, N, K = dims
+            a, b = synth.bmm_inputs(B, M, N, K, dtype, seed)
+            self.ref = T.bmm(a, b) if oracle else None
+        else:
+            B, Cin, H, W, Cout, Hk, Wk, S, Pd = dims
+            img, ker = synth.conv_inputs(B, Cin, H, W, Cout, Hk, Wk, dtype, seed)
+            self.ref = T.conv2d(img, ker, S, Pd) if oracle else None
+            a, b = ker, img                      # kernel tensor first, image second
+        self.a_host, self.b_host = a, b
+        self.op = P.opevo_op_create(KIND[kind], dims, synth.DTYPE_CODE[dtype])
+        self.a = synth.to_device(a, dtype)
+        self.b = synth.to_device(b, dtype)
+        na, nb, nc = P.opevo_op_sizes(self.op)
+        assert (na, nb) == (a.size, b.size)
+        self.c = torch.empty(nc, dtype=torch.float32, device="cuda:0")
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.tol = TOL32 if dtype == "f32" else TOL16
+
+    def run(self, variant, cfg, kernel=None):
+        own = kernel is None
+        if own:
+            kernel, _ = P.opevo_kernel_build(self.op, variant, cfg)
+        self.c.fill_(float("nan"))            # a kernel that skips outputs cannot pass
+        P.opevo_kernel_launch(kernel, self.a.data_ptr(), self.b.data_ptr(), self.c.data_ptr(), self.stream)
+        self.torch.cuda.synchronize()
+        if own:
+            P.opevo_kernel_destroy(kernel)
+        return self.c.cpu().numpy()
+
+    def check(self, variant, cfg, label=""):
+        _say("  case %s %s %s cfg=%s" % (self.kind, self.dims, label, list(map(int, cfg))))
+        out = self.run(variant, cfg)
+        mx, fro = errors(out, self.ref)
+        assert mx <= self.tol[0] and fro <= self.tol[1], (label, list(cfg), mx, fro, P.opevo_kernel_defines(self.op, variant, cfg))
+        return mx, fro
+
+    def random_valid(self, variant, n, seed, want_paths=(0, 1, 2), max_acc=256):
+        """n seeded random members that the decoder calls valid, spread over the kernel paths."""
+        sp = P.opevo_op_space(self.op, variant)
+        rng = P.opevo_rng_create(seed)
+        got, per_path = [], {p: 0 for p in want_paths}
+        for _ in range(200000):
+            cfg = P.opevo_space_random(sp, rng)
+            plan = P.opevo_kernel_plan(self.op, variant, cfg)
+            if plan.status != P.OPEVO_OK or plan.path not in per_path or plan.acc_per_lane > max_acc:
+                continue
+            if per_path[plan.path] >= -(-n // len(want_paths)):
+                continue
+            per_path[plan.path] += 1
+            got.append(cfg)
+            if len(got) >= n:
+                break
+        P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+        return got
+
+    def close(self):
+        P.opevo_op_destroy(self.op)
+
+
+def _build_many(w, variant, cfgs):
+    with ThreadPoolExecutor(8) as ex:
+        return list(ex.map(lambda c: P.opevo_kernel_build(w.op, variant, c)[0], cfgs))
+
+
+# ------------------------------------------------------------------ config 1: 64^3 fp32, all 343
+def test_matmul64_f32_every_two_level_config_matches_oracle(torch_cuda):
+    w = Workload(torch_cuda, "matmul", (64, 64, 64), "f32", 1234, "uniform")
+    sp = P.opevo_op_space(w.op, P.OPEVO_TILE2)
+    cfgs = [P.opevo_space_unrank(sp, r) for r in range(343)]
+    assert len({tuple(c) for c in cfgs}) == 343
+    kernels = _build_many(w, P.OPEVO_TILE2, cfgs)
+    worst = 0.0
+    outs = []
+    for i, (cfg, k) in enumerate(zip(cfgs, kernels)):
+        if i % 49 == 0:
+            _say("  two-level config %d/343 %s" % (i, list(cfg)))
+        out = w.run(P.OPEVO_TILE2, cfg, k)
+        mx, fro = errors(out, w.ref)
+        assert mx <= TOL32[0] and fro <= TOL32[1], (list(cfg), mx, fro)
+        worst = max(worst, mx)
+        outs.append(out)
+        P.opevo_kernel_destroy(k)
+    # every legal configuration yields the same tensor (up to summation order)
+    spread = np.max(np.abs(np.stack(outs) - outs[0]))
+    assert spread <= 1e-4
+    _say("  343 configs, worst scaled error %.3g, spread %.3g" % (worst, spread))
+    P.opevo_space_destroy(sp); w.close()
+
+
+# ------------------------------------------------------------------ config 2: MatMul 512x1024x1024 bf16
+MM1_CASES = [
+    ("mfma32 double-buffered", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1]),
+    ("mfma32 single stage", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 0]),
+    ("mfma32 one atom per basic tile", [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1]),
+    ("mfma32 basic tile smaller than atom", [4, 2, 16, 4, 8, 2, 32, 2, 64, 16, 1]),
+    ("mfma32 deep slab", [8, 1, 1, 64, 16, 1, 2, 32, 4, 256, 0]),
+    ("mfma16", [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 1]),
+    ("mfma16 single stage", [32, 1, 1, 16, 64, 1, 1, 16, 8, 128, 0]),
+    ("mfma 1 wave, ragged slab share", [16, 1, 1, 32, 8, 1, 4, 32, 64, 16, 1]),
+    ("mfma 16 waves", [1, 4, 2, 64, 4, 4, 1, 64, 32, 32, 1]),
+    ("scalar fallback", [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1]),
+    ("scalar fallback thin", [512, 1, 1, 1, 1, 1, 1, 1024, 128, 8, 0]),
+    ("scalar odd K slab", [16, 2, 4, 4, 32, 2, 4, 4, 1024, 1, 1]),
+]
+
+
+def test_matmul_mm1_bf16_handpicked_and_random_configs(torch_cuda):
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
+    for label, cfg in MM1_CASES:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 24, seed=101):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_matmul_fp16_inputs(torch_cuda):
+    w = Workload(torch_cuda, "matmul", (256, 384, 512), "f16", 77)
+    for label, cfg in [("mfma32 f16", [2, 2, 2, 32, 3, 2, 1, 64, 8, 64, 1]),
+                       ("mfma16 f16", [8, 1, 1, 32, 8, 1, 3, 16, 16, 32, 0]),
+                       ("scalar f16", [32, 2, 1, 4, 48, 2, 1, 4, 32, 16, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+
+
+def test_matmul_multi_prime_axes(torch_cuda):
+    # 96 = 2^5*3, 160 = 2^5*5, 224 = 2^5*7: factor moves of several primes, ragged thread shares
+    w = Workload(torch_cuda, "matmul", (96, 160, 224), "bf16", 5)
+    for label, cfg in [("3x32 rows", [1, 1, 3, 32, 5, 1, 1, 32, 7, 32, 1]),
+                       ("atom16 with 5 and 3", [2, 3, 1, 16, 2, 5, 1, 16, 7, 32, 0]),
+                       ("scalar with odd tiles", [2, 2, 3, 8, 2, 2, 5, 8, 16, 14, 1]),
+                       ("K slab 112", [3, 1, 1, 32, 1, 5, 1, 32, 2, 112, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 12, seed=3):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_degenerate_sizes(torch_cuda):
+    for dims, cfg in [((1, 1, 1), [1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 0]),
+                      ((1, 16, 8), [1, 1, 1, 1, 1, 1, 2, 8, 2, 4, 1]),
+                      ((32, 32, 16), [1, 1, 1, 32, 1, 1, 1, 32, 1, 16, 1])]:
+        w = Workload(torch_cuda, "matmul", dims, "bf16", 9)
+        w.check(P.OPEVO_TILE4, cfg, "degenerate")
+        w.close()
+
+
+# ------------------------------------------------------------------ config 3: BMM 128 x (128x64 . 64x128)
+BMM_CASES = [
+    ("lds, 2 batches per workgroup", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1]),
+    ("direct from global", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0]),
+    ("lds, two slabs", [128, 1, 1, 2, 2, 32, 1, 2, 1, 64, 2, 32, 1]),
+    ("mfma16 direct", [32, 4, 4, 2, 1, 16, 2, 2, 2, 16, 1, 64, 0]),
+    ("mfma16 lds", [128, 1, 4, 2, 1, 16, 2, 2, 2, 16, 2, 32, 1]),
+    ("scalar", [16, 8, 8, 2, 2, 4, 4, 2, 4, 4, 4, 16, 1]),
+    ("whole batch in one grid row", [1, 128, 1, 2, 2, 32, 1, 2, 2, 32, 1, 64, 1]),
+]
+
+
+def test_bmm_attention_shape_bf16(torch_cuda):
+    w = Workload(torch_cuda, "bmm", (128, 128, 128, 64), "bf16", 1236)
+    for label, cfg in BMM_CASES:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 18, seed=202):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_bmm_odd_batch(torch_cuda):
+    w = Workload(torch_cuda, "bmm", (15, 48, 80, 96), "bf16", 31)     # batch 3*5
+    for label, cfg in [("3 per workgroup", [5, 3, 1, 1, 3, 16, 5, 1, 1, 16, 3, 32, 1]),
+                       ("direct", [15, 1, 3, 1, 1, 16, 1, 5, 1, 16, 1, 96, 0]),
+                       ("scalar", [1, 15, 4, 3, 2, 2, 5, 2, 2, 4, 8, 12, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+
+
+# ------------------------------------------------------------------ config 4: Conv2d 1x64x56x56, 3x3
+CONV56_CASES = [
+    ("mfma32 8 rows x 56", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 1, 1, 1, 56, 9, 64, 1]),
+    ("mfma32 single stage", [1, 1, 2, 1, 1, 32, 7, 1, 1, 8, 2, 1, 1, 28, 18, 32, 0]),
+    ("mfma16 7-pixel pieces", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1]),
+    ("mfma16 slab 96", [1, 1, 4, 1, 1, 16, 14, 1, 1, 4, 1, 1, 7, 8, 6, 96, 1]),
+    ("scalar", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
+    ("scalar one pixel tiles", [1, 1, 8, 1, 1, 8, 56, 1, 1, 1, 8, 1, 1, 7, 64, 9, 1]),
+]
+
+
+def test_conv56_bf16(torch_cuda):
+    w = Workload(torch_cuda, "conv2d", (1, 64, 56, 56, 64, 3, 3, 1, 1), "bf16", 1237)
+    for label, cfg in CONV56_CASES:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 18, seed=303):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_conv_stride_padding_kernel_shapes(torch_cuda):
+    # small relatives of the paper's C1 (11x11, stride 4, no padding) and C2 (5x5, padding 2)
+    w = Workload(torch_cuda, "conv2d", (2, 3, 35, 35, 16, 11, 11, 4, 0), "bf16", 41)   # out 7x7, R = 363
+    for label, cfg in [("scalar C1-like", [2, 1, 2, 1, 2, 4, 7, 1, 1, 1, 1, 1, 1, 7, 33, 11, 1]),
+                       ("scalar C1-like b", [1, 2, 1, 2, 2, 4, 1, 1, 7, 1, 1, 7, 1, 1, 3, 121, 0])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (4, 16, 12, 12, 32, 5, 5, 1, 2), "bf16", 42)    # out 12x12, R = 400
+    for label, cfg in [("scalar C2-like", [4, 1, 2, 1, 4, 4, 3, 1, 2, 2, 3, 2, 1, 2, 25, 16, 1]),
+                       ("mfma32, batch inside the tile", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 25, 16, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 9, seed=404):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (2, 16, 9, 9, 32, 3, 3, 2, 1), "bf16", 43)      # stride 2, out 5x5, R = 144
+    for label, cfg in [("stride 2 mfma16 slab 48 -> scalar", [1, 2, 1, 1, 2, 16, 1, 1, 1, 5, 5, 1, 1, 1, 3, 48, 1]),
+                       ("stride 2 scalar", [2, 1, 2, 2, 2, 4, 5, 1, 1, 1, 1, 1, 5, 1, 9, 16, 0])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+
+
+# ------------------------------------------------------------------ config 5: full sizes
+def test_conv14_batch32_bf16_full_size(torch_cuda):
+    _say("  oracle for conv 32x256x14x14 (3.7e9 MACs) ...")
+    w = Workload(torch_cuda, "conv2d", (32, 256, 14, 14, 256, 3, 3, 1, 1), "bf16", 1239)
+    for label, cfg in [("mfma32, 8 images per tile", [4, 8, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 36, 64, 1]),
+                       ("mfma16, 4 images per tile", [8, 4, 4, 2, 1, 32, 7, 1, 1, 2, 7, 1, 1, 2, 72, 32, 1]),
+                       ("scalar", [32, 1, 8, 2, 2, 8, 2, 1, 7, 1, 2, 1, 1, 7, 256, 9, 0])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=505, want_paths=(1, 2)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
+    """Full size of the headline workload.  The oracle computes 24 full rows of C and 4096
+    scattered entries one by one (the full fp64 product is 5.5e11 MACs)."""
+    torch = torch_cuda
+    M = N = K = 8192
+    w = Workload(torch, "matmul", (M, N, K), "bf16", 1238, oracle=False)
+    rs = np.random.default_rng(8192)
+    rows = np.sort(rs.choice(M, size=24, replace=False))
+    ei, ej = rs.integers(0, M, 4096), rs.integers(0, N, 4096)
+    _say("  oracle rows/entries for 8192^3 ...")
+    ref_rows = T.matmul_rows(w.a_host, w.b_host, rows)
+    ref_ent = T.matmul_entries(w.a_host, w.b_host, ei, ej)
+    cases = [("256x256 tile, 4 waves, double-buffered", [32, 2, 1, 128, 32, 2, 1, 128, 128, 64, 1]),
+             ("256x128 tile, 8 waves", [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1]),
+             ("128x128 single stage", [64, 2, 2, 32, 64, 2, 1, 64, 128, 64, 0]),
+             ("mfma16 32x64 tile", [256, 2, 1, 16, 128, 2, 1, 32, 128, 64, 1])]
+    for cfg in w.random_valid(P.OPEVO_TILE4, 4, seed=606, want_paths=(1, 2)):
+        cases.append(("random", list(cfg)))
+    for label, cfg in cases:
+        _say("  case 8192^3 %s cfg=%s" % (label, list(map(int, cfg))))
+        out = w.run(P.OPEVO_TILE4, cfg).reshape(M, N)
+        assert np.all(np.isfinite(out)), label           # every output written (NaN pre-fill)
+        mx, fro = errors(out[rows], ref_rows)
+        assert mx <= TOL16[0] and fro <= TOL16[1], (label, cfg, mx, fro)
+        mx, fro = errors(out[ei, ej], ref_ent)
+        assert mx <= TOL16[0] and fro <= TOL16[1], (label, cfg, mx, fro)
+        # property that holds at any size: column sums of C equal (1^T A) B
+        colsum = w.a_host.astype(np.float64).sum(axis=0) @ w.b_host.astype(np.float64)
+        assert np.max(np.abs(out.astype(np.float64).sum(axis=0) - colsum)) <= 2e-2 * (np.max(np.abs(colsum)) + 1)
+    w.close()
+
+
+# ------------------------------------------------------------------ harness pieces
+def test_compare_f32_matches_numpy(torch_cuda):
+    torch = torch_cuda
+    rs = np.random.default_rng(1)
+    for n in (1, 255, 256 * 1024 + 17, 3_000_001):
+        ref = rs.standard_normal(n).astype(np.float32)
+        c = (ref + 1e-3 * rs.standard_normal(n)).astype(np.float32)
+        mx, fro = P.opevo_compare_f32(torch.from_numpy(c).cuda().data_ptr(), torch.from_numpy(ref).cuda().data_ptr(), n,
+                                      torch.cuda.current_stream().cuda_stream)
+        wmx, wfro = errors(c, ref)
+        assert abs(mx - wmx) <= 1e-12 and abs(fro - wfro) <= 1e-9 * max(wfro, 1e-30)
+    c = ref.copy(); c[12345] = np.nan
+    mx, _ = P.opevo_compare_f32(torch.from_numpy(c).cuda().data_ptr(), torch.from_numpy(ref).cuda().data_ptr(), n,
+                                torch.cuda.current_stream().cuda_stream)
+    assert mx == np.inf
+
+
+def test_kernel_time_and_deadline(torch_cuda):
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235, oracle=False)
+    k, ms = P.opevo_kernel_build(w.op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
+    med, per = P.opevo_kernel_time(k, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, 3, 0, 5)
+    assert 0.0 < med < 5.0 and per.min() > 0 and per.max() < 10 * per.min()
+    res = P.opevo_kernel_resources(k)
+    assert res["vgprs"] > 0 and res["spill_bytes"] == 0
+    P.opevo_kernel_destroy(k)
+    # scalar kernel with a deadline of one clock tick: every workgroup leaves at its first K slab,
+    # the kernel ends normally and the trial is reported invalid
+    k, _ = P.opevo_kernel_build(w.op, P.OPEVO_TILE4, [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1])
+    with pytest.raises(P.OpevoError) as ei:
+        P.opevo_kernel_time(k, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, 1, 1, 1, timeout_ms=1e-9)
+    assert ei.value.status == P.OPEVO_E_INVALID and "deadline" in ei.value.message
+    med, _ = P.opevo_kernel_time(k, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, 1, 1, 2, timeout_ms=5000.0)
+    assert med > 0
+    P.opevo_kernel_destroy(k)
+    w.close()
+
+
+def test_tune_runs_alg1_on_the_gpu_with_parity_gate(torch_cuda):
+    torch = torch_cuda
+    w = Workload(torch, "matmul", (512, 1024, 1024), "bf16", 1235)
+    ref = torch.from_numpy(w.ref.astype(np.float32)).cuda()
+    res = P.opevo_tune(w.op, P.OPEVO_TILE4, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), ref.data_ptr(), w.stream,
+                       trials=60, lambda_=8, rho=8, q=0.5, seed=0, compile_threads=8, warmup=2, samples=3,
+                       trial_timeout_ms=500.0)
+    logs = res["logs"]
+    assert res["n_trials"] == 60 and len(logs["fitness"]) == 60
+    assert res["n_parity_fail"] == 0 and res["n_compile_fail"] == 0
+    assert len({tuple(c) for c in logs["cfg"]}) == 60                    # never sampled twice
+    ok = logs["status"] == P.OPEVO_OK
+    assert np.all(logs["fitness"][ok] > 0) and np.all(logs["fitness"][~ok] == 0)
+    assert set(np.unique(logs["status"])) <= {P.OPEVO_OK, P.OPEVO_E_INVALID}
+    assert res["best_tflops"] == logs["fitness"].max() > 0
+    assert tuple(res["best_cfg"]) == tuple(logs["cfg"][res["best_trial"]])
+    assert np.all(np.diff(logs["wall_s"]) >= 0)
+    # the trajectory is the oracle's Alg. 1 given the fitness the GPU reported
+    from oracle import search as S
+    osp = S.Space([S.Factor(512, 4), S.Factor(1024, 4), S.Factor(1024, 2), S.Categorical(2)])
+    t = S.OpEvo(osp, 8, 8, 0.5, 0)
+    i = 0
+    while i < 60:
+        xs = t.ask(60 - i)
+        assert [osp.flat(x) for x in xs] == [list(c) for c in logs["cfg"][i:i + len(xs)]]
+        t.tell(xs, list(logs["fitness"][i:i + len(xs)]))
+        i += len(xs)
+    # and the winner really computes the product
+    w.check(P.OPEVO_TILE4, res["best_cfg"], "tuned best")
+    _say("  best %.1f TFLOP/s at trial %d: %s" % (res["best_tflops"], res["best_trial"], list(res["best_cfg"])))
+    w.close()
