@@ -65,6 +65,10 @@ class opevo_tune_result(C.Structure):
 
 
 def _load() -> C.CDLL:
+    # PyTorch ships its own HIP runtime.  The library must bind to that same instance (a second
+    # runtime in the process cannot see the device), so torch's libraries are loaded first and
+    # the dynamic linker resolves libopevo's libamdhip64 / libhiprtc dependencies to them.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError("%s is missing: build it with `python paper_2006_05664_amd/build.py`" % LIB_PATH)
     return C.CDLL(LIB_PATH)

@@ -33,19 +33,29 @@ CompileResult compile_source(const std::string &tmpl, const std::string &defines
         res.log = "template " + tmpl + " is not built into the library";
         return res;
     }
-    const std::string src = std::string(prologue) + "\n" + body;
+    // The -D constants are written into the source as #define lines rather than passed as
+    // options: hipRTC force-includes its runtime header first, and short macro names such as N
+    // must not be visible while that header is parsed.
+    std::string src;
+    std::vector<std::string> opts;
+    {
+        std::istringstream is(defines);
+        std::string t;
+        while (is >> t) {
+            const size_t eq = t.find('=');
+            if (t.rfind("-D", 0) == 0 && eq != std::string::npos)
+                src += "#define " + t.substr(2, eq - 2) + " " + t.substr(eq + 1) + "\n";
+            else
+                opts.push_back(t);
+        }
+    }
+    src += std::string(prologue) + "\n" + body;
     hiprtcProgram prog;
     hiprtcResult r = hiprtcCreateProgram(&prog, src.c_str(), (tmpl + ".hip").c_str(), 0, nullptr, nullptr);
     if (r != HIPRTC_SUCCESS) {
         res.status = OPEVO_E_HIPRTC;
         res.log = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
         return res;
-    }
-    std::vector<std::string> opts;
-    {
-        std::istringstream is(defines);
-        std::string t;
-        while (is >> t) opts.push_back(t);
     }
     opts.insert(opts.end(), {"--offload-arch=gfx950", "-O3", "-std=c++17",
                              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"});

@@ -330,13 +330,13 @@ def test_compare_f32_matches_numpy(torch_cuda):
     for n in (1, 255, 256 * 1024 + 17, 3_000_001):
         ref = rs.standard_normal(n).astype(np.float32)
         c = (ref + 1e-3 * rs.standard_normal(n)).astype(np.float32)
-        mx, fro = P.opevo_compare_f32(torch.from_numpy(c).cuda().data_ptr(), torch.from_numpy(ref).cuda().data_ptr(), n,
-                                      torch.cuda.current_stream().cuda_stream)
+        dc, dref = torch.from_numpy(c).cuda(), torch.from_numpy(ref).cuda()   # keep both alive
+        mx, fro = P.opevo_compare_f32(dc.data_ptr(), dref.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
         wmx, wfro = errors(c, ref)
         assert abs(mx - wmx) <= 1e-12 and abs(fro - wfro) <= 1e-9 * max(wfro, 1e-30)
     c = ref.copy(); c[12345] = np.nan
-    mx, _ = P.opevo_compare_f32(torch.from_numpy(c).cuda().data_ptr(), torch.from_numpy(ref).cuda().data_ptr(), n,
-                                torch.cuda.current_stream().cuda_stream)
+    dc, dref = torch.from_numpy(c).cuda(), torch.from_numpy(ref).cuda()
+    mx, _ = P.opevo_compare_f32(dc.data_ptr(), dref.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
     assert mx == np.inf
 
 
