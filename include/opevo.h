@@ -246,11 +246,22 @@ int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *
 int opevo_compare_f32(const float *c, const float *ref, int64_t n, void *stream,
                       double *max_scaled, double *rel_fro);
 
+/* The same for a sample of rows: c is viewed as a matrix with row_len columns, ref_rows holds
+ * the n_rows reference rows row_index[0..n_rows) (DEVICE int32) back to back.  For outputs
+ * whose full reference is too expensive to compute on the host. */
+int opevo_compare_rows_f32(const float *c, const float *ref_rows, const int32_t *row_index,
+                           int64_t n_rows, int64_t row_len, void *stream,
+                           double *max_scaled, double *rel_fro);
+
 /* -------------------------------------------------------- whole tuning run (Alg. 1) */
 typedef struct {
     const void *a, *b;         /* DEVICE inputs                                                  */
     void       *c;             /* DEVICE fp32 output, overwritten by every trial                 */
-    const float *ref;          /* DEVICE fp32 reference tensor for the parity gate, or NULL      */
+    const float *ref;          /* DEVICE fp32 reference for the parity gate, or NULL: the whole
+                                  output, or (n_ref_rows > 0) only the sampled rows, back to back */
+    const int32_t *ref_row_index;  /* DEVICE row numbers of the sampled reference rows, or NULL   */
+    int32_t     n_ref_rows;    /* 0: ref is the whole output                                     */
+    int32_t     ref_row_len;   /* columns of the output viewed as a matrix (sampled reference)   */
     void       *stream;        /* hipStream_t                                                    */
     int32_t     trials;        /* evaluation budget, the initial lambda included                 */
     int32_t     lambda, rho;   /* Alg. 1                                                         */

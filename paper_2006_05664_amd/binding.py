@@ -48,6 +48,7 @@ class opevo_plan(C.Structure):
 
 class opevo_tune_args(C.Structure):
     _fields_ = [("a", C.c_void_p), ("b", C.c_void_p), ("c", C.c_void_p), ("ref", C.c_void_p),
+                ("ref_row_index", C.c_void_p), ("n_ref_rows", C.c_int32), ("ref_row_len", C.c_int32),
                 ("stream", C.c_void_p), ("trials", C.c_int32), ("lambda_", C.c_int32), ("rho", C.c_int32),
                 ("q", C.c_double), ("seed", C.c_uint64), ("compile_threads", C.c_int32),
                 ("warmup", C.c_int32), ("launches_per_sample", C.c_int32), ("samples", C.c_int32),
@@ -125,6 +126,7 @@ _SIGNATURES = {
     "opevo_kernel_launch": [_vp, _vp, _vp, _vp, _vp],
     "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
     "opevo_compare_f32": [_vp, _vp, C.c_int64, _vp, _f64p, _f64p],
+    "opevo_compare_rows_f32": [_vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _f64p, _f64p],
     "opevo_tune": [_vp, C.c_int, C.POINTER(opevo_tune_args), _i32p, C.POINTER(opevo_tune_result)],
 }
 for _name, _argtypes in _SIGNATURES.items():
@@ -499,7 +501,15 @@ def opevo_compare_f32(c: int, ref: int, n: int, stream: int = 0) -> Tuple[float,
     return mx.value, fro.value
 
 
+def opevo_compare_rows_f32(c: int, ref_rows: int, row_index: int, n_rows: int, row_len: int,
+                           stream: int = 0) -> Tuple[float, float]:
+    mx, fro = C.c_double(), C.c_double()
+    _check(lib.opevo_compare_rows_f32(c, ref_rows, row_index, n_rows, row_len, stream, C.byref(mx), C.byref(fro)))
+    return mx.value, fro.value
+
+
 def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = None, stream: int = 0,
+               ref_row_index: Optional[int] = None, n_ref_rows: int = 0, ref_row_len: int = 0,
                trials: int = 500, lambda_: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0,
                compile_threads: int = 8, warmup: int = 3, launches_per_sample: int = 0, samples: int = 5,
                trial_timeout_ms: float = 0.0, tol_max_scaled: float = 2e-2, tol_rel_fro: float = 5e-3) -> dict:
@@ -513,7 +523,8 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
     logs = {"cfg": np.zeros((trials, w), dtype=np.int32), "fitness": np.zeros(trials),
             "status": np.zeros(trials, dtype=np.int32), "compile_ms": np.zeros(trials),
             "run_ms": np.zeros(trials), "wall_s": np.zeros(trials)}
-    args = opevo_tune_args(a=a, b=b, c=c, ref=ref, stream=stream, trials=trials, lambda_=lambda_, rho=rho,
+    args = opevo_tune_args(a=a, b=b, c=c, ref=ref, ref_row_index=ref_row_index, n_ref_rows=n_ref_rows,
+                           ref_row_len=ref_row_len, stream=stream, trials=trials, lambda_=lambda_, rho=rho,
                            q=q, seed=seed, compile_threads=compile_threads, warmup=warmup,
                            launches_per_sample=launches_per_sample, samples=samples,
                            trial_timeout_ms=trial_timeout_ms, tol_max_scaled=tol_max_scaled, tol_rel_fro=tol_rel_fro,

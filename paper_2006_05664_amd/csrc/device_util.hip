@@ -16,12 +16,16 @@ namespace {
 constexpr int kBlocks = 1024;
 constexpr int kThreads = 256;
 
+// rows == NULL: c and ref are both n elements.  rows != NULL: ref holds n = n_rows * row_len
+// elements, the rows rows[0..n_rows) of c viewed as a matrix with row_len columns.
 __global__ __launch_bounds__(kThreads)
-void compare_partial(const float *__restrict__ c, const float *__restrict__ ref, long n, double *__restrict__ part)
+void compare_partial(const float *__restrict__ c, const float *__restrict__ ref, long n,
+                     const int *__restrict__ rows, long row_len, double *__restrict__ part)
 {
     double mx = 0.0, se = 0.0, sr = 0.0;
     for (long i = (long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long)gridDim.x * kThreads) {
-        const double r = ref[i], d = (double)c[i] - r;
+        const long ci = rows ? (long)rows[i / row_len] * row_len + i % row_len : i;
+        const double r = ref[i], d = (double)c[ci] - r;
         const double s = fabs(d) / (fabs(r) + 1.0);
         mx = (s <= mx) ? mx : (s == s ? s : INFINITY);   // NaN -> inf
         se += d * d;
@@ -62,7 +66,8 @@ double g_ticks_per_ms[64] = {0.0};
 
 namespace opevo {
 
-int compare_f32(const float *c, const float *ref, int64_t n, hipStream_t stream, double *max_scaled, double *rel_fro)
+int compare_f32(const float *c, const float *ref, int64_t n, const int *rows, int64_t row_len,
+                hipStream_t stream, double *max_scaled, double *rel_fro)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -79,7 +84,8 @@ int compare_f32(const float *c, const float *ref, int64_t n, hipStream_t stream,
     }
     int blocks = int(std::min<int64_t>(kBlocks, (n + kThreads - 1) / kThreads));
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(compare_partial, dim3(blocks), dim3(kThreads), 0, stream, c, ref, (long)n, ws);
+    hipLaunchKernelGGL(compare_partial, dim3(blocks), dim3(kThreads), 0, stream, c, ref, (long)n, rows,
+                       (long)row_len, ws);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "compare_partial launch");
     std::vector<double> host(size_t(3) * blocks);
@@ -143,5 +149,15 @@ extern "C" int opevo_compare_f32(const float *c, const float *ref, int64_t n, vo
                                  double *max_scaled, double *rel_fro)
 {
     if (!c || !ref || n < 1) return opevo::fail(OPEVO_E_ARG, "compare_f32: bad arguments");
-    return opevo::compare_f32(c, ref, n, static_cast<hipStream_t>(stream), max_scaled, rel_fro);
+    return opevo::compare_f32(c, ref, n, nullptr, 1, static_cast<hipStream_t>(stream), max_scaled, rel_fro);
+}
+
+extern "C" int opevo_compare_rows_f32(const float *c, const float *ref_rows, const int32_t *row_index,
+                                      int64_t n_rows, int64_t row_len, void *stream,
+                                      double *max_scaled, double *rel_fro)
+{
+    if (!c || !ref_rows || !row_index || n_rows < 1 || row_len < 1)
+        return opevo::fail(OPEVO_E_ARG, "compare_rows_f32: bad arguments");
+    return opevo::compare_f32(c, ref_rows, n_rows * row_len, row_index, row_len,
+                              static_cast<hipStream_t>(stream), max_scaled, rel_fro);
 }

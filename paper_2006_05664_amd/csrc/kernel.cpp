@@ -40,6 +40,7 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     k->flops = op.flops();
     k->tmpl = d.tmpl;
     k->defines = d.defines;
+    k->name = d.kernel_name;
     if (compile_ms)
         *compile_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = k;
@@ -50,7 +51,7 @@ int load_kernel(opevo_kernel *k)
 {
     if (k->fn) return OPEVO_OK;
     HIP_TRY(hipModuleLoadData(&k->module, k->code.data()));
-    hipError_t e = hipModuleGetFunction(&k->fn, k->module, "opevo_kernel");
+    hipError_t e = hipModuleGetFunction(&k->fn, k->module, k->name.c_str());
     if (e != hipSuccess) {
         (void)hipModuleUnload(k->module);
         k->module = nullptr; k->fn = nullptr;

@@ -12,7 +12,7 @@
 struct opevo_kernel {
     opevo_plan plan;
     double flops = 0.0;
-    std::string tmpl, defines;
+    std::string tmpl, defines, name;
     std::vector<char> code;        // gfx950 code object from hipRTC
     hipModule_t module = nullptr;  // loaded on first launch
     hipFunction_t fn = nullptr;
@@ -41,5 +41,6 @@ int hip_fail(hipError_t e, const char *what);
 }  // namespace opevo
 
 namespace opevo {
-int compare_f32(const float *c, const float *ref, int64_t n, hipStream_t stream, double *max_scaled, double *rel_fro);
+int compare_f32(const float *c, const float *ref, int64_t n, const int *rows, int64_t row_len,
+                hipStream_t stream, double *max_scaled, double *rel_fro);
 }

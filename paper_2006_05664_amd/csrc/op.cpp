@@ -181,6 +181,17 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     }
 
     out.tmpl = path == 0 ? "gemm_scalar" : "gemm_mfma";
+    // one symbol per configuration, so profiles list each instantiated kernel on its own line
+    {
+        std::ostringstream nm;
+        nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? "bmm" : "conv")
+           << (four_level ? "4" : "2");
+        int width = 0;
+        for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : 1;
+        for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
+        out.kernel_name = nm.str();
+    }
+    D << "-DKERNEL_NAME=" << out.kernel_name << " ";
     D << "-DOP=" << op.kind << " -DIN_DTYPE=" << op.dtype << " -DM=" << op.M << " -DN=" << op.N
       << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
       << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv;

@@ -30,6 +30,7 @@ struct Decoded {
     opevo_plan plan;
     std::string tmpl;      // template name: "gemm_scalar" or "gemm_mfma"
     std::string defines;   // space separated -D options
+    std::string kernel_name;   // symbol of the instantiated kernel
 };
 
 // OPEVO_OK (plan.status says valid/invalid) or OPEVO_E_ILLEGAL / OPEVO_E_ARG.

@@ -177,7 +177,7 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As
 }
 
 extern "C" __global__ __launch_bounds__(NT)
-void opevo_kernel(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
+void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
                   unsigned long long *ctl /* deadline control, used by the scalar template only */)
 {
     extern __shared__ __attribute__((aligned(16))) u16 smem[];

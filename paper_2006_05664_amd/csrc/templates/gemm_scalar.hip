@@ -15,7 +15,7 @@
 // scores the trial as invalid (fitness 0).
 
 extern "C" __global__ __launch_bounds__(NT)
-void opevo_kernel(const in_t *__restrict__ A, const in_t *__restrict__ B, float *__restrict__ C,
+void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *__restrict__ C,
                   unsigned long long *ctl)
 {
     extern __shared__ __attribute__((aligned(16))) float smem_f[];

@@ -38,6 +38,10 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
     if (!args->a || !args->b || !args->c) return fail(OPEVO_E_ARG, "tune: device pointers a, b, c are required");
     if (args->trials < 1 || args->lambda < 1 || args->rho < 1 || args->samples < 1 || args->warmup < 0)
         return fail(OPEVO_E_ARG, "tune: trials, lambda, rho, samples must be >= 1");
+    if (args->ref && args->n_ref_rows > 0) {
+        if (!args->ref_row_index || args->ref_row_len < 1 || op->c_elems() % args->ref_row_len != 0)
+            return fail(OPEVO_E_ARG, "tune: sampled reference needs row indices and a row length dividing the output");
+    }
     std::memset(result, 0, sizeof *result);
     result->best_trial = -1;
 
@@ -100,7 +104,13 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
                                      args->launches_per_sample, args->samples, args->trial_timeout_ms, &ms, nullptr);
                 if (status == OPEVO_OK && args->ref) {
                     double mx = 0.0, fro = 0.0;
-                    status = compare_f32(static_cast<const float *>(args->c), args->ref, op->c_elems(), stream, &mx, &fro);
+                    if (args->n_ref_rows > 0)
+                        status = compare_f32(static_cast<const float *>(args->c), args->ref,
+                                             int64_t(args->n_ref_rows) * args->ref_row_len, args->ref_row_index,
+                                             args->ref_row_len, stream, &mx, &fro);
+                    else
+                        status = compare_f32(static_cast<const float *>(args->c), args->ref, op->c_elems(), nullptr, 1,
+                                             stream, &mx, &fro);
                     if (status == OPEVO_OK && !(mx <= args->tol_max_scaled && fro <= args->tol_rel_fro)) {
                         status = OPEVO_E_PARITY;
                         set_error("parity: max scaled error %.3g, relative Frobenius error %.3g [%s]", mx, fro,

@@ -340,6 +340,20 @@ def test_compare_f32_matches_numpy(torch_cuda):
     assert mx == np.inf
 
 
+def test_compare_rows_f32_matches_numpy(torch_cuda):
+    torch = torch_cuda
+    rs = np.random.default_rng(2)
+    rows_total, row_len = 300, 257
+    c = rs.standard_normal((rows_total, row_len)).astype(np.float32)
+    rows = np.array([299, 0, 17, 150, 151], dtype=np.int32)
+    ref = (c[rows] + 1e-3 * rs.standard_normal((rows.size, row_len))).astype(np.float32)
+    dc, dref, drows = torch.from_numpy(c).cuda(), torch.from_numpy(ref).cuda(), torch.from_numpy(rows).cuda()
+    mx, fro = P.opevo_compare_rows_f32(dc.data_ptr(), dref.data_ptr(), drows.data_ptr(), rows.size, row_len,
+                                       torch.cuda.current_stream().cuda_stream)
+    wmx, wfro = errors(c[rows], ref)
+    assert abs(mx - wmx) <= 1e-12 and abs(fro - wfro) <= 1e-9 * wfro
+
+
 def test_kernel_time_and_deadline(torch_cuda):
     w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235, oracle=False)
     k, ms = P.opevo_kernel_build(w.op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
