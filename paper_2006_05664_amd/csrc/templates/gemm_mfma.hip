@@ -11,11 +11,15 @@
 // LDS layout (16-bit elements): As[stage][BM][BK+PAD] and Bs[stage][BN][BK+PAD], both with
 // the reduction index contiguous, which is the order an MFMA lane wants its 8 operand values
 // in.  A rows arrive that way from global memory; B arrives with n contiguous, so each
-// thread loads an 8(k) x 8(n) block, transposes it in registers and writes 8 rows of 16 B.
+// thread loads a KB(k) x 8(n) block (KB = 8, 4 or 2, the largest that still gives every thread
+// a block), transposes it in registers and writes 8 LDS rows of 2*KB bytes.  Consecutive lanes
+// take consecutive k-blocks of the same 8 columns, so that their transposed stores fall into
+// one padded LDS row after another without bank conflicts.
 //
-// FLAG = 1: two LDS stages; the global loads of slab kt+1 are issued before the MFMAs of
-//           slab kt and written to the other stage afterwards (one barrier per slab); the
-//           MFMA K loop is fully unrolled.
+// FLAG = 1: two LDS stages and two register slabs: the global loads of slab kt+2 are issued
+//           before the MFMAs of slab kt, slab kt+1 (loaded one step earlier) is written to the
+//           other stage after them (one barrier per slab); the MFMA loop is fully unrolled and
+//           software-pipelined (fragments of the next step are read while this step's MFMAs run).
 // FLAG = 0: one stage, load -> barrier -> compute -> barrier; K loop not unrolled.
 // BMM only, STAGE_LDS = 0: no LDS at all, fragments are read straight from global memory.
 
@@ -43,13 +47,20 @@ constexpr int MI = TM / ATOM, NI = TN / ATOM;                 // atoms per wave 
 constexpr int FMI = (FM % ATOM == 0) ? FM / ATOM : 1;         // atoms per basic tile
 constexpr int FNI = (FN % ATOM == 0) ? FN / ATOM : 1;
 constexpr int LDA = BK + PAD, LDB = BK + PAD;
+__device__ __forceinline__ int lds_off(int row, int k)   // element offset of (row, k) in a stage
+{
+    return row * (BK + PAD) + k;
+}
 constexpr int A_STAGE = BM * LDA, B_STAGE = BN * LDB;
 constexpr int A_CHUNKS = BM * (BK / 8);                       // 16-byte pieces of the A slab
 constexpr int NA = (A_CHUNKS + NT - 1) / NT;
 #if OP == OP_CONV
 constexpr int B_CHUNKS = BN * (BK / 8);                       // (column, 8 taps) gathers
+constexpr int KB = 8;
 #else
-constexpr int B_CHUNKS = (BK / 8) * (BN / 8);                 // 8x8 blocks of the B slab
+// B slab in KB(k) x 8(n) blocks; KB shrinks (8 -> 4 -> 2) until every thread owns a block
+constexpr int KB = ((BK / 8) * (BN / 8) >= NT) ? 8 : ((BK / 4) * (BN / 8) >= NT) ? 4 : 2;
+constexpr int B_CHUNKS = (BK / KB) * (BN / 8);
 #endif
 constexpr int NB = (B_CHUNKS + NT - 1) / NT;
 
@@ -58,7 +69,7 @@ struct Slab {
 #if OP == OP_CONV
     u32x4 b[NB];
 #else
-    u32x4 b[NB][8];
+    u32x4 b[NB][KB];
 #endif
 };
 
@@ -93,10 +104,13 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
             v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
             s.b[i] = v;
 #else
-            const int kb = q / (BN / 8), nb = q % (BN / 8);
+            // consecutive lanes take consecutive k-blocks of the same 8 columns: their transposed
+            // LDS rows are then contiguous (no bank conflicts) and each global row still gets
+            // whole 128-byte segments from the 8 lanes that share a k-block
+            const int kb = q % (BK / KB), nb = q / (BK / KB);
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                s.b[i][j] = *(const u32x4 *)(Bb + (long)(k0 + kb * 8 + j) * N + n0 + nb * 8);
+            for (int j = 0; j < KB; ++j)
+                s.b[i][j] = *(const u32x4 *)(Bb + (long)(k0 + kb * KB + j) * N + n0 + nb * 8);
 #endif
         }
     }
@@ -109,7 +123,7 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
         const int q = tid + i * NT;
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
             const int row = q / (BK / 8), kc = q % (BK / 8);
-            *(u32x4 *)(As + row * LDA + kc * 8) = s.a[i];
+            *(u32x4 *)(As + lds_off(row, kc * 8)) = s.a[i];
         }
     }
 #pragma unroll
@@ -118,26 +132,22 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
         if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
 #if OP == OP_CONV
             const int c = q % BN, kc = q / BN;
-            *(u32x4 *)(Bs + c * LDB + kc * 8) = s.b[i];
+            *(u32x4 *)(Bs + lds_off(c, kc * 8)) = s.b[i];
 #else
-            const int kb = q / (BN / 8), nb = q % (BN / 8);
-            // 8x8 transpose: row j of the block is k = kb*8+j holding n = nb*8 .. +7
+            const int kb = q % (BK / KB), nb = q / (BK / KB);
+            // KB x 8 transpose: row j of the block is k = kb*KB+j holding n = nb*8 .. +7
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                u32x4 o;
                 const int d = c / 2;
-                if (c % 2 == 0) {
-                    o.x = (s.b[i][0][d] & 0xffffu) | (s.b[i][1][d] << 16);
-                    o.y = (s.b[i][2][d] & 0xffffu) | (s.b[i][3][d] << 16);
-                    o.z = (s.b[i][4][d] & 0xffffu) | (s.b[i][5][d] << 16);
-                    o.w = (s.b[i][6][d] & 0xffffu) | (s.b[i][7][d] << 16);
-                } else {
-                    o.x = (s.b[i][0][d] >> 16) | (s.b[i][1][d] & 0xffff0000u);
-                    o.y = (s.b[i][2][d] >> 16) | (s.b[i][3][d] & 0xffff0000u);
-                    o.z = (s.b[i][4][d] >> 16) | (s.b[i][5][d] & 0xffff0000u);
-                    o.w = (s.b[i][6][d] >> 16) | (s.b[i][7][d] & 0xffff0000u);
-                }
-                *(u32x4 *)(Bs + (nb * 8 + c) * LDB + kb * 8) = o;
+                u32 o[KB / 2];
+#pragma unroll
+                for (int t = 0; t < KB / 2; ++t)
+                    o[t] = (c % 2 == 0) ? ((s.b[i][2 * t][d] & 0xffffu) | (s.b[i][2 * t + 1][d] << 16))
+                                        : ((s.b[i][2 * t][d] >> 16) | (s.b[i][2 * t + 1][d] & 0xffff0000u));
+                u16 *dst = Bs + lds_off(nb * 8 + c, kb * KB);
+                if (KB == 8) { u32x4 v; v.x = o[0]; v.y = o[1 % (KB / 2)]; v.z = o[2 % (KB / 2)]; v.w = o[3 % (KB / 2)]; *(u32x4 *)dst = v; }
+                else if (KB == 4) { typedef __attribute__((ext_vector_type(2))) unsigned int u32x2; u32x2 v; v.x = o[0]; v.y = o[1 % (KB / 2)]; *(u32x2 *)dst = v; }
+                else { *(u32 *)dst = o[0]; }
             }
 #endif
         }
@@ -146,34 +156,57 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
 
 // MFMAs of one LDS-resident slab.  Lane l of a wave supplies, for atom row/column l % ATOM,
 // the 8 reduction values starting at 8*(l / ATOM) of each KA-wide step.
+// A slab is consumed in steps of one basic tile (FMI x FNI atoms) per KA-wide K step: the
+// FMI + FNI fragments of a step are read from LDS, then FMI*FNI MFMAs form their outer product.
+__device__ __forceinline__ void load_frags(frag_t (&af)[FMI], frag_t (&bf)[FNI], const u16 *As, const u16 *Bs,
+                                           int a_row0, int b_row0, int lk, int step)
+{
+    constexpr int TJ = NI / FNI, TI = MI / FMI;
+    const int kk = step / (TI * TJ), i0 = (step / TJ) % TI * FMI, j0 = step % TJ * FNI;
+#pragma unroll
+    for (int i = 0; i < FMI; ++i)
+        af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + lds_off(a_row0 + (i0 + i) * ATOM, kk * KA + lk)));
+#pragma unroll
+    for (int j = 0; j < FNI; ++j)
+        bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(Bs + lds_off(b_row0 + (j0 + j) * ATOM, kk * KA + lk)));
+}
+
 __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *Bs,
                                              int a_row0, int b_row0, int lk)
 {
+    constexpr int TJ = NI / FNI, TI = MI / FMI;
+    constexpr int STEPS = (BK / KA) * TI * TJ;
 #if FLAG
+    // fully unrolled, fragments of step t+1 are read before the MFMAs of step t are issued
+    // (two register sets), so LDS latency hides behind the matrix pipe inside one wave
+    frag_t af[2][FMI], bf[2][FNI];
+    load_frags(af[0], bf[0], As, Bs, a_row0, b_row0, lk, 0);
 #pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+        if (t + 1 < STEPS) load_frags(af[(t + 1) & 1], bf[(t + 1) & 1], As, Bs, a_row0, b_row0, lk, t + 1);
+        const int i0 = (t / TJ) % TI * FMI, j0 = t % TJ * FNI;
+#pragma unroll
+        for (int i = 0; i < FMI; ++i)
+#pragma unroll
+            for (int j = 0; j < FNI; ++j)
+                acc[i0 + i][j0 + j] = MFMA(af[t & 1][i], bf[t & 1][j], acc[i0 + i][j0 + j]);
+    }
 #else
 #pragma unroll 1
-#endif
     for (int kk = 0; kk < BK / KA; ++kk) {
 #pragma unroll
-        for (int i0 = 0; i0 < MI; i0 += FMI) {
+        for (int tt = 0; tt < TI * TJ; ++tt) {
+            frag_t af[FMI], bf[FNI];
+            load_frags(af, bf, As, Bs, a_row0, b_row0, lk + kk * KA, tt);
+            const int i0 = tt / TJ * FMI, j0 = tt % TJ * FNI;
 #pragma unroll
-            for (int j0 = 0; j0 < NI; j0 += FNI) {
-                frag_t af[FMI], bf[FNI];
-#pragma unroll
-                for (int i = 0; i < FMI; ++i)
-                    af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + (a_row0 + (i0 + i) * ATOM) * LDA + kk * KA + lk));
+            for (int i = 0; i < FMI; ++i)
 #pragma unroll
                 for (int j = 0; j < FNI; ++j)
-                    bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(Bs + (b_row0 + (j0 + j) * ATOM) * LDB + kk * KA + lk));
-#pragma unroll
-                for (int i = 0; i < FMI; ++i)
-#pragma unroll
-                    for (int j = 0; j < FNI; ++j)
-                        acc[i0 + i][j0 + j] = MFMA(af[i], bf[j], acc[i0 + i][j0 + j]);
-            }
+                    acc[i0 + i][j0 + j] = MFMA(af[i], bf[j], acc[i0 + i][j0 + j]);
         }
     }
+#endif
 }
 
 extern "C" __global__ __launch_bounds__(NT)
@@ -213,25 +246,39 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         u16 *As = smem, *Bs = smem + NSTAGE * A_STAGE;
         Slab slab;
 #if OP == OP_CONV
-#define LOAD_SLAB(kt) load_slab(slab, Ab, Bb, m0, (kt) * BK, tid, cb)
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, cb)
 #else
-#define LOAD_SLAB(kt) load_slab(slab, Ab, Bb, m0, (kt) * BK, tid, n0)
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, n0)
 #endif
 #if FLAG
+        // Two LDS stages, two register slabs: the loads of slab kt+2 are issued before the MFMAs
+        // of slab kt; slab kt+1 (loaded one iteration earlier) is written to the other stage
+        // after them.  Global latency therefore has two K steps to hide in.
+        Slab slab1;
+        constexpr int KPAIRS = KSTEPS / 2 * 2;
         if (bi > 0) __syncthreads();
-        LOAD_SLAB(0);
+        LOAD_INTO(slab, 0);
+        if (KSTEPS > 1) LOAD_INTO(slab1, 1);
         store_slab(slab, As, Bs, tid);
         __syncthreads();
-        for (int kt = 0; kt < KSTEPS; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < KSTEPS) LOAD_SLAB(kt + 1);
-            compute_slab(acc, As + cur * A_STAGE, Bs + cur * B_STAGE, wm * TM + lrow, wn * TN + lrow, lk);
-            if (kt + 1 < KSTEPS) store_slab(slab, As + (cur ^ 1) * A_STAGE, Bs + (cur ^ 1) * B_STAGE, tid);
+#define KCLAMP(k) ((k) < KSTEPS ? (k) : KSTEPS - 1)
+#define COMPUTE(stage) compute_slab(acc, As + (stage) * A_STAGE, Bs + (stage) * B_STAGE, wm * TM + lrow, wn * TN + lrow, lk)
+        // branch-free body: slab indices past the end are clamped (a few redundant loads at
+        // the tail) so that the accumulators never cross a conditional block
+        for (int kt = 0; kt < KPAIRS; kt += 2) {
+            LOAD_INTO(slab, KCLAMP(kt + 2));
+            COMPUTE(0);
+            store_slab(slab1, As + A_STAGE, Bs + B_STAGE, tid);
+            __syncthreads();
+            LOAD_INTO(slab1, KCLAMP(kt + 3));
+            COMPUTE(1);
+            store_slab(slab, As, Bs, tid);
             __syncthreads();
         }
+        if (KSTEPS % 2) COMPUTE(0);
 #else
         for (int kt = 0; kt < KSTEPS; ++kt) {
-            LOAD_SLAB(kt);
+            LOAD_INTO(slab, kt);
             __syncthreads();
             store_slab(slab, As, Bs, tid);
             __syncthreads();
