@@ -206,12 +206,16 @@ int opevo_kernel_plan(const opevo_op *op, int variant, const int32_t *cfg, opevo
 int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg,
                          char *buf, size_t cap);
 /* hipRTC serialises compilations inside one process, so concurrent instantiation (the paper
- * compiles on 8 CPU threads, Sec. 6) runs on worker processes forked from the caller.  Start
- * the pool early, ideally before the process first touches the GPU; workers keep no device
- * file open and only run hipRTC.  Idempotent; *n_running (may be NULL) = workers alive.
- * Without a pool every instantiation compiles in the calling process. */
+ * compiles on 8 CPU threads, Sec. 6) runs on worker processes.  Started before the calling
+ * process has opened the GPU, a worker is the executable opevo_rtc_worker next to the library
+ * (fork + exec; it uses the hipRTC of the ROCm installation under /opt/rocm).  Started later,
+ * no exec is done: a worker is then a fork of the caller that only serves compile requests
+ * with the hipRTC the caller is bound to.  Workers keep no device file open.  Idempotent;
+ * *n_running (may be NULL) = workers alive.  Without a pool every instantiation compiles in
+ * the calling process.  opevo_compile_pool_kind: 1 executable workers, 0 forks, -1 no pool. */
 int opevo_compile_pool_start(int n_workers, int *n_running);
 int opevo_compile_pool_stop(void);
+int opevo_compile_pool_kind(int *kind);
 
 /* Instantiate: render + hipRTC-compile for gfx950 (works without a GPU).  Returns
  * OPEVO_E_INVALID for an invalid configuration (no kernel), OPEVO_E_HIPRTC on a compile

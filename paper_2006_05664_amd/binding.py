@@ -117,6 +117,7 @@ _SIGNATURES = {
     "opevo_op_space": [_vp, C.c_int, C.POINTER(_vp)],
     "opevo_compile_pool_start": [C.c_int, C.POINTER(C.c_int)],
     "opevo_compile_pool_stop": [],
+    "opevo_compile_pool_kind": [C.POINTER(C.c_int)],
     "opevo_kernel_plan": [_vp, C.c_int, _i32p, C.POINTER(opevo_plan)],
     "opevo_kernel_defines": [_vp, C.c_int, _i32p, C.c_char_p, C.c_size_t],
     "opevo_kernel_build": [_vp, C.c_int, _i32p, C.POINTER(_vp), _f64p],
@@ -440,6 +441,12 @@ def opevo_compile_pool_start(n_workers: int) -> int:
 
 def opevo_compile_pool_stop() -> None:
     _check(lib.opevo_compile_pool_stop())
+
+
+def opevo_compile_pool_kind() -> int:
+    k = C.c_int()
+    _check(lib.opevo_compile_pool_kind(C.byref(k)))
+    return k.value
 
 
 def opevo_kernel_plan(op, variant: int, cfg) -> opevo_plan:

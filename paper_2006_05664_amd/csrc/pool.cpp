@@ -1,86 +1,23 @@
-// hipRTC compilation, in-process and on a pool of forked worker processes.
+// Pool of hipRTC worker processes: see pool.hpp.
 #include "pool.hpp"
 
-#include <chrono>
 #include <condition_variable>
 #include <csignal>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
-#include <sstream>
 
 #include <dirent.h>
+#include <dlfcn.h>
+#include <fcntl.h>
 #include <sys/types.h>
 #include <sys/wait.h>
 #include <unistd.h>
 
-#include <hip/hiprtc.h>
-
 #include "common.hpp"
-#include "kernel.hpp"
 
 namespace opevo {
-
-CompileResult compile_source(const std::string &tmpl, const std::string &defines)
-{
-    CompileResult res;
-    const auto t0 = std::chrono::steady_clock::now();
-    const char *prologue = template_source("common");
-    const char *body = template_source(tmpl.c_str());
-    if (!prologue || !body) {
-        res.status = OPEVO_E_ARG;
-        res.log = "template " + tmpl + " is not built into the library";
-        return res;
-    }
-    // The -D constants are written into the source as #define lines rather than passed as
-    // options: hipRTC force-includes its runtime header first, and short macro names such as N
-    // must not be visible while that header is parsed.
-    std::string src;
-    std::vector<std::string> opts;
-    {
-        std::istringstream is(defines);
-        std::string t;
-        while (is >> t) {
-            const size_t eq = t.find('=');
-            if (t.rfind("-D", 0) == 0 && eq != std::string::npos)
-                src += "#define " + t.substr(2, eq - 2) + " " + t.substr(eq + 1) + "\n";
-            else
-                opts.push_back(t);
-        }
-    }
-    src += std::string(prologue) + "\n" + body;
-    hiprtcProgram prog;
-    hiprtcResult r = hiprtcCreateProgram(&prog, src.c_str(), (tmpl + ".hip").c_str(), 0, nullptr, nullptr);
-    if (r != HIPRTC_SUCCESS) {
-        res.status = OPEVO_E_HIPRTC;
-        res.log = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
-        return res;
-    }
-    opts.insert(opts.end(), {"--offload-arch=gfx950", "-O3", "-std=c++17",
-                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"});
-    std::vector<const char *> optv;
-    for (const auto &o : opts) optv.push_back(o.c_str());
-    r = hiprtcCompileProgram(prog, int(optv.size()), optv.data());
-    if (r != HIPRTC_SUCCESS) {
-        size_t n = 0;
-        hiprtcGetProgramLogSize(prog, &n);
-        std::string log(n, '\0');
-        if (n) hiprtcGetProgramLog(prog, &log[0]);
-        hiprtcDestroyProgram(&prog);
-        if (log.size() > 1500) log.resize(1500);
-        res.status = OPEVO_E_HIPRTC;
-        res.log = std::string(hiprtcGetErrorString(r)) + "\n" + log;
-        return res;
-    }
-    size_t code_size = 0;
-    hiprtcGetCodeSize(prog, &code_size);
-    res.code.resize(code_size);
-    hiprtcGetCode(prog, res.code.data());
-    hiprtcDestroyProgram(&prog);
-    res.ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
-    return res;
-}
 
 namespace {
 
@@ -93,69 +30,49 @@ struct Worker {
 std::mutex g_mu;
 std::condition_variable g_cv;
 std::vector<Worker> g_workers;
+int g_kind = -1;
 
-bool write_all(int fd, const void *buf, size_t n)
+// Has this process opened the GPU (KFD or a render node)?  Then it must not exec any more.
+bool gpu_is_open()
 {
-    const char *p = static_cast<const char *>(buf);
-    while (n) {
-        ssize_t w = ::write(fd, p, n);
-        if (w < 0) { if (errno == EINTR) continue; return false; }
-        p += w; n -= size_t(w);
+    DIR *d = opendir("/proc/self/fd");
+    if (!d) return true;   // cannot tell: be careful
+    bool open = false;
+    while (dirent *e = readdir(d)) {
+        if (e->d_name[0] < '0' || e->d_name[0] > '9') continue;
+        char link[64], target[256];
+        snprintf(link, sizeof link, "/proc/self/fd/%s", e->d_name);
+        ssize_t n = readlink(link, target, sizeof target - 1);
+        if (n <= 0) continue;
+        target[n] = '\0';
+        if (strstr(target, "/dev/kfd") || strstr(target, "/dev/dri/")) { open = true; break; }
     }
-    return true;
+    closedir(d);
+    return open;
 }
 
-bool read_all(int fd, void *buf, size_t n)
+std::string worker_executable()
 {
-    char *p = static_cast<char *>(buf);
-    while (n) {
-        ssize_t r = ::read(fd, p, n);
-        if (r < 0) { if (errno == EINTR) continue; return false; }
-        if (r == 0) return false;
-        p += r; n -= size_t(r);
-    }
-    return true;
+    Dl_info info;
+    if (!dladdr(reinterpret_cast<const void *>(&pool_start), &info) || !info.dli_fname) return "";
+    std::string path = info.dli_fname;
+    const size_t slash = path.rfind('/');
+    path = (slash == std::string::npos ? std::string(".") : path.substr(0, slash)) + "/opevo_rtc_worker";
+    return access(path.c_str(), X_OK) == 0 ? path : "";
 }
 
-bool write_str(int fd, const std::string &s)
+void close_other_fds(int keep_a, int keep_b)
 {
-    uint64_t n = s.size();
-    return write_all(fd, &n, sizeof n) && (n == 0 || write_all(fd, s.data(), n));
-}
-
-bool read_str(int fd, std::string &s)
-{
-    uint64_t n = 0;
-    if (!read_all(fd, &n, sizeof n) || n > (uint64_t(1) << 30)) return false;
-    s.resize(n);
-    return n == 0 || read_all(fd, &s[0], n);
-}
-
-[[noreturn]] void worker_main(int req, int resp)
-{
-    // drop every inherited descriptor (device files included) except the two pipe ends
-    if (DIR *d = opendir("/proc/self/fd")) {
-        std::vector<int> fds;
-        while (dirent *e = readdir(d)) {
-            int fd = atoi(e->d_name);
-            if (e->d_name[0] >= '0' && e->d_name[0] <= '9' && fd > 2 && fd != req && fd != resp && fd != dirfd(d))
-                fds.push_back(fd);
-        }
-        closedir(d);
-        for (int fd : fds) ::close(fd);
+    DIR *d = opendir("/proc/self/fd");
+    if (!d) return;
+    std::vector<int> fds;
+    while (dirent *e = readdir(d)) {
+        if (e->d_name[0] < '0' || e->d_name[0] > '9') continue;
+        const int fd = atoi(e->d_name);
+        if (fd > 2 && fd != keep_a && fd != keep_b && fd != dirfd(d)) fds.push_back(fd);
     }
-    signal(SIGPIPE, SIG_IGN);
-    for (;;) {
-        std::string tmpl, defines;
-        if (!read_str(req, tmpl) || !read_str(req, defines)) break;
-        CompileResult r = compile_source(tmpl, defines);
-        int32_t status = r.status;
-        std::string code(r.code.begin(), r.code.end());
-        if (!write_all(resp, &status, sizeof status) || !write_all(resp, &r.ms, sizeof r.ms) ||
-            !write_str(resp, code) || !write_str(resp, r.log))
-            break;
-    }
-    _exit(0);   // no atexit handlers, no runtime teardown in the child
+    closedir(d);
+    for (int fd : fds) ::close(fd);
 }
 
 }  // namespace
@@ -168,6 +85,12 @@ int pool_size()
     return n;
 }
 
+int pool_kind()
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_workers.empty() ? -1 : g_kind;
+}
+
 int pool_start(int n)
 {
     std::lock_guard<std::mutex> lock(g_mu);
@@ -176,19 +99,36 @@ int pool_start(int n)
     if (alive > 0 || n <= 0) return alive;
     if (n > 64) n = 64;
     signal(SIGPIPE, SIG_IGN);
+    const std::string exe = gpu_is_open() ? std::string() : worker_executable();
+    g_kind = exe.empty() ? 0 : 1;
     for (int i = 0; i < n; ++i) {
         int req[2], resp[2];
         if (pipe(req) != 0) break;
         if (pipe(resp) != 0) { ::close(req[0]); ::close(req[1]); break; }
-        pid_t pid = fork();
+        const pid_t pid = fork();
         if (pid < 0) { ::close(req[0]); ::close(req[1]); ::close(resp[0]); ::close(resp[1]); break; }
         if (pid == 0) {
             ::close(req[1]); ::close(resp[0]);
-            worker_main(req[0], resp[1]);
+            close_other_fds(req[0], resp[1]);
+            if (!exe.empty()) {
+                // the worker executable talks on descriptors 3 (requests) and 4 (responses)
+                int a = dup(req[0]), b = dup(resp[1]);      // move out of the way of 3 and 4
+                while (a <= 4) a = dup(a);
+                while (b <= 4) b = dup(b);
+                dup2(a, 3); dup2(b, 4);
+                close_other_fds(3, 4);
+                char *const argv[] = {const_cast<char *>(exe.c_str()), nullptr};
+                execv(exe.c_str(), argv);
+                _exit(127);
+            }
+            serve_compile_requests(req[0], resp[1]);
+            _exit(0);   // no atexit handlers, no runtime teardown in the child
         }
         ::close(req[0]); ::close(resp[1]);
         Worker w;
         w.pid = pid; w.to = req[1]; w.from = resp[0];
+        fcntl(w.to, F_SETFD, FD_CLOEXEC);
+        fcntl(w.from, F_SETFD, FD_CLOEXEC);
         g_workers.push_back(w);
     }
     return int(g_workers.size());
@@ -269,6 +209,13 @@ int opevo_compile_pool_start(int n_workers, int *n_running)
 int opevo_compile_pool_stop(void)
 {
     opevo::pool_stop();
+    return OPEVO_OK;
+}
+
+int opevo_compile_pool_kind(int *kind)
+{
+    if (!kind) return opevo::fail(OPEVO_E_ARG, "compile_pool_kind: NULL argument");
+    *kind = opevo::pool_kind();
     return OPEVO_OK;
 }
 
