@@ -106,6 +106,7 @@ def main() -> int:
 
     # ---- the dominant kernel (the best configuration found), re-measured live with HIP events
     roofline = None
+    ceiling = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream) if dtype != "f32" else None
     if best > 0:
         kernel, _ = P.opevo_kernel_build(op, variant, res["best_cfg"])
         ms, _ = P.opevo_kernel_time(kernel, da.data_ptr(), db.data_ptr(), dc.data_ptr(), stream,
@@ -114,7 +115,9 @@ def main() -> int:
         achieved = flops / (ms * 1e-3) * 1e-12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": None,
-                    "kernel_ms": round(ms, 5), "kernel": "best configuration of this run"}
+                    "kernel_ms": round(ms, 5), "kernel": "best configuration of this run",
+                    "mfma_only_ceiling": round(ceiling, 1) if ceiling else None,
+                    "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}
 
     out = {
         "metric": "best-found TFLOP/s after K OpEvo trials (and fraction of bf16 dense MFMA peak)",
@@ -128,7 +131,7 @@ def main() -> int:
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),
                    "n_invalid": int(res["n_invalid"]), "n_compile_fail": int(res["n_compile_fail"]),
                    "n_parity_fail": int(res["n_parity_fail"]), "parity_gate": sample,
-                   "timing": "median of 5 samples, each >= 200 us of back-to-back launches, inputs cache-warm"},
+                   "timing": "per trial: 25 ms warm-up, then median of 5 back-to-back samples of >= 200 us; inputs cache-warm"},
         "roofline": roofline,
         "cpu_baseline": {"value": round(oracle_flops / oracle_s * 1e-12, 6), "unit": "TFLOP/s", "cores": threads,
                          "kind": "oracle", "sample": sample, "seconds": round(oracle_s, 2), "host_cores_visible": cores},

@@ -189,7 +189,8 @@ int opevo_op_space(const opevo_op *op, int variant, opevo_space **out);
 
 typedef struct {
     int32_t status;        /* OPEVO_OK or OPEVO_E_INVALID                                      */
-    int32_t path;          /* 0 scalar FMA, 1 MFMA 32x32x16, 2 MFMA 16x16x32                   */
+    int32_t path;          /* 0 scalar FMA, 1 MFMA 32x32x16, 2 MFMA 16x16x32, 3 MFMA 32x32x16 with
+                              operands streamed global -> LDS directly                         */
     int32_t grid[3];
     int32_t block;         /* threads per workgroup                                            */
     int32_t lds_bytes;
@@ -233,16 +234,28 @@ int opevo_kernel_resources(opevo_kernel *kernel, int *vgprs, int *sgprs, int *sp
  * tensor [Cout,Cin,Hk,Wk], b = the image [B,Cin,H,W].  Asynchronous. */
 int opevo_kernel_launch(opevo_kernel *kernel, const void *a, const void *b, void *c, void *stream);
 /* Timing (Sec. 3: f = TFLOP/s): `warmup` untimed launches (the first of them is itself
- * timed, to size a sample), then `samples` samples of `launches_per_sample` back-to-back
- * launches bracketed by two hipEvents on `stream`; ms per launch of each sample into
+ * timed, to size a sample, and followed by a synchronisation), then `samples` samples of
+ * `launches_per_sample` launches each; warm-ups and samples are enqueued back to back with
+ * one hipEvent between consecutive samples on `stream` and a single synchronisation at the
+ * end, so the GPU never idles inside the measurement.  ms per launch of each sample into
  * samples_ms (may be NULL), median into *median_ms.  launches_per_sample <= 0: chosen so that
  * one sample spans at least 200 us.  A launch of 50 ms or more is taken as the measurement
- * on its own.  timeout_ms > 0 gives scalar-template kernels a deadline per sample: one that
- * is still running then winds down by itself (every workgroup leaves at its next K slab) and
- * the call returns OPEVO_E_INVALID; 0 = no deadline.  Synchronises `stream`. */
+ * on its own.  warmup_ms > 0 extends the warm-up until that much GPU time has been spent
+ * (at most 4000 launches): after idling the device needs tens of milliseconds to reach its
+ * sustained clocks, and a sample taken earlier under-reports the kernel by up to a quarter.
+ * timeout_ms > 0 gives scalar-template kernels a deadline of timeout_ms per
+ * launch: one that is still running then winds down by itself (every workgroup leaves at its
+ * next K slab) and the call returns OPEVO_E_INVALID; 0 = no deadline.  Synchronises `stream`. */
 int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *c, void *stream,
-                      int warmup, int launches_per_sample, int samples, double timeout_ms,
-                      double *median_ms, double *samples_ms);
+                      int warmup, double warmup_ms, int launches_per_sample, int samples,
+                      double timeout_ms, double *median_ms, double *samples_ms);
+
+/* The matrix-pipe ceiling this device sustains: TFLOP/s of a kernel that only issues
+ * 32x32x16 MFMAs of the given input type (OPEVO_BF16 / OPEVO_F16) on register operands, measured
+ * like any trial after 40 ms of warm-up.  Under its power limit an MI355X sustains well below
+ * the nominal peak; kernel results are best read against both.  Allocates and frees a small
+ * device buffer.  Synchronises `stream`. */
+int opevo_mfma_ceiling(int in_dtype, void *stream, double *tflops);
 
 /* Parity gate: c and ref are DEVICE fp32 arrays of n elements.
  * max_scaled = max |c-ref| / (|ref|+1), rel_fro = ||c-ref||_F / ||ref||_F (0 if both 0).
@@ -273,6 +286,7 @@ typedef struct {
     uint64_t    seed;
     int32_t     compile_threads;   /* concurrent hipRTC instantiations per generation (>= 1)     */
     int32_t     warmup, launches_per_sample, samples;   /* as opevo_kernel_time                  */
+    double      warmup_ms;                              /* as opevo_kernel_time, 0 = none        */
     double      trial_timeout_ms;                       /* as opevo_kernel_time, 0 = none        */
     double      tol_max_scaled, tol_rel_fro;            /* parity gate thresholds                */
     /* optional per-trial logs, each `trials` long (cfg_log: trials*width), may be NULL */

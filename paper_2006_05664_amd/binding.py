@@ -52,7 +52,7 @@ class opevo_tune_args(C.Structure):
                 ("stream", C.c_void_p), ("trials", C.c_int32), ("lambda_", C.c_int32), ("rho", C.c_int32),
                 ("q", C.c_double), ("seed", C.c_uint64), ("compile_threads", C.c_int32),
                 ("warmup", C.c_int32), ("launches_per_sample", C.c_int32), ("samples", C.c_int32),
-                ("trial_timeout_ms", C.c_double), ("tol_max_scaled", C.c_double), ("tol_rel_fro", C.c_double),
+                ("warmup_ms", C.c_double), ("trial_timeout_ms", C.c_double), ("tol_max_scaled", C.c_double), ("tol_rel_fro", C.c_double),
                 ("cfg_log", C.POINTER(C.c_int32)), ("fitness_log", C.POINTER(C.c_double)),
                 ("status_log", C.POINTER(C.c_int32)), ("compile_ms_log", C.POINTER(C.c_double)),
                 ("run_ms_log", C.POINTER(C.c_double)), ("wall_s_log", C.POINTER(C.c_double))]
@@ -125,7 +125,8 @@ _SIGNATURES = {
     "opevo_kernel_code_size": [_vp, C.POINTER(C.c_size_t)],
     "opevo_kernel_resources": [_vp, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)],
     "opevo_kernel_launch": [_vp, _vp, _vp, _vp, _vp],
-    "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
+    "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_double, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
+    "opevo_mfma_ceiling": [C.c_int, _vp, _f64p],
     "opevo_compare_f32": [_vp, _vp, C.c_int64, _vp, _f64p, _f64p],
     "opevo_compare_rows_f32": [_vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _f64p, _f64p],
     "opevo_tune": [_vp, C.c_int, C.POINTER(opevo_tune_args), _i32p, C.POINTER(opevo_tune_result)],
@@ -493,13 +494,19 @@ def opevo_kernel_launch(kernel, a: int, b: int, c: int, stream: int = 0) -> None
 
 
 def opevo_kernel_time(kernel, a: int, b: int, c: int, stream: int = 0, warmup: int = 3,
-                      launches_per_sample: int = 0, samples: int = 5, timeout_ms: float = 0.0
-                      ) -> Tuple[float, np.ndarray]:
+                      launches_per_sample: int = 0, samples: int = 5, timeout_ms: float = 0.0,
+                      warmup_ms: float = 25.0) -> Tuple[float, np.ndarray]:
     med = C.c_double()
     per = np.empty(samples, dtype=np.float64)
-    _check(lib.opevo_kernel_time(kernel, a, b, c, stream, warmup, launches_per_sample, samples, timeout_ms,
+    _check(lib.opevo_kernel_time(kernel, a, b, c, stream, warmup, warmup_ms, launches_per_sample, samples, timeout_ms,
                                  C.byref(med), _dp(per)))
     return med.value, per
+
+
+def opevo_mfma_ceiling(in_dtype: int = OPEVO_BF16, stream: int = 0) -> float:
+    v = C.c_double()
+    _check(lib.opevo_mfma_ceiling(in_dtype, stream, C.byref(v)))
+    return v.value
 
 
 def opevo_compare_f32(c: int, ref: int, n: int, stream: int = 0) -> Tuple[float, float]:
@@ -519,7 +526,7 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                ref_row_index: Optional[int] = None, n_ref_rows: int = 0, ref_row_len: int = 0,
                trials: int = 500, lambda_: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0,
                compile_threads: int = 8, warmup: int = 3, launches_per_sample: int = 0, samples: int = 5,
-               trial_timeout_ms: float = 0.0, tol_max_scaled: float = 2e-2, tol_rel_fro: float = 5e-3) -> dict:
+               warmup_ms: float = 25.0, trial_timeout_ms: float = 0.0, tol_max_scaled: float = 2e-2, tol_rel_fro: float = 5e-3) -> dict:
     """Runs Alg. 1 on the GPU; returns the result struct fields, the best configuration and the
     per-trial logs as numpy arrays."""
     space = opevo_op_space(op, variant)
@@ -534,7 +541,7 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                            ref_row_len=ref_row_len, stream=stream, trials=trials, lambda_=lambda_, rho=rho,
                            q=q, seed=seed, compile_threads=compile_threads, warmup=warmup,
                            launches_per_sample=launches_per_sample, samples=samples,
-                           trial_timeout_ms=trial_timeout_ms, tol_max_scaled=tol_max_scaled, tol_rel_fro=tol_rel_fro,
+                           warmup_ms=warmup_ms, trial_timeout_ms=trial_timeout_ms, tol_max_scaled=tol_max_scaled, tol_rel_fro=tol_rel_fro,
                            cfg_log=_ip(logs["cfg"]), fitness_log=_dp(logs["fitness"]),
                            status_log=_ip(logs["status"]), compile_ms_log=_dp(logs["compile_ms"]),
                            run_ms_log=_dp(logs["run_ms"]), wall_s_log=_dp(logs["wall_s"]))

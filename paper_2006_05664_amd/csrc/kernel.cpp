@@ -57,7 +57,7 @@ int load_kernel(opevo_kernel *k)
         k->module = nullptr; k->fn = nullptr;
         return hip_fail(e, "hipModuleGetFunction");
     }
-    if (k->plan.lds_bytes > 32768) {
+    if (k->plan.path != 3 && k->plan.lds_bytes > 32768) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k->fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, k->plan.lds_bytes);
         if (e != hipSuccess && k->plan.lds_bytes > 65536) return hip_fail(e, "hipFuncSetAttribute(max dynamic LDS)");
@@ -71,13 +71,15 @@ int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStr
 {
     if (int rc = load_kernel(k)) return rc;
     void *args[] = {(void *)&a, (void *)&b, (void *)&c, (void *)&ctl};
+    // the direct-to-LDS template declares its stages statically; the others take dynamic LDS
+    const unsigned dyn_lds = k->plan.path == 3 ? 0u : unsigned(k->plan.lds_bytes);
     HIP_TRY(hipModuleLaunchKernel(k->fn, k->plan.grid[0], k->plan.grid[1], k->plan.grid[2],
-                                  k->plan.block, 1, 1, k->plan.lds_bytes, stream, args, nullptr));
+                                  k->plan.block, 1, 1, dyn_lds, stream, args, nullptr));
     return OPEVO_OK;
 }
 
 int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStream_t stream,
-                int warmup, int launches_per_sample, int samples, double timeout_ms,
+                int warmup, double warmup_ms, int launches_per_sample, int samples, double timeout_ms,
                 double *median_ms, double *samples_ms)
 {
     if (samples < 1) return fail(OPEVO_E_ARG, "kernel_time: samples must be >= 1");
@@ -85,54 +87,79 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
     unsigned long long *ctl = nullptr;
     if (timeout_ms > 0.0 && k->plan.path == 0)
         if (int rc = deadline_ctl(&ctl)) return rc;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    HIP_TRY(hipEventCreate(&e0));
-    hipError_t e = hipEventCreate(&e1);
-    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+    // samples + 1 events: the samples run back to back, without a host round trip (and an idle
+    // GPU) between them; only the first, estimating launch is followed by a synchronisation
+    std::vector<hipEvent_t> ev(size_t(samples) + 1, nullptr);
     int rc = OPEVO_OK;
+    for (auto &e : ev) {
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) { rc = hip_fail(err, "hipEventCreate"); break; }
+    }
     std::vector<double> ms(samples, 0.0);
-    // n back-to-back launches between two events on the caller's stream -> ms per launch
-    auto timed = [&](int n, double *out_ms) -> int {
-        if (ctl)
-            if (int r2 = deadline_arm(ctl, timeout_ms, stream)) return r2;
-        hipError_t err = hipEventRecord(e0, stream);
-        if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
-        for (int i = 0; i < n; ++i)
-            if (int r2 = launch_kernel(k, a, b, c, stream, ctl)) return r2;
-        err = hipEventRecord(e1, stream);
-        if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
-        err = hipEventSynchronize(e1);
-        if (err != hipSuccess) return hip_fail(err, "hipEventSynchronize (kernel fault?)");
+    auto elapsed = [&](hipEvent_t a0, hipEvent_t a1, int n, double *out_ms) -> int {
         float t = 0.f;
-        err = hipEventElapsedTime(&t, e0, e1);
+        hipError_t err = hipEventElapsedTime(&t, a0, a1);
         if (err != hipSuccess) return hip_fail(err, "hipEventElapsedTime");
         *out_ms = double(t) / n;
-        if (ctl) {
-            bool expired = false;
-            if (int r2 = deadline_expired(ctl, stream, &expired)) return r2;
-            if (expired) return fail(OPEVO_E_INVALID, "trial exceeded its %.0f ms deadline", timeout_ms);
-        }
         return OPEVO_OK;
     };
+    auto check_deadline = [&]() -> int {
+        if (!ctl) return OPEVO_OK;
+        bool expired = false;
+        if (int r2 = deadline_expired(ctl, stream, &expired)) return r2;
+        if (expired) return fail(OPEVO_E_INVALID, "trial exceeded its %.0f ms deadline", timeout_ms);
+        return OPEVO_OK;
+    };
+#define EV_TRY(call)                                                        \
+    do {                                                                    \
+        hipError_t err_ = (call);                                           \
+        if (err_ != hipSuccess) { rc = hip_fail(err_, #call); break; }      \
+    } while (0)
     do {
+        if (rc) break;
         // the first launch doubles as warm-up and as the estimate that sizes a sample
         double first = 0.0;
-        if ((rc = timed(1, &first))) break;
+        if (ctl && (rc = deadline_arm(ctl, timeout_ms, stream))) break;
+        EV_TRY(hipEventRecord(ev[0], stream));
+        if ((rc = launch_kernel(k, a, b, c, stream, ctl))) break;
+        EV_TRY(hipEventRecord(ev[1], stream));
+        EV_TRY(hipEventSynchronize(ev[1]));
+        if ((rc = elapsed(ev[0], ev[1], 1, &first))) break;
+        if ((rc = check_deadline())) break;
         if (first >= 50.0) {   // slow member: one launch is measurement enough
             for (int s = 0; s < samples; ++s) ms[s] = first;
             break;
         }
-        for (int i = 1; i < warmup && rc == OPEVO_OK; ++i) rc = launch_kernel(k, a, b, c, stream, ctl);
-        if (rc) break;
         int n = launches_per_sample;
         if (n <= 0) {   // long enough that event resolution and launch gaps do not dominate
             n = int(std::ceil(0.2 / std::max(first, 1e-4)));
             n = std::max(1, std::min(n, 2000));
         }
-        for (int s = 0; s < samples && rc == OPEVO_OK; ++s) rc = timed(n, &ms[s]);
+        // warm-up: at least `warmup` launches and at least warmup_ms of GPU time, so that the
+        // clocks have ramped up before the first sample (they take tens of ms after idling)
+        int n_warm = std::max(0, warmup - 1);
+        if (warmup_ms > 0.0) n_warm = std::max(n_warm, std::min(4000, int(std::ceil(warmup_ms / std::max(first, 1e-4))) - 1));
+        // deadline for everything that follows (warm-ups and all samples together)
+        if (ctl && (rc = deadline_arm(ctl, timeout_ms * (double(samples) * n + n_warm + 1), stream))) break;
+        for (int i = 0; i < n_warm && rc == OPEVO_OK; ++i) rc = launch_kernel(k, a, b, c, stream, ctl);
+        if (rc) break;
+        EV_TRY(hipEventRecord(ev[0], stream));
+        for (int s = 0; s < samples && rc == OPEVO_OK; ++s) {
+            for (int i = 0; i < n && rc == OPEVO_OK; ++i) rc = launch_kernel(k, a, b, c, stream, ctl);
+            if (rc) break;
+            hipError_t err = hipEventRecord(ev[s + 1], stream);
+            if (err != hipSuccess) rc = hip_fail(err, "hipEventRecord");
+        }
+        if (rc) break;
+        hipError_t err = hipEventSynchronize(ev[samples]);
+        if (err != hipSuccess) { rc = hip_fail(err, "hipEventSynchronize (kernel fault?)"); break; }
+        for (int s = 0; s < samples && rc == OPEVO_OK; ++s) rc = elapsed(ev[s], ev[s + 1], n, &ms[s]);
+        if (rc) break;
+        rc = check_deadline();
     } while (0);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
+#undef EV_TRY
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
     if (rc) return rc;
     if (samples_ms) std::memcpy(samples_ms, ms.data(), sizeof(double) * samples);
     std::sort(ms.begin(), ms.end());
@@ -180,6 +207,40 @@ int opevo_kernel_resources(opevo_kernel *k, int *vgprs, int *sgprs, int *spill_b
     return OPEVO_OK;
 }
 
+int opevo_mfma_ceiling(int in_dtype, void *stream_, double *tflops)
+{
+    if (!tflops || (in_dtype != OPEVO_BF16 && in_dtype != OPEVO_F16))
+        return fail(OPEVO_E_ARG, "mfma_ceiling: bf16 or fp16 only");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int blocks = 2048, iters = 2048;
+    std::ostringstream d;
+    d << "-DKERNEL_NAME=opevo_mfma_peak -DIN_DTYPE=" << in_dtype << " -DITERS=" << iters
+      << " -DOP=0 -DBATCH_INNER=1";
+    CompileResult r = pool_compile("mfma_peak", d.str());
+    if (r.status != OPEVO_OK) return fail(r.status, "hipRTC failed for the MFMA ceiling kernel: %s", r.log.c_str());
+    opevo_kernel k;
+    k.code = std::move(r.code);
+    k.name = "opevo_mfma_peak";
+    std::memset(&k.plan, 0, sizeof k.plan);
+    k.plan.path = 1;
+    k.plan.grid[0] = blocks; k.plan.grid[1] = 1; k.plan.grid[2] = 1;
+    k.plan.block = 256;
+    void *buf = nullptr;
+    const size_t in_bytes = 4096 * 2, out_bytes = size_t(blocks) * 256 * 4;
+    HIP_TRY(hipMalloc(&buf, in_bytes + out_bytes));
+    int rc = OPEVO_OK;
+    double ms = 0.0;
+    hipError_t e = hipMemsetAsync(buf, 0, in_bytes + out_bytes, stream);
+    if (e != hipSuccess) rc = hip_fail(e, "hipMemsetAsync");
+    if (!rc)
+        rc = time_kernel(&k, buf, buf, static_cast<char *>(buf) + in_bytes, stream, 3, 40.0, 4, 5, 0.0, &ms, nullptr);
+    if (k.module) (void)hipModuleUnload(k.module);
+    (void)hipFree(buf);
+    if (rc) return rc;
+    *tflops = double(blocks) * 4.0 * 8.0 * iters * 32768.0 / (ms * 1e-3) * 1e-12;
+    return OPEVO_OK;
+}
+
 int opevo_kernel_launch(opevo_kernel *k, const void *a, const void *b, void *c, void *stream)
 {
     if (!k || !a || !b || !c) return fail(OPEVO_E_ARG, "kernel_launch: NULL argument");
@@ -187,11 +248,11 @@ int opevo_kernel_launch(opevo_kernel *k, const void *a, const void *b, void *c, 
 }
 
 int opevo_kernel_time(opevo_kernel *k, const void *a, const void *b, void *c, void *stream,
-                      int warmup, int launches_per_sample, int samples, double timeout_ms,
+                      int warmup, double warmup_ms, int launches_per_sample, int samples, double timeout_ms,
                       double *median_ms, double *samples_ms)
 {
     if (!k || !a || !b || !c) return fail(OPEVO_E_ARG, "kernel_time: NULL argument");
-    return time_kernel(k, a, b, c, static_cast<hipStream_t>(stream), warmup, launches_per_sample, samples,
+    return time_kernel(k, a, b, c, static_cast<hipStream_t>(stream), warmup, warmup_ms, launches_per_sample, samples,
                        timeout_ms, median_ms, samples_ms);
 }
 

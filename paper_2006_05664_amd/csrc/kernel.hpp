@@ -30,7 +30,7 @@ int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStr
 // timeout_ms > 0 arms the deadline of the scalar template: a launch still running after that
 // long winds down and the call returns OPEVO_E_INVALID.
 int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStream_t stream,
-                int warmup, int launches_per_sample, int samples, double timeout_ms,
+                int warmup, double warmup_ms, int launches_per_sample, int samples, double timeout_ms,
                 double *median_ms, double *samples_ms);
 // Deadline control block (device memory, one per device, library-owned).
 int deadline_ctl(unsigned long long **ctl);

@@ -144,6 +144,21 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
     }
     const bool stage_lds = !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
+    // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
+    // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.
+    int nstage_dlds = 0;
+    if (path == 1 && flagv == 1 && stage_lds && op.kind != OPEVO_CONV2D && 64 * WM * WN <= kMaxThreads) {
+        const int64_t nw = WM * WN;
+        const bool bk_ok = (BK == 32 || BK == 64 || BK == 128);
+        const bool bn_ok = (BN % 128 == 0 || BN == 64 || BN == 32);
+        const bool split_ok = (BM * BK * 2) % (1024 * nw) == 0 && (BK * BN * 2) % (1024 * nw) == 0;
+        if (bk_ok && bn_ok && split_ok) {
+            const int64_t per = (BM * BK * 2 + BK * BN * 2) / (1024 * nw);
+            for (int st = 4; st >= 2; --st)
+                if (st * (BM + BN) * BK * 2 <= kMaxLds && (st - 2) * per <= 63) { nstage_dlds = st; break; }
+        }
+        if (nstage_dlds) path = 3;
+    }
 
     int64_t NT;
     if (four_level) NT = 64 * WM * WN;
@@ -152,9 +167,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         if (NT > 256) NT = 256;
     }
     int64_t acc = (path == 0) ? (BM * BN + NT - 1) / NT : (TM * TN) / 64;
-    const int nstage = (path != 0 && flagv && ksteps > 1) ? 2 : 1;
+    const int nstage = path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
+    else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BK + kPad) * 2;
 
     p.path = path;
@@ -171,7 +187,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (lds + (path == 0 ? 16 : 0) > kMaxLds)   // the scalar template adds a static flag word
         invalid(p, "%ld bytes of LDS > %ld", long(lds), long(kMaxLds));
     else if (m1 > 65535 || b1 > 65535) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
-    else if (path != 0 && stage_lds) {
+    else if (path != 0 && path != 3 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
         const int64_t a_chunks = (BM * (BK / 8) + NT - 1) / NT;
         const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BK / 8) + NT - 1) / NT
@@ -180,7 +196,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             invalid(p, "%ld staging registers per lane > 256", long((a_chunks + b_chunks) * 4));
     }
 
-    out.tmpl = path == 0 ? "gemm_scalar" : "gemm_mfma";
+    out.tmpl = path == 0 ? "gemm_scalar" : path == 3 ? "gemm_mfma_dlds" : "gemm_mfma";
     // one symbol per configuration, so profiles list each instantiated kernel on its own line
     {
         std::ostringstream nm;
@@ -196,9 +212,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
       << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
       << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv;
     if (path != 0) {
-        D << " -DATOM=" << (path == 1 ? 32 : 16) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
+        D << " -DATOM=" << (path == 2 ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
-          << " -DNSTAGE=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
+          << " -DNSTAGE=" << nstage << " -DNSTG=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
     }
     if (op.kind == OPEVO_CONV2D) {
         D << " -DCIN=" << op.cin << " -DHIN=" << op.hin << " -DWIN=" << op.win << " -DHK=" << op.hk

@@ -100,7 +100,7 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
             int status = c.status;
             if (status == OPEVO_OK && rc_final == OPEVO_OK) {
                 const auto t_run = std::chrono::steady_clock::now();
-                status = time_kernel(c.kernel, args->a, args->b, args->c, stream, args->warmup,
+                status = time_kernel(c.kernel, args->a, args->b, args->c, stream, args->warmup, args->warmup_ms,
                                      args->launches_per_sample, args->samples, args->trial_timeout_ms, &ms, nullptr);
                 if (status == OPEVO_OK && args->ref) {
                     double mx = 0.0, fro = 0.0;

@@ -97,7 +97,7 @@ class Workload:
         assert mx <= self.tol[0] and fro <= self.tol[1], (label, list(cfg), mx, fro, P.opevo_kernel_defines(self.op, variant, cfg))
         return mx, fro
 
-    def random_valid(self, variant, n, seed, want_paths=(0, 1, 2), max_acc=256):
+    def random_valid(self, variant, n, seed, want_paths=(0, 1, 2, 3), max_acc=256):
         """n seeded random members that the decoder calls valid, spread over the kernel paths."""
         sp = P.opevo_op_space(self.op, variant)
         rng = P.opevo_rng_create(seed)
@@ -161,6 +161,10 @@ MM1_CASES = [
     ("mfma16 single stage", [32, 1, 1, 16, 64, 1, 1, 16, 8, 128, 0]),
     ("mfma 1 wave, ragged slab share", [16, 1, 1, 32, 8, 1, 4, 32, 64, 16, 1]),
     ("mfma 16 waves", [1, 4, 2, 64, 4, 4, 1, 64, 32, 32, 1]),
+    ("direct-to-LDS, 4 stages of 32", [2, 2, 1, 128, 8, 4, 1, 32, 32, 32, 1]),
+    ("direct-to-LDS, slab 128, 2 stages", [4, 2, 2, 32, 8, 2, 2, 32, 8, 128, 1]),
+    ("direct-to-LDS, 64-wide tile, 1 wave", [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1]),
+    ("direct-to-LDS, 2 stages of 128", [4, 2, 1, 64, 8, 2, 1, 64, 8, 128, 1]),
     ("scalar fallback", [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1]),
     ("scalar fallback thin", [512, 1, 1, 1, 1, 1, 1, 1024, 128, 8, 0]),
     ("scalar odd K slab", [16, 2, 4, 4, 32, 2, 4, 4, 1024, 1, 1]),
@@ -209,7 +213,9 @@ def test_degenerate_sizes(torch_cuda):
 
 # ------------------------------------------------------------------ config 3: BMM 128 x (128x64 . 64x128)
 BMM_CASES = [
-    ("lds, 2 batches per workgroup", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1]),
+    ("lds (direct), 2 batches per workgroup", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1]),
+    ("lds (direct), 4 batches, 2 slabs of 32", [32, 4, 1, 2, 2, 32, 1, 1, 4, 32, 2, 32, 1]),
+    ("lds register-staged, 2 batches", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 4, 16, 1]),
     ("direct from global", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0]),
     ("lds, two slabs", [128, 1, 1, 2, 2, 32, 1, 2, 1, 64, 2, 32, 1]),
     ("mfma16 direct", [32, 4, 4, 2, 1, 16, 2, 2, 2, 16, 1, 64, 0]),
@@ -307,7 +313,7 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
              ("256x128 tile, 8 waves", [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1]),
              ("128x128 single stage", [64, 2, 2, 32, 64, 2, 1, 64, 128, 64, 0]),
              ("mfma16 32x64 tile", [256, 2, 1, 16, 128, 2, 1, 32, 128, 64, 1])]
-    for cfg in w.random_valid(P.OPEVO_TILE4, 4, seed=606, want_paths=(1, 2)):
+    for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(1, 2, 3)):
         cases.append(("random", list(cfg)))
     for label, cfg in cases:
         _say("  case 8192^3 %s cfg=%s" % (label, list(map(int, cfg))))
@@ -372,6 +378,12 @@ def test_kernel_time_and_deadline(torch_cuda):
     assert med > 0
     P.opevo_kernel_destroy(k)
     w.close()
+
+
+def test_mfma_ceiling_is_plausible(torch_cuda):
+    t = P.opevo_mfma_ceiling(P.OPEVO_BF16, torch_cuda.cuda.current_stream().cuda_stream)
+    _say("  MFMA-only ceiling %.0f TFLOP/s" % t)
+    assert 500.0 < t < 2600.0          # nominal dense bf16 peak is 2500
 
 
 def test_tune_runs_alg1_on_the_gpu_with_parity_gate(torch_cuda):

@@ -91,7 +91,7 @@ def test_four_level_spaces_cover_the_output_once_and_are_not_mostly_invalid(kd):
             n_mfma += plan.path != 0
             assert plan.block <= 1024 and plan.lds_bytes <= 160 * 1024 and plan.acc_per_lane <= 256
             if plan.path:
-                atom = 32 if plan.path == 1 else 16
+                atom = 16 if plan.path == 2 else 32
                 assert plan.wave_tile[0] % atom == 0 and plan.wave_tile[1] % atom == 0
         else:
             assert plan.reason
@@ -102,11 +102,14 @@ def test_four_level_spaces_cover_the_output_once_and_are_not_mostly_invalid(kd):
 
 COMPILE_CASES = [
     ("scalar f32 two-level", (P.OPEVO_MATMUL, (64, 64, 64)), P.OPEVO_F32, P.OPEVO_TILE2, [8, 8, 4, 16, 2, 32], 0),
-    ("mfma 32x32 double-buffered", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1], 1),
+    ("mfma 32x32 register-staged double buffer", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 64, 16, 1], 1),
+    ("mfma 32x32 direct-to-LDS", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1], 3),
+    ("mfma 32x32 direct-to-LDS fp16, 2 stages", MM1, P.OPEVO_F16, P.OPEVO_TILE4, [4, 2, 1, 64, 8, 2, 1, 64, 8, 128, 1], 3),
     ("mfma 16x16 single stage", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 0], 2),
-    ("mfma fp16", MM1, P.OPEVO_F16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 32, 32, 1], 1),
+    ("mfma fp16", MM1, P.OPEVO_F16, P.OPEVO_TILE4, [2, 2, 2, 64, 8, 2, 2, 32, 32, 32, 0], 1),
     ("scalar fallback bf16", MM1, P.OPEVO_BF16, P.OPEVO_TILE4, [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1], 0),
-    ("bmm lds", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1], 1),
+    ("bmm lds direct", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1], 3),
+    ("bmm lds register-staged", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 4, 16, 1], 1),
     ("bmm direct", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0], 1),
     ("conv mfma", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1], 2),
     ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
