@@ -8,7 +8,7 @@ evaluates exactly K trials of one OpEvo run (lambda = rho = 8, q = 0.5) after `-
 untimed trials of a throw-away run.  Inputs are seeded, synthetic and resident in HBM before
 the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps 200] [--warmup 8] [--workload mm8192_bf16] [--seed 0]
+    python bench.py [--gpus 1] [--steps 400] [--warmup 8] [--workload mm8192_bf16] [--seed 0]
 """
 import argparse
 import json
@@ -26,12 +26,17 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}   # MI355X dense MFM
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mm8192_bf16")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=96, help="rows of C the CPU oracle computes (8192^3 only)")
     ap.add_argument("--timeout-ms", type=float, default=300.0, help="deadline of a scalar-template trial")
+    ap.add_argument("--traffic", default=None,
+                    help="measured HBM bytes per launch of the dominant kernel, 'fetch,write' (from counter runs)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
+                         "known-size reference that scales the HBM counters of a profiler run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: trials are timed one at a time on a single MI355X; "
@@ -90,6 +95,12 @@ def main() -> int:
                             warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=args.timeout_ms,
                             tol_max_scaled=tol[0], tol_rel_fro=tol[1])
 
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.neg(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if args.warmup > 0:
         tune(args.warmup, seed=args.seed + 7919)
     torch.cuda.synchronize()
@@ -106,17 +117,26 @@ def main() -> int:
 
     # ---- the dominant kernel (the best configuration found), re-measured live with HIP events
     roofline = None
-    ceiling = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream) if dtype != "f32" else None
+    ceiling = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=True) if dtype != "f32" else None
+    ceiling0 = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=False) if dtype != "f32" else None
     if best > 0:
         kernel, _ = P.opevo_kernel_build(op, variant, res["best_cfg"])
         ms, _ = P.opevo_kernel_time(kernel, da.data_ptr(), db.data_ptr(), dc.data_ptr(), stream,
                                     warmup=3, launches_per_sample=20, samples=3)
         P.opevo_kernel_destroy(kernel)
         achieved = flops / (ms * 1e-3) * 1e-12
+        defines = P.opevo_kernel_defines(op, variant, res["best_cfg"])
+        kname = next((d.split("=", 1)[1] for d in defines.split() if d.startswith("-DKERNEL_NAME=")), "?")
+        traffic = None
+        if args.traffic:
+            fetch, write = (float(x) for x in args.traffic.split(","))
+            traffic = {"fetch_bytes": fetch, "write_bytes": write, "total_bytes": fetch + write,
+                       "algorithmic_bytes": P.opevo_op_bytes(op)}
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": None,
-                    "kernel_ms": round(ms, 5), "kernel": "best configuration of this run",
+                    "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": traffic,
+                    "kernel_ms": round(ms, 5), "kernel": kname,
                     "mfma_only_ceiling": round(ceiling, 1) if ceiling else None,
+                    "mfma_only_ceiling_zero_operands": round(ceiling0, 1) if ceiling0 else None,
                     "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}
 
     out = {

@@ -252,10 +252,13 @@ int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *
 
 /* The matrix-pipe ceiling this device sustains: TFLOP/s of a kernel that only issues
  * 32x32x16 MFMAs of the given input type (OPEVO_BF16 / OPEVO_F16) on register operands, measured
- * like any trial after 40 ms of warm-up.  Under its power limit an MI355X sustains well below
- * the nominal peak; kernel results are best read against both.  Allocates and frees a small
- * device buffer.  Synchronises `stream`. */
-int opevo_mfma_ceiling(int in_dtype, void *stream, double *tflops);
+ * like any trial after 40 ms of warm-up.  random_data = 0: all operands zero (no operand bit
+ * toggles: the clock stays near its maximum and the result near the nominal peak);
+ * random_data != 0: operands uniform in (-1, 1), as a workload's are (the device then lowers its
+ * clock to stay inside its power limit, and this is the ceiling a real kernel is up against).
+ * Kernel results are best read against both.  Allocates and frees a small device buffer.
+ * Synchronises `stream`. */
+int opevo_mfma_ceiling(int in_dtype, int random_data, void *stream, double *tflops);
 
 /* Parity gate: c and ref are DEVICE fp32 arrays of n elements.
  * max_scaled = max |c-ref| / (|ref|+1), rel_fro = ||c-ref||_F / ||ref||_F (0 if both 0).

@@ -126,7 +126,7 @@ _SIGNATURES = {
     "opevo_kernel_resources": [_vp, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)],
     "opevo_kernel_launch": [_vp, _vp, _vp, _vp, _vp],
     "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_double, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
-    "opevo_mfma_ceiling": [C.c_int, _vp, _f64p],
+    "opevo_mfma_ceiling": [C.c_int, C.c_int, _vp, _f64p],
     "opevo_compare_f32": [_vp, _vp, C.c_int64, _vp, _f64p, _f64p],
     "opevo_compare_rows_f32": [_vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _f64p, _f64p],
     "opevo_tune": [_vp, C.c_int, C.POINTER(opevo_tune_args), _i32p, C.POINTER(opevo_tune_result)],
@@ -503,9 +503,9 @@ def opevo_kernel_time(kernel, a: int, b: int, c: int, stream: int = 0, warmup: i
     return med.value, per
 
 
-def opevo_mfma_ceiling(in_dtype: int = OPEVO_BF16, stream: int = 0) -> float:
+def opevo_mfma_ceiling(in_dtype: int = OPEVO_BF16, stream: int = 0, random_data: bool = True) -> float:
     v = C.c_double()
-    _check(lib.opevo_mfma_ceiling(in_dtype, stream, C.byref(v)))
+    _check(lib.opevo_mfma_ceiling(in_dtype, 1 if random_data else 0, stream, C.byref(v)))
     return v.value
 
 

@@ -207,7 +207,7 @@ int opevo_kernel_resources(opevo_kernel *k, int *vgprs, int *sgprs, int *spill_b
     return OPEVO_OK;
 }
 
-int opevo_mfma_ceiling(int in_dtype, void *stream_, double *tflops)
+int opevo_mfma_ceiling(int in_dtype, int random_data, void *stream_, double *tflops)
 {
     if (!tflops || (in_dtype != OPEVO_BF16 && in_dtype != OPEVO_F16))
         return fail(OPEVO_E_ARG, "mfma_ceiling: bf16 or fp16 only");
@@ -226,12 +226,31 @@ int opevo_mfma_ceiling(int in_dtype, void *stream_, double *tflops)
     k.plan.grid[0] = blocks; k.plan.grid[1] = 1; k.plan.grid[2] = 1;
     k.plan.block = 256;
     void *buf = nullptr;
-    const size_t in_bytes = 4096 * 2, out_bytes = size_t(blocks) * 256 * 4;
+    const size_t in_elems = 6 * 256 * 8, in_bytes = in_elems * 2, out_bytes = size_t(blocks) * 256 * 4;
     HIP_TRY(hipMalloc(&buf, in_bytes + out_bytes));
     int rc = OPEVO_OK;
     double ms = 0.0;
     hipError_t e = hipMemsetAsync(buf, 0, in_bytes + out_bytes, stream);
     if (e != hipSuccess) rc = hip_fail(e, "hipMemsetAsync");
+    if (!rc && random_data) {
+        // uniform values in (-1, 1): random sign, exponent and mantissa bits, as a workload's operands have
+        std::vector<uint16_t> host(in_elems);
+        Rng rng(0x5eed);
+        for (auto &h : host) {
+            const float v = float(rng.next_double() * 2.0 - 1.0);
+            if (in_dtype == OPEVO_BF16) {
+                uint32_t u;
+                std::memcpy(&u, &v, 4);
+                h = uint16_t((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+            } else {
+                const _Float16 f = _Float16(v);
+                std::memcpy(&h, &f, 2);
+            }
+        }
+        e = hipMemcpyAsync(buf, host.data(), in_bytes, hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) rc = hip_fail(e, "hipMemcpyAsync");
+    }
     if (!rc)
         rc = time_kernel(&k, buf, buf, static_cast<char *>(buf) + in_bytes, stream, 3, 40.0, 4, 5, 0.0, &ms, nullptr);
     if (k.module) (void)hipModuleUnload(k.module);

@@ -16,10 +16,11 @@
 //    are read with the transposing LDS load: in each group of 16 lanes, lane s supplies the
 //    address of 4 consecutive n at row k + s/4, and lane i receives the 4 consecutive k of
 //    column n0 + i (two such reads per fragment).
+//  * Fragment reads run one MFMA step ahead of the MFMAs, across slab boundaries as well, so
+//    no LDS latency is exposed after a barrier.
 //  * The waits are explicit: s_waitcnt vmcnt(n) with n = the loads this wave issued after the
 //    slab it needs, then a bare s_barrier (the fence of __syncthreads() would drain every
-//    outstanding load).  Each stage is its own LDS object so that the compiler can tell that
-//    loads landing in one stage do not alias the fragment reads of another.
+//    outstanding load).
 
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
@@ -31,7 +32,6 @@ typedef __attribute__((ext_vector_type(8))) _Float16 frag_t;
 typedef __attribute__((ext_vector_type(4))) short v4s;
 typedef __attribute__((ext_vector_type(8))) short v8s;
 typedef f32x16 acc_t;
-#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 constexpr int NW = NT / 64;
 constexpr int MI = TM / 32, NI = TN / 32;
@@ -48,7 +48,20 @@ constexpr int PER = LA + LB;
 __device__ __forceinline__ int a_swz(int row) { return (row / A_RPW) % ACH; }
 __device__ __forceinline__ int b_swz(int krow) { return ((krow / B_RPW) % B_SWM) << 2; }
 
-__device__ __forceinline__ void issue_slab(const u16 *__restrict__ Ab, const u16 *__restrict__ Bb, u16 *stage,
+// One wave-wide 16-byte-per-lane load whose destination is LDS: lane i's 16 bytes land at
+// lds_base + 16 * i (lds_base wave-uniform, passed in M0).  It is written as inline assembly so
+// that the compiler's own wait-count bookkeeping never sees these loads: whenever it loses track
+// of which LDS object such a load fills, it guards later LDS reads with a wait for ALL
+// outstanding loads, which would cut the ring down to a single slab in flight.  The kernel
+// places every wait these loads need itself (WAIT_VMCNT below).
+__device__ __forceinline__ void dma16(const u16 *g, unsigned lds_base)
+{
+    const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+}
+
+// stage: LDS byte address of the stage to fill
+__device__ __forceinline__ void issue_slab(const u16 *__restrict__ Ab, const u16 *__restrict__ Bb, unsigned stage,
                                            int m0, int n0, int k0, int wave, int lane)
 {
 #pragma unroll
@@ -56,14 +69,14 @@ __device__ __forceinline__ void issue_slab(const u16 *__restrict__ Ab, const u16
         const int instr = wave * LA + t;                 // which 1 KiB piece of the A part
         const int p = instr * 64 + lane;                 // 16-byte position this lane fills
         const int row = p / ACH, kc = (p % ACH) ^ a_swz(row);
-        __builtin_amdgcn_global_load_lds(Ab + (long)(m0 + row) * K + k0 + kc * 8, LDS_PTR(stage + instr * 512), 16, 0, 0);
+        dma16(Ab + (long)(m0 + row) * K + k0 + kc * 8, stage + instr * 1024);
     }
 #pragma unroll
     for (int t = 0; t < LB; ++t) {
         const int instr = wave * LB + t;
         const int p = instr * 64 + lane;
         const int krow = p / BCH, c = (p % BCH) ^ b_swz(krow);
-        __builtin_amdgcn_global_load_lds(Bb + (long)(k0 + krow) * N + n0 + c * 8, LDS_PTR(stage + A_STAGE + instr * 512), 16, 0, 0);
+        dma16(Bb + (long)(k0 + krow) * N + n0 + c * 8, stage + (A_STAGE + instr * 512) * 2);
     }
 }
 
@@ -93,7 +106,9 @@ __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], c
 }
 
 // s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at their maxima), gfx9 encoding
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | (0x7 << 4) | (0xf << 8))
+#define VMC(n) ((n) < 63 ? (n) : 63)
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((VMC(n) & 0xf) | ((VMC(n) >> 4) << 14) | (0x7 << 4) | (0xf << 8))
+#define WAIT_LGKM_VMCNT(n) __builtin_amdgcn_s_waitcnt((VMC(n) & 0xf) | ((VMC(n) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
 #define BARRIER() do { asm volatile("" ::: "memory"); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
 #define KCLAMP(k) ((k) < KSTEPS ? (k) : KSTEPS - 1)
 
@@ -101,19 +116,9 @@ extern "C" __global__ __launch_bounds__(NT)
 void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
                  unsigned long long *ctl /* deadline control, used by the scalar template only */)
 {
-    __shared__ __attribute__((aligned(1024))) u16 st0[STAGE];
-    __shared__ __attribute__((aligned(1024))) u16 st1[STAGE];
-#if NSTG > 2
-    __shared__ __attribute__((aligned(1024))) u16 st2[STAGE];
-#else
-#define st2 st0
-#endif
-#if NSTG > 3
-    __shared__ __attribute__((aligned(1024))) u16 st3[STAGE];
-#else
-#define st3 st0
-#endif
-    u16 *const stg[4] = {st0, st1, st2, st3};
+    __shared__ __attribute__((aligned(1024))) u16 ring[NSTG * STAGE];
+    u16 *const stg[4] = {ring, ring + STAGE, ring + (NSTG > 2 ? 2 : 0) * STAGE, ring + (NSTG > 3 ? 3 : 0) * STAGE};
+    const unsigned ring_addr = (unsigned)(unsigned long)(__attribute__((address_space(3))) u16 *)ring;   // LDS byte address
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
@@ -133,26 +138,31 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
         if (bi > 0) BARRIER();      // every wave is done reading the previous batch's stages
-        // prologue: slabs 0 .. NSTG-2 in flight, slab 0 landed, its first fragments read
+        // prologue: slabs 0 .. NSTG-1 in flight (one per stage), slab 0 landed, its first fragments read
 #pragma unroll
-        for (int s = 0; s < NSTG - 1; ++s) issue_slab(Ab, Bb, stg[s], m0, n0, KCLAMP(s) * BK, wave, lane);
-        WAIT_VMCNT((NSTG - 2) * PER);
+        for (int s = 0; s < NSTG; ++s) issue_slab(Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(s) * BK, wave, lane);
+        WAIT_VMCNT((NSTG - 1) * PER);
         BARRIER();
         frag_t af[2][MI], bf[2][NI];
         load_frags(af[0], bf[0], stg[0], wm, wn, lane, 0);
 
-        // slab q, resident in stage s
+        // Slab q, resident in stage s.  The fragment reads run one MFMA step ahead of the MFMAs,
+        // across slab boundaries too: before the last step of a slab the wave makes sure slab
+        // q + 1 has landed for everyone, reads that slab's first fragments, and only then issues
+        // the MFMAs of its own last step, which cover the latency of those reads.  At that barrier
+        // every wave holds all of slab q in registers, so stage s is refilled right there.
         auto slab_step = [&](int q, int s) {
-            if (q > 0) {
-                WAIT_VMCNT((NSTG - 2) * PER);   // this wave's part of slab q has landed
-                BARRIER();                       // everyone's has, and the stage of slab q-1 is free
-                load_frags(af[0], bf[0], stg[s], wm, wn, lane, 0);
-            }
-            // refill the stage slab q-1 used (past the end: a redundant copy of the last slab)
-            issue_slab(Ab, Bb, stg[(s + NSTG - 1) % NSTG], m0, n0, KCLAMP(q + NSTG - 1) * BK, wave, lane);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                if (kk + 1 < KK) load_frags(af[(kk + 1) & 1], bf[(kk + 1) & 1], stg[s], wm, wn, lane, kk + 1);
+                if (kk + 1 < KK) {
+                    load_frags(af[(kk + 1) & 1], bf[(kk + 1) & 1], stg[s], wm, wn, lane, kk + 1);
+                } else {
+                    WAIT_LGKM_VMCNT((NSTG - 2) * PER);   // own fragments of this step read, own part of slab q+1 landed
+                    BARRIER();
+                    load_frags(af[0], bf[0], stg[(s + 1) % NSTG], wm, wn, lane, 0);
+                    // past the end: a redundant copy of the last slab
+                    issue_slab(Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(q + NSTG) * BK, wave, lane);
+                }
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
