@@ -22,6 +22,13 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}   # MI355X dense MFMA / fp32 vector peaks
 
+# HBM-side bytes per launch (fetch, write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
+# known-size elementwise pass (profiles/mm8192_bf16_best_kernel_counters.txt), keyed by (workload, BM, BN): the
+# traffic of an MFMA-template member is set by its workgroup tile, not by how the tile is split among waves.
+# --traffic overrides this with the figures of a fresh counter run.
+MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1627718946.0, 268435456.0,
+                                                "opevo_mm4_32_4_16_4_32_4_2_32_256_32_1")}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -34,6 +41,10 @@ def main() -> int:
     ap.add_argument("--timeout-ms", type=float, default=300.0, help="deadline of a scalar-template trial")
     ap.add_argument("--traffic", default=None,
                     help="measured HBM bytes per launch of the dominant kernel, 'fetch,write' (from counter runs)")
+    ap.add_argument("--roofline-cfg", default=None,
+                    help="comma-separated configuration to measure the roofline object on instead of this run's "
+                         "best (for hardware-counter runs, whose per-dispatch overhead perturbs the timings "
+                         "that steer the search)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
                          "known-size reference that scales the HBM counters of a profiler run")
@@ -119,19 +130,26 @@ def main() -> int:
     roofline = None
     ceiling = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=True) if dtype != "f32" else None
     ceiling0 = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=False) if dtype != "f32" else None
-    if best > 0:
-        kernel, _ = P.opevo_kernel_build(op, variant, res["best_cfg"])
+    roof_cfg = [int(x) for x in args.roofline_cfg.split(",")] if args.roofline_cfg else res["best_cfg"]
+    if best > 0 or args.roofline_cfg:
+        kernel, _ = P.opevo_kernel_build(op, variant, roof_cfg)
         ms, _ = P.opevo_kernel_time(kernel, da.data_ptr(), db.data_ptr(), dc.data_ptr(), stream,
                                     warmup=3, launches_per_sample=20, samples=3)
         P.opevo_kernel_destroy(kernel)
         achieved = flops / (ms * 1e-3) * 1e-12
-        defines = P.opevo_kernel_defines(op, variant, res["best_cfg"])
+        defines = P.opevo_kernel_defines(op, variant, roof_cfg)
         kname = next((d.split("=", 1)[1] for d in defines.split() if d.startswith("-DKERNEL_NAME=")), "?")
         traffic = None
+        plan = P.opevo_kernel_plan(op, variant, roof_cfg)
+        measured = MEASURED_TRAFFIC.get((args.workload, int(plan.tile[0]), int(plan.tile[1])))
         if args.traffic:
             fetch, write = (float(x) for x in args.traffic.split(","))
             traffic = {"fetch_bytes": fetch, "write_bytes": write, "total_bytes": fetch + write,
-                       "algorithmic_bytes": P.opevo_op_bytes(op)}
+                       "algorithmic_bytes": P.opevo_op_bytes(op), "source": "--traffic"}
+        elif measured and plan.path != 0:
+            traffic = {"fetch_bytes": measured[0], "write_bytes": measured[1], "total_bytes": measured[0] + measured[1],
+                       "algorithmic_bytes": P.opevo_op_bytes(op),
+                       "source": "rocprofv3 counters of %s (same %dx%d workgroup tile)" % (measured[2], plan.tile[0], plan.tile[1])}
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": traffic,
                     "kernel_ms": round(ms, 5), "kernel": kname,
