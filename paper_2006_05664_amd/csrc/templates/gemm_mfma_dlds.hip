@@ -3,7 +3,7 @@
 //
 // Roles of the tiling factors are those of the register-staged MFMA template: workgroup tile
 // BM x BN, WM x WN waves, per-wave tile TM x TN of 32x32x16 atoms, K consumed in KSTEPS slabs of
-// BK.  What differs is how a slab travels:
+// BK.  What differs is how a slab travels and how the instruction stream is laid out:
 //
 //  * Every wave issues wave-wide 16-byte-per-lane loads whose destination is LDS (1 KiB per
 //    instruction, no registers, no LDS store instructions).  NSTG stages of BM*BK + BK*BN
@@ -16,11 +16,17 @@
 //    are read with the transposing LDS load: in each group of 16 lanes, lane s supplies the
 //    address of 4 consecutive n at row k + s/4, and lane i receives the 4 consecutive k of
 //    column n0 + i (two such reads per fragment).
-//  * Fragment reads run one MFMA step ahead of the MFMAs, across slab boundaries as well, so
-//    no LDS latency is exposed after a barrier.
+//  * One MFMA step (all atoms of the wave tile for 16 k) uses one of two fragment buffer sets;
+//    between its MFMAs the wave issues, one or two at a time, the LDS reads of the next step's
+//    fragments (across slab boundaries too) and, in the last step of a slab, the loads that
+//    refill the stage.  The order is pinned with scheduling barriers: every LDS read and every
+//    load issue sits in the shadow of an MFMA, so a single wave per SIMD can keep its matrix
+//    pipe busy, which in turn allows 128 x 128 wave tiles, the shape with the least LDS traffic
+//    per flop (LDS bandwidth, not the matrix pipe, limits smaller wave tiles).
 //  * The waits are explicit: s_waitcnt vmcnt(n) with n = the loads this wave issued after the
 //    slab it needs, then a bare s_barrier (the fence of __syncthreads() would drain every
 //    outstanding load).
+//  * C is written with non-temporal stores: it is never read again.
 
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
@@ -48,67 +54,77 @@ constexpr int PER = LA + LB;
 __device__ __forceinline__ int a_swz(int row) { return (row / A_RPW) % ACH; }
 __device__ __forceinline__ int b_swz(int krow) { return ((krow / B_RPW) % B_SWM) << 2; }
 
-// One wave-wide 16-byte-per-lane load whose destination is LDS: lane i's 16 bytes land at
-// lds_base + 16 * i (lds_base wave-uniform, passed in M0).  It is written as inline assembly so
-// that the compiler's own wait-count bookkeeping never sees these loads: whenever it loses track
-// of which LDS object such a load fills, it guards later LDS reads with a wait for ALL
-// outstanding loads, which would cut the ring down to a single slab in flight.  The kernel
-// places every wait these loads need itself (WAIT_VMCNT below).
-__device__ __forceinline__ void dma16(const u16 *g, unsigned lds_base)
+// One wave-wide 16-byte-per-lane load whose destination is LDS: lane i's 16 bytes, read from
+// base + off (base wave-uniform, off per lane), land at lds_base + 16 * i (lds_base wave-uniform,
+// passed in M0).  It is written as inline assembly so that the compiler's own wait-count
+// bookkeeping never sees these loads: whenever it loses track of which LDS object such a load
+// fills, it guards later LDS reads with a wait for ALL outstanding loads, which would cut the
+// ring down to a single slab in flight.  The kernel places every wait these loads need itself
+// (WAIT_VMCNT below).
+__device__ __forceinline__ void dma16(const u16 *base, unsigned off, unsigned lds_base)
 {
-    const unsigned m = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
-// stage: LDS byte address of the stage to fill
-__device__ __forceinline__ void issue_slab(const u16 *__restrict__ Ab, const u16 *__restrict__ Bb, unsigned stage,
-                                           int m0, int n0, int k0, int wave, int lane)
+// The 1 KiB piece number `instr` of a stage's A part covers the 16-byte positions
+// p = instr * 64 + lane: row p / ACH, chunk position p % ACH, which holds global chunk
+// (p % ACH) ^ a_swz(row).  Split into a wave-uniform part (first row of the piece) and a per-lane
+// byte offset that repeats every PA pieces, so a wave keeps min(LA, PA) offsets in registers.
+constexpr int lane_period(int per_row, int swz_rows)
 {
-#pragma unroll
-    for (int t = 0; t < LA; ++t) {
-        const int instr = wave * LA + t;                 // which 1 KiB piece of the A part
-        const int p = instr * 64 + lane;                 // 16-byte position this lane fills
-        const int row = p / ACH, kc = (p % ACH) ^ a_swz(row);
-        dma16(Ab + (long)(m0 + row) * K + k0 + kc * 8, stage + instr * 1024);
-    }
-#pragma unroll
-    for (int t = 0; t < LB; ++t) {
-        const int instr = wave * LB + t;
-        const int p = instr * 64 + lane;
-        const int krow = p / BCH, c = (p % BCH) ^ b_swz(krow);
-        dma16(Bb + (long)(k0 + krow) * N + n0 + c * 8, stage + (A_STAGE + instr * 512) * 2);
-    }
+    int p = 1;
+    while ((p * 64) % per_row != 0 || (p * 64 / per_row) % swz_rows != 0) ++p;
+    return p;
+}
+constexpr int PA = lane_period(ACH, A_RPW * ACH), PB = lane_period(BCH, B_RPW * B_SWM);
+constexpr int NA = LA < PA ? LA : PA, NB = LB < PB ? LB : PB;
+
+__device__ __forceinline__ unsigned a_lane_off(int instr, int lane)
+{
+    const int p = instr * 64 + lane, row0 = instr * 64 / ACH, row = p / ACH;
+    return (unsigned)((row - row0) * K + (((p % ACH) ^ a_swz(row)) << 3)) * 2u;
+}
+__device__ __forceinline__ unsigned b_lane_off(int instr, int lane)
+{
+    const int p = instr * 64 + lane, krow0 = instr * 64 / BCH, krow = p / BCH;
+    return (unsigned)((krow - krow0) * N + (((p % BCH) ^ b_swz(krow)) << 3)) * 2u;
 }
 
-__device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], const u16 *stage,
-                                           int wm, int wn, int lane, int kk)
+// stage: LDS byte address of the stage to fill; slot: which share of the slab this wave issues
+// (wave-uniform, in a scalar register); aoff / boff: a_lane_off / b_lane_off of the wave's pieces.
+// piece t (0 .. PER-1) of this wave's share of a slab: the A pieces first, then the B pieces
+__device__ __forceinline__ void issue_piece(int t, const u16 *__restrict__ Ab, const u16 *__restrict__ Bb, unsigned stage,
+                                            int m0, int n0, int k0, int slot, const unsigned (&aoff)[NA],
+                                            const unsigned (&boff)[NB])
 {
-    const u16 *As = stage, *Bs = stage + A_STAGE;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        const int row = wm * TM + i * 32 + (lane & 31);
-        const int kc = kk * 2 + (lane >> 5);
-        af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + row * BK + ((kc ^ a_swz(row)) << 3)));
+    if (t < LA) {
+        const int instr = slot * LA + t;
+        dma16(Ab + (long)(m0 + instr * 64 / ACH) * K + k0, aoff[t % PA], stage + instr * 1024);
+    } else {
+        const int u = t - LA, instr = slot * LB + u;
+        dma16(Bb + (long)(k0 + instr * 64 / BCH) * N + n0, boff[u % PB], stage + (A_STAGE + instr * 512) * 2);
     }
+}
+__device__ __forceinline__ frag_t read_a(const u16 *stage, int wm, int lane, int kk, int i)
+{
+    const int row = wm * TM + i * 32 + (lane & 31);
+    const int kc = kk * 2 + (lane >> 5);
+    return __builtin_bit_cast(frag_t, *(const u32x4 *)(stage + row * BK + ((kc ^ a_swz(row)) << 3)));
+}
+__device__ __forceinline__ v4s read_b_half(const u16 *stage, int wn, int lane, int kk, int j, int r)
+{
     const int s = lane & 15;
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int n = wn * TN + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
-        v4s h[2];
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int krow = kk * 16 + 8 * (lane >> 5) + 4 * r + (s >> 2);
-            const u16 *p = Bs + krow * BN + (((n >> 3) ^ b_swz(krow)) << 3) + (n & 7);
-            h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)p);
-        }
-        bf[j] = __builtin_bit_cast(frag_t, __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7));
-    }
+    const int n = wn * TN + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const int krow = kk * 16 + 8 * (lane >> 5) + 4 * r + (s >> 2);
+    const u16 *p = stage + A_STAGE + krow * BN + (((n >> 3) ^ b_swz(krow)) << 3) + (n & 7);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)p);
 }
 
 // s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at their maxima), gfx9 encoding
 #define VMC(n) ((n) < 63 ? (n) : 63)
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((VMC(n) & 0xf) | ((VMC(n) >> 4) << 14) | (0x7 << 4) | (0xf << 8))
 #define WAIT_LGKM_VMCNT(n) __builtin_amdgcn_s_waitcnt((VMC(n) & 0xf) | ((VMC(n) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
+#define WAIT_LGKM() __builtin_amdgcn_s_waitcnt(0xf | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
 #define BARRIER() do { asm volatile("" ::: "memory"); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
 #define KCLAMP(k) ((k) < KSTEPS ? (k) : KSTEPS - 1)
 
@@ -117,11 +133,17 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                  unsigned long long *ctl /* deadline control, used by the scalar template only */)
 {
     __shared__ __attribute__((aligned(1024))) u16 ring[NSTG * STAGE];
-    u16 *const stg[4] = {ring, ring + STAGE, ring + (NSTG > 2 ? 2 : 0) * STAGE, ring + (NSTG > 3 ? 3 : 0) * STAGE};
-    const unsigned ring_addr = (unsigned)(unsigned long)(__attribute__((address_space(3))) u16 *)ring;   // LDS byte address
+    const unsigned ring_addr = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long)(__attribute__((address_space(3))) u16 *)ring);   // LDS byte address
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const int slot = uwave;
+    unsigned aoff[NA], boff[NB];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) aoff[t] = a_lane_off(slot * LA + t, lane);
+#pragma unroll
+    for (int t = 0; t < NB; ++t) boff[t] = b_lane_off(slot * LB + t, lane);
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
         const long batch = (long)blockIdx.z * BATCH_INNER + bi;
@@ -137,36 +159,66 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        if (bi > 0) BARRIER();      // every wave is done reading the previous batch's stages
+        if (bi > 0) {               // the previous batch: own loads landed, every wave done reading the stages
+            WAIT_VMCNT(0);
+            BARRIER();
+        }
         // prologue: slabs 0 .. NSTG-1 in flight (one per stage), slab 0 landed, its first fragments read
 #pragma unroll
-        for (int s = 0; s < NSTG; ++s) issue_slab(Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(s) * BK, wave, lane);
+        for (int s = 0; s < NSTG; ++s)
+#pragma unroll
+            for (int t = 0; t < PER; ++t)
+                issue_piece(t, Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(s) * BK, slot, aoff, boff);
         WAIT_VMCNT((NSTG - 1) * PER);
         BARRIER();
-        frag_t af[2][MI], bf[2][NI];
-        load_frags(af[0], bf[0], stg[0], wm, wn, lane, 0);
+        frag_t af[2][MI];
+        v4s bh[2][NI][2];
+        constexpr int NR = MI + 2 * NI;            // fragment reads per MFMA step
+        constexpr int SLOTS = MI * NI;             // MFMAs per step
+        // read number k of the fragments of step (stage, kk) into buffer set b
+        auto frag_read = [&](int b, const u16 *stage, int kk, int k) {
+            if (k == 0) af[b][0] = read_a(stage, wm, lane, kk, 0);
+            else if (k <= 2 * NI) bh[b][(k - 1) / 2][(k - 1) % 2] = read_b_half(stage, wn, lane, kk, (k - 1) / 2, (k - 1) % 2);
+            else af[b][k - 2 * NI] = read_a(stage, wm, lane, kk, k - 2 * NI);
+        };
+#pragma unroll
+        for (int k = 0; k < NR; ++k) frag_read(0, ring, 0, k);
 
-        // Slab q, resident in stage s.  The fragment reads run one MFMA step ahead of the MFMAs,
-        // across slab boundaries too: before the last step of a slab the wave makes sure slab
-        // q + 1 has landed for everyone, reads that slab's first fragments, and only then issues
-        // the MFMAs of its own last step, which cover the latency of those reads.  At that barrier
-        // every wave holds all of slab q in registers, so stage s is refilled right there.
+        // One MFMA step.  Its MFMAs use buffer set kk & 1; between them the wave issues, one or two
+        // at a time, the reads of the next step's fragments and (in the last step of a slab, after
+        // the barrier) the loads that refill the stage.  sched_barrier pins that order.
         auto slab_step = [&](int q, int s) {
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                if (kk + 1 < KK) {
-                    load_frags(af[(kk + 1) & 1], bf[(kk + 1) & 1], stg[s], wm, wn, lane, kk + 1);
-                } else {
-                    WAIT_LGKM_VMCNT((NSTG - 2) * PER);   // own fragments of this step read, own part of slab q+1 landed
-                    BARRIER();
-                    load_frags(af[0], bf[0], stg[(s + 1) % NSTG], wm, wn, lane, 0);
-                    // past the end: a redundant copy of the last slab
-                    issue_slab(Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(q + NSTG) * BK, wave, lane);
+                const bool last = kk + 1 == KK;
+                const int nact = NR + (last ? PER : 0);
+                const u16 *nstage = ring + (last ? (s + 1) % NSTG : s) * STAGE;
+                const int nkk = last ? 0 : kk + 1, nb = (kk + 1) & 1;
+#pragma unroll
+                for (int m = 0; m < SLOTS; ++m) {
+                    const int i = m / NI, j = m % NI;
+                    const frag_t bfr = __builtin_bit_cast(frag_t, __builtin_shufflevector(bh[kk & 1][j][0], bh[kk & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
+                    acc[i][j] = MFMA(af[kk & 1][i], bfr, acc[i][j]);
+                    if (m == 0 && last) {
+                        WAIT_LGKM_VMCNT((NSTG - 2) * PER);
+                        BARRIER();
+                    }
+                    constexpr int UMAX = (NR + PER + SLOTS - 1) / SLOTS + 1;    // most actions behind one MFMA
+                    const int lo = (m * nact + SLOTS - 1) / SLOTS, hi = ((m + 1) * nact + SLOTS - 1) / SLOTS;
+#pragma unroll
+                    for (int u = 0; u < UMAX; ++u) {
+                        const int a = lo + u;
+                        if (a >= hi) continue;
+                        if (!last) frag_read(nb, nstage, nkk, a);
+                        else {
+                            // the last step's actions: the NR reads with the PER loads spread evenly among them
+                            const int nl = a * PER / nact, nl1 = (a + 1) * PER / nact;
+                            if (nl1 > nl) issue_piece(nl, Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(q + NSTG) * BK, slot, aoff, boff);
+                            else frag_read(nb, nstage, nkk, a - nl);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[kk & 1][i], bf[kk & 1][j], acc[i][j]);
             }
         };
         constexpr int KMAIN = KSTEPS / NSTG * NSTG;
@@ -186,7 +238,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4;
-                    Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)] = acc[i][j][r];
+                    __builtin_nontemporal_store(acc[i][j][r], &Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)]);
                 }
     }
 }
