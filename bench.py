@@ -26,8 +26,8 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}   # MI355X dense MFM
 # known-size elementwise pass (profiles/mm8192_bf16_best_kernel_counters.txt), keyed by (workload, BM, BN): the
 # traffic of an MFMA-template member is set by its workgroup tile, not by how the tile is split among waves.
 # --traffic overrides this with the figures of a fresh counter run.
-MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1627718946.0, 268435456.0,
-                                                "opevo_mm4_32_4_16_4_32_4_2_32_256_32_1")}
+MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1610929510.0, 268467018.0,
+                                                "opevo_mm4_32_2_8_16_32_4_2_32_256_32_1")}
 
 
 def main() -> int:
