@@ -77,22 +77,32 @@ def main() -> int:
     # ---- CPU oracle: reference for the parity gate, timed as the reported CPU baseline
     cores = len(os.sched_getaffinity(0))
     threads = oracle_tensor.num_threads()
+    # A sample of C's leading index (rows of a MatMul, batches of a BMM, images of a Conv2d) whenever the
+    # whole fp64 product would take minutes; --oracle-rows sets the sample size of the 8192^3 MatMul.
     t0 = time.perf_counter()
-    if args.workload == "mm8192_bf16":
-        M, N, K = w["dims"]
-        rows = np.sort(np.random.default_rng(4242).choice(M, size=args.oracle_rows, replace=False)).astype(np.int32)
-        ref = oracle_tensor.matmul_rows(a_host, b_host, rows)
-        oracle_flops = 2.0 * rows.size * N * K
-        sample = "%d of %d rows of C (fp64 triple loop, OpenMP over rows)" % (rows.size, M)
-        row_len = N
+    n_lead = w["dims"][0]
+    row_len = n_c // n_lead
+    n_sample = n_lead
+    if flops > 2.0e10:
+        n_sample = args.oracle_rows if w["kind"] == "matmul" else max(1, min(n_lead, int(3.0e9 / (flops / n_lead))))
+    rows = None
+    if n_sample < n_lead:
+        rows = np.sort(np.random.default_rng(4242).choice(n_lead, size=n_sample, replace=False)).astype(np.int32)
+    if w["kind"] == "matmul":
+        ref = oracle_tensor.matmul(a_host, b_host) if rows is None else oracle_tensor.matmul_rows(a_host, b_host, rows)
+        unit = "rows"
+    elif w["kind"] == "bmm":
+        ref = oracle_tensor.bmm(a_host, b_host) if rows is None else oracle_tensor.bmm(a_host[rows], b_host[rows])
+        unit = "batches"
     else:
-        if w["kind"] == "matmul":
-            ref = oracle_tensor.matmul(a_host, b_host)
-        elif w["kind"] == "bmm":
-            ref = oracle_tensor.bmm(a_host, b_host)
-        else:
-            ref = oracle_tensor.conv2d(b_host, a_host, w["dims"][7], w["dims"][8])
-        oracle_flops, sample, rows, row_len = flops, "the whole output", None, 0
+        img = b_host if rows is None else b_host[rows]
+        ref = oracle_tensor.conv2d(img, a_host, w["dims"][7], w["dims"][8])
+        unit = "images"
+    oracle_flops = flops * n_sample / n_lead
+    if rows is None:
+        sample, row_len = "the whole output (fp64 plain loops, OpenMP over the outermost index)", 0
+    else:
+        sample = "%d of %d %s of C (fp64 plain loops, OpenMP over the outermost index)" % (n_sample, n_lead, unit)
     oracle_s = time.perf_counter() - t0
     dref = torch.from_numpy(np.ascontiguousarray(ref, dtype=np.float32).ravel()).cuda()
     drows = torch.from_numpy(rows).cuda() if rows is not None else None

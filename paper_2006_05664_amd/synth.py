@@ -67,6 +67,12 @@ WORKLOADS: Dict[str, dict] = {
     "conv56_bf16": dict(kind="conv2d", dims=(1, 64, 56, 56, 64, 3, 3, 1, 1), dtype="bf16", seed=1237),
     "mm8192_bf16": dict(kind="matmul", dims=(8192, 8192, 8192), dtype="bf16", seed=1238, dist="normal"),
     "conv14_bf16": dict(kind="conv2d", dims=(32, 256, 14, 14, 256, 3, 3, 1, 1), dtype="bf16", seed=1239),
+    # the paper's own operator shapes (App. B.1-B.3) with untransposed operands
+    "mm2_bf16": dict(kind="matmul", dims=(512, 4096, 1024), dtype="bf16", seed=1240, dist="normal"),
+    "mm3_bf16": dict(kind="matmul", dims=(512, 1024, 4096), dtype="bf16", seed=1241, dist="normal"),
+    "bmm1_bf16": dict(kind="bmm", dims=(960, 128, 64, 128), dtype="bf16", seed=1242),
+    "c1_bf16": dict(kind="conv2d", dims=(512, 3, 227, 227, 64, 11, 11, 4, 0), dtype="bf16", seed=1243),
+    "c2_bf16": dict(kind="conv2d", dims=(512, 64, 27, 27, 192, 5, 5, 1, 2), dtype="bf16", seed=1244),
 }
 
 

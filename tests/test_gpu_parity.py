@@ -311,6 +311,10 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
     ref_ent = T.matmul_entries(w.a_host, w.b_host, ei, ej)
     cases = [("256x256 tile, 4 waves, double-buffered", [32, 2, 1, 128, 32, 2, 1, 128, 128, 64, 1]),
              ("256x128 tile, 8 waves", [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1]),
+             ("direct-to-LDS 256x256, 4 waves of 128x128, 4 stages of 32", [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1]),
+             ("direct-to-LDS 256x256, 8 waves of 128x64, 4 stages of 32", [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1]),
+             ("direct-to-LDS 256x256, 8 waves of 128x64, 2 stages of 64", [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1]),
+             ("direct-to-LDS 256x256, 16 waves of 64x64", [32, 4, 16, 4, 32, 4, 2, 32, 256, 32, 1]),
              ("128x128 single stage", [64, 2, 2, 32, 64, 2, 1, 64, 128, 64, 0]),
              ("mfma16 32x64 tile", [256, 2, 1, 16, 128, 2, 1, 32, 128, 64, 1])]
     for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(1, 2, 3)):
@@ -327,6 +331,55 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
         colsum = w.a_host.astype(np.float64).sum(axis=0) @ w.b_host.astype(np.float64)
         assert np.max(np.abs(out.astype(np.float64).sum(axis=0) - colsum)) <= 2e-2 * (np.max(np.abs(colsum)) + 1)
     w.close()
+
+
+# ------------------------------------------------------------------ the paper's own operator shapes
+PAPER_SHAPES = [
+    # name, kind, dims, seed, units of the leading index the oracle computes, template paths of the
+    # seeded random members (the scalar template is left out where a bad member would run for
+    # seconds at these sizes), hand-picked members
+    ("MM2", "matmul", (512, 4096, 1024), 1240, 24, (0, 1, 2, 3),
+     [("direct-to-LDS 256x256", [2, 2, 2, 64, 16, 2, 2, 64, 32, 32, 1]), ("mfma16", [16, 2, 1, 16, 64, 2, 1, 32, 16, 64, 1])]),
+    ("MM3", "matmul", (512, 1024, 4096), 1241, 24, (0, 1, 2, 3),
+     [("direct-to-LDS 128x128, slab 64", [4, 2, 2, 32, 8, 2, 2, 32, 64, 64, 1]), ("register-staged", [4, 2, 2, 32, 8, 2, 2, 32, 256, 16, 1])]),
+    ("BMM1", "bmm", (960, 128, 64, 128), 1242, 6, (0, 1, 2, 3),
+     [("direct-to-LDS, 15 grid rows of 64 batches", [15, 64, 2, 1, 2, 32, 1, 1, 1, 64, 2, 64, 1]),
+      ("mfma16, 480 batches per workgroup", [2, 480, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0])]),
+    ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (1, 2), []),
+    # C1's reduction axis 3*11*11 = 363 has no factor 16: only the scalar template applies
+    ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (),
+     [("scalar, 16 x 484 tile", [128, 4, 4, 1, 4, 4, 5, 11, 1, 1, 5, 1, 11, 1, 11, 33, 1])]),
+]
+
+
+def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
+    """MM2, MM3, BMM1, C1, C2 of App. B at full size (multi-prime axes: 960 = 2^6*3*5, 55 = 5*11,
+    27 = 3^3, 192 = 2^6*3, 363 = 3*11^2, 1600 = 2^6*5^2).  The oracle computes a seeded sample of
+    rows / batches / images; the whole output must be finite (NaN pre-fill)."""
+    torch = torch_cuda
+    for name, kind, dims, seed, n_sample, paths, picked in PAPER_SHAPES:
+        w = Workload(torch, kind, dims, "bf16", seed, oracle=False)
+        lead = dims[0]
+        idx = np.sort(np.random.default_rng(seed).choice(lead, size=n_sample, replace=False))
+        _say("  oracle sample for %s %s ..." % (name, dims))
+        if kind == "matmul":
+            ref = T.matmul_rows(w.a_host, w.b_host, idx)
+        elif kind == "bmm":
+            ref = T.bmm(w.a_host[idx], w.b_host[idx])
+        else:
+            ref = T.conv2d(w.b_host[idx], w.a_host, dims[7], dims[8])
+        cases = [(label, cfg) for label, cfg in picked]
+        if paths:
+            cases += [("random", list(c)) for c in w.random_valid(P.OPEVO_TILE4, 4, seed=seed + 1, want_paths=paths)]
+        for label, cfg in cases:
+            plan = P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg)
+            assert plan.status == P.OPEVO_OK, (name, label, cfg, plan.reason)
+            _say("  case %s %s path %d cfg=%s" % (name, label, plan.path, list(map(int, cfg))))
+            out = w.run(P.OPEVO_TILE4, cfg).reshape(lead, -1)
+            assert np.all(np.isfinite(out)), (name, label)
+            mx, fro = errors(out[idx].ravel(), np.asarray(ref).ravel())
+            assert mx <= TOL16[0] and fro <= TOL16[1], (name, label, cfg, mx, fro)
+        w.close()
 
 
 # ------------------------------------------------------------------ harness pieces
