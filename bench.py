@@ -38,7 +38,9 @@ def main() -> int:
     ap.add_argument("--workload", default="mm8192_bf16")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=96, help="rows of C the CPU oracle computes (8192^3 only)")
-    ap.add_argument("--timeout-ms", type=float, default=300.0, help="deadline of a scalar-template trial")
+    ap.add_argument("--timeout-ms", type=float, default=0.0,
+                    help="deadline of a scalar-template launch; 0 = 300 ms scaled by the workload's flops relative "
+                         "to the 8192^3 MatMul, at least 10 ms")
     ap.add_argument("--traffic", default=None,
                     help="measured HBM bytes per launch of the dominant kernel, 'fetch,write' (from counter runs)")
     ap.add_argument("--roofline-cfg", default=None,
@@ -108,12 +110,14 @@ def main() -> int:
     drows = torch.from_numpy(rows).cuda() if rows is not None else None
     tol = (1e-4, 1e-4) if dtype == "f32" else (2e-2, 5e-3)
 
+    timeout_ms = args.timeout_ms if args.timeout_ms > 0 else max(10.0, 300.0 * flops / (2.0 * 8192.0 ** 3))
+
     def tune(trials, seed):
         return P.opevo_tune(op, variant, da.data_ptr(), db.data_ptr(), dc.data_ptr(), dref.data_ptr(), stream,
                             ref_row_index=drows.data_ptr() if drows is not None else None,
                             n_ref_rows=int(rows.size) if rows is not None else 0, ref_row_len=row_len,
                             trials=trials, lambda_=8, rho=8, q=0.5, seed=seed, compile_threads=8,
-                            warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=args.timeout_ms,
+                            warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=timeout_ms, progress_every=100,
                             tol_max_scaled=tol[0], tol_rel_fro=tol[1])
 
     if args.copy_probe:

@@ -299,6 +299,12 @@ typedef struct {
     double     *compile_ms_log;
     double     *run_ms_log;    /* median ms per launch                                           */
     double     *wall_s_log;    /* seconds since the start of the run when the trial finished     */
+    int32_t     progress_every; /* > 0: after every generation that crosses a multiple of this many
+                                   trials, one line on stderr (trials done, best TFLOP/s, seconds);
+                                   0: silent.  Independently of this, OPEVO_TUNE_TRACE=1 in the
+                                   environment prints one line per trial before its kernel runs
+                                   (kernel name = configuration), so that the log of a run that
+                                   died names what was on the GPU                                   */
 } opevo_tune_args;
 
 typedef struct {

@@ -33,6 +33,13 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     CompileResult r = pool_compile(d.tmpl, d.defines);
     if (r.status != OPEVO_OK)
         return fail(r.status, "hipRTC failed for [%s]: %s", d.defines.c_str(), r.log.c_str());
+    // A direct-to-LDS member whose K loop did not unroll compiles into a code object of hundreds of
+    // KiB (register arrays indexed through select chains); fully unrolled ones take about 20 KiB.
+    // The decoder's size rule should already have kept such members away from this template; one
+    // that slips through is never launched.
+    if (d.plan.path == 3 && r.code.size() > (128u << 10))
+        return fail(OPEVO_E_INVALID, "direct-to-LDS template did not unroll (code object of %zu bytes) [%s]",
+                    r.code.size(), d.defines.c_str());
     opevo_kernel *k = new (std::nothrow) opevo_kernel;
     if (!k) return fail(OPEVO_E_ARG, "out of memory");
     k->code = std::move(r.code);

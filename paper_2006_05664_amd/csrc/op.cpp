@@ -9,6 +9,7 @@ using namespace opevo;
 
 static const int kMaxThreads = 1024;            // threads per workgroup on gfx950
 static const int kMaxLds = 160 * 1024;          // LDS bytes per workgroup on gfx950
+static const int64_t kMaxDldsBody = 256;        // unrolled K-loop body of the direct-to-LDS template, instructions
 static const int kMaxAcc = 256;                 // fp32 accumulators per lane kept in registers
 static const int kPad = 8;                      // LDS row padding of the MFMA template (elements)
 
@@ -156,6 +157,14 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             const int64_t per = (BM * BK * 2 + BK * BN * 2) / (1024 * nw);
             for (int st = 4; st >= 2; --st)
                 if (st * (BM + BN) * BK * 2 <= kMaxLds && (st - 2) * per <= 63) { nstage_dlds = st; break; }
+            // The template keeps accumulators and fragments in register arrays and relies on its K
+            // loop body (one pass over the ring) unrolling completely.  Instructions in that body:
+            // per stage and MFMA step the MFMAs and fragment reads, per stage the loads.  Bodies
+            // past this size were seen not to unroll (code objects of 0.5-1.5 MB instead of 20 KB);
+            // such members use the register-staged template instead.
+            const int64_t mi = TM / 32, ni = TN / 32, kk = BK / 16;
+            const int64_t body = nstage_dlds * (kk * (mi * ni + mi + 2 * ni) + per);
+            if (body > kMaxDldsBody) nstage_dlds = 0;
         }
         if (nstage_dlds) path = 3;
     }

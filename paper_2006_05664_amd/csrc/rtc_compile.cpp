@@ -58,8 +58,13 @@ CompileResult compile_source(const std::string &tmpl, const std::string &defines
         res.log = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
         return res;
     }
+    // -pragma-unroll-threshold: the templates keep accumulators and fragments in register arrays and
+    // mark every loop over them for full unrolling; the compiler's default size limit for such
+    // loops makes it give up on the larger members, which then compile (slowly) into code objects
+    // of megabytes that index those arrays through select chains.
     opts.insert(opts.end(), {"--offload-arch=gfx950", "-O3", "-std=c++17",
-                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"});
+                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                             "-mllvm", "-pragma-unroll-threshold=400000"});
     std::vector<const char *> optv;
     for (const auto &o : opts) optv.push_back(o.c_str());
     r = hiprtcCompileProgram(prog, int(optv.size()), optv.data());

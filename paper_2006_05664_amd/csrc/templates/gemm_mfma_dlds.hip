@@ -229,6 +229,11 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
         for (int s = 0; s < KSTEPS - KMAIN; ++s) slab_step(KMAIN + s, s);
 
+        // The last NSTG slab steps issued loads past the end of K (redundant copies of the last
+        // slab, so that the wait counts stay uniform).  They must have landed before this wave ends:
+        // a load that arrives after the workgroup's LDS has been handed to another workgroup would
+        // write into memory this kernel no longer owns.
+        WAIT_VMCNT(0);
         // Epilogue: an atom's result sits with column (l % 32) in lane l, register r being
         // row 8*(r/4) + 4*(l/32) + r%4.
 #pragma unroll

@@ -4,6 +4,8 @@
 #include <chrono>
 #include <cmath>
 #include <condition_variable>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <thread>
@@ -61,6 +63,10 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
     std::vector<double> fit(gen_cap);
     int done = 0, rc_final = OPEVO_OK;
     double best = 0.0;
+    // OPEVO_TUNE_TRACE=1 in the environment: one line on stderr per trial, before its kernel runs,
+    // so that the log of a run that died names the configuration that was on the GPU
+    const char *trace_env = std::getenv("OPEVO_TUNE_TRACE");
+    const bool trace = trace_env && trace_env[0] && trace_env[0] != '0';
 
     while (done < args->trials) {
         const int n = tuner->ask(cfgs.data(), args->trials - done);
@@ -98,6 +104,12 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
             Child &c = kids[i];
             double tflops = 0.0, ms = 0.0;
             int status = c.status;
+            if (trace) {
+                std::fprintf(stderr, "[opevo_tune] trial %d %s: built (status %d, %.0f ms)%s\n", done + i,
+                             c.kernel ? c.kernel->name.c_str() : "-", status, c.compile_ms,
+                             status == OPEVO_OK ? ", running" : "");
+                std::fflush(stderr);
+            }
             if (status == OPEVO_OK && rc_final == OPEVO_OK) {
                 const auto t_run = std::chrono::steady_clock::now();
                 status = time_kernel(c.kernel, args->a, args->b, args->c, stream, args->warmup, args->warmup_ms,
@@ -151,6 +163,11 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
         result->compile_s += seconds_since(t_compile);
         if (rc_final != OPEVO_OK) break;
         tuner->tell(cfgs.data(), fit.data(), n);
+        if (args->progress_every > 0 && (done + n) / args->progress_every != done / args->progress_every) {
+            std::fprintf(stderr, "[opevo_tune] %d/%d trials, best %.2f TFLOP/s, %d invalid, %.1f s\n", done + n,
+                         args->trials, best, result->n_invalid, seconds_since(t_start));
+            std::fflush(stderr);
+        }
         done += n;
     }
     // compile_s was measured around the whole generation; what is left after the GPU share
