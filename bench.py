@@ -135,6 +135,8 @@ def main() -> int:
     wall = time.perf_counter() - t0
 
     logs = res["logs"]
+    parity_failures = [[int(x) for x in logs["cfg"][i]] for i in range(int(res["n_trials"]))
+                       if int(logs["status"][i]) == P.OPEVO_E_PARITY]
     best = float(res["best_tflops"])
     fit = logs["fitness"]
     trials_to_best = int(res["best_trial"]) + 1
@@ -182,7 +184,7 @@ def main() -> int:
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),
                    "n_invalid": int(res["n_invalid"]), "n_compile_fail": int(res["n_compile_fail"]),
-                   "n_parity_fail": int(res["n_parity_fail"]), "parity_gate": sample,
+                   "n_parity_fail": int(res["n_parity_fail"]), "parity_failures": parity_failures, "parity_gate": sample,
                    "timing": "per trial: 25 ms warm-up, then median of 5 back-to-back samples of >= 200 us; inputs cache-warm"},
         "roofline": roofline,
         "cpu_baseline": {"value": round(oracle_flops / oracle_s * 1e-12, 6), "unit": "TFLOP/s", "cores": threads,

@@ -64,6 +64,20 @@ int load_kernel(opevo_kernel *k)
         k->module = nullptr; k->fn = nullptr;
         return hip_fail(e, "hipModuleGetFunction");
     }
+    if (k->plan.path == 3) {
+        // The direct-to-LDS template counts its own outstanding loads (s_waitcnt vmcnt(n)).  Register
+        // spills would put scratch stores on the same counter, and stores may complete out of order
+        // with loads, so a count could be reached while a slab is still in flight.  A member that
+        // spills is therefore not run (it would be slow anyway).
+        int scratch_bytes = 0;
+        e = hipFuncGetAttribute(&scratch_bytes, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, k->fn);
+        if (e == hipSuccess && scratch_bytes > 0) {
+            (void)hipModuleUnload(k->module);
+            k->module = nullptr; k->fn = nullptr;
+            return fail(OPEVO_E_INVALID, "direct-to-LDS member spills %d bytes of registers per lane", scratch_bytes);
+        }
+        (void)hipGetLastError();
+    }
     if (k->plan.path != 3 && k->plan.lds_bytes > 32768) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k->fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, k->plan.lds_bytes);

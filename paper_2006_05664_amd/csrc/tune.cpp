@@ -138,6 +138,13 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
                     else status = OPEVO_E_INVALID;
                 }
             }
+            if (trace || status == OPEVO_E_PARITY) {
+                std::fprintf(stderr, "[opevo_tune] trial %d %s: status %d, %.3f ms, %.2f TFLOP/s%s%s\n", done + i,
+                             c.kernel ? c.kernel->name.c_str() : "-", status, ms, tflops,
+                             status == OPEVO_E_PARITY ? " PARITY FAILURE: " : "",
+                             status == OPEVO_E_PARITY ? last_error() : "");
+                std::fflush(stderr);
+            }
             if (status == OPEVO_E_INVALID) result->n_invalid++;
             else if (status == OPEVO_E_HIPRTC) result->n_compile_fail++;
             else if (status == OPEVO_E_PARITY) result->n_parity_fail++;

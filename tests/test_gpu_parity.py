@@ -84,7 +84,17 @@ class Workload:
         if own:
             kernel, _ = P.opevo_kernel_build(self.op, variant, cfg)
         self.c.fill_(float("nan"))            # a kernel that skips outputs cannot pass
-        P.opevo_kernel_launch(kernel, self.a.data_ptr(), self.b.data_ptr(), self.c.data_ptr(), self.stream)
+        try:
+            P.opevo_kernel_launch(kernel, self.a.data_ptr(), self.b.data_ptr(), self.c.data_ptr(), self.stream)
+        except P.OpevoError as e:
+            # the one resource rule that needs the compiled kernel: a direct-to-LDS member that spills
+            # registers is invalid (fitness 0) and is never launched
+            if e.status == P.OPEVO_E_INVALID and "spills" in e.message:
+                _say("    (invalid after compilation: %s)" % e.message)
+                if own:
+                    P.opevo_kernel_destroy(kernel)
+                return None
+            raise
         self.torch.cuda.synchronize()
         if own:
             P.opevo_kernel_destroy(kernel)
@@ -93,6 +103,9 @@ class Workload:
     def check(self, variant, cfg, label=""):
         _say("  case %s %s %s cfg=%s" % (self.kind, self.dims, label, list(map(int, cfg))))
         out = self.run(variant, cfg)
+        if out is None:
+            assert label == "random", (label, list(cfg))     # hand-picked members must run
+            return None
         mx, fro = errors(out, self.ref)
         assert mx <= self.tol[0] and fro <= self.tol[1], (label, list(cfg), mx, fro, P.opevo_kernel_defines(self.op, variant, cfg))
         return mx, fro
@@ -160,7 +173,8 @@ MM1_CASES = [
     ("mfma16", [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 1]),
     ("mfma16 single stage", [32, 1, 1, 16, 64, 1, 1, 16, 8, 128, 0]),
     ("mfma 1 wave, ragged slab share", [16, 1, 1, 32, 8, 1, 4, 32, 64, 16, 1]),
-    ("mfma 16 waves", [1, 4, 2, 64, 4, 4, 1, 64, 32, 32, 1]),
+    ("mfma 16 waves of 128x64, double-buffered, slab 16", [1, 4, 4, 32, 4, 4, 1, 64, 64, 16, 1]),
+    ("direct-to-LDS, 16 waves of 64x64", [2, 4, 2, 32, 4, 4, 2, 32, 32, 32, 1]),
     ("direct-to-LDS, 4 stages of 32", [2, 2, 1, 128, 8, 4, 1, 32, 32, 32, 1]),
     ("direct-to-LDS, slab 128, 2 stages", [4, 2, 2, 32, 8, 2, 2, 32, 8, 128, 1]),
     ("direct-to-LDS, 64-wide tile, 1 wave", [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1]),
@@ -321,7 +335,11 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
         cases.append(("random", list(cfg)))
     for label, cfg in cases:
         _say("  case 8192^3 %s cfg=%s" % (label, list(map(int, cfg))))
-        out = w.run(P.OPEVO_TILE4, cfg).reshape(M, N)
+        out = w.run(P.OPEVO_TILE4, cfg)
+        if out is None:
+            assert label == "random", label
+            continue
+        out = out.reshape(M, N)
         assert np.all(np.isfinite(out)), label           # every output written (NaN pre-fill)
         mx, fro = errors(out[rows], ref_rows)
         assert mx <= TOL16[0] and fro <= TOL16[1], (label, cfg, mx, fro)
@@ -375,7 +393,11 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
             plan = P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg)
             assert plan.status == P.OPEVO_OK, (name, label, cfg, plan.reason)
             _say("  case %s %s path %d cfg=%s" % (name, label, plan.path, list(map(int, cfg))))
-            out = w.run(P.OPEVO_TILE4, cfg).reshape(lead, -1)
+            out = w.run(P.OPEVO_TILE4, cfg)
+            if out is None:
+                assert label == "random", (name, label)
+                continue
+            out = out.reshape(lead, -1)
             assert np.all(np.isfinite(out)), (name, label)
             mx, fro = errors(out[idx].ravel(), np.asarray(ref).ravel())
             assert mx <= TOL16[0] and fro <= TOL16[1], (name, label, cfg, mx, fro)
