@@ -126,3 +126,42 @@ def test_templates_compile_for_gfx950(label, kd, dtype, variant, cfg, path):
     assert P.opevo_kernel_code_size(kernel) > 1000 and ms > 0
     assert "-DBM=%d" % plan.tile[0] in P.opevo_kernel_defines(op, variant, cfg)
     P.opevo_kernel_destroy(kernel)
+
+
+def test_direct_to_lds_members_with_large_bodies_use_the_register_staged_template():
+    """The direct-to-LDS template needs its K-loop body to unroll completely; the decoder keeps
+    members whose body estimate exceeds 256 instructions on the register-staged template."""
+    mm2 = _op((P.OPEVO_MATMUL, (512, 4096, 1024)), P.OPEVO_BF16)
+    big = [4, 1, 4, 32, 64, 2, 4, 8, 8, 128, 1]       # 128x64 tile, slab 128, 2 waves: body 3*(8*10+24) = 312
+    plan = P.opevo_kernel_plan(mm2, P.OPEVO_TILE4, big)
+    assert plan.status == P.OPEVO_OK and plan.path == 1
+    mm = _op((P.OPEVO_MATMUL, (8192, 8192, 8192)), P.OPEVO_BF16)
+    for cfg in ([32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1],      # 4 waves of 128x128: 4*(2*28+8) = 256
+                [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1],      # 8 waves of 128x64
+                [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1]):      # slab 64, 2 stages
+        plan = P.opevo_kernel_plan(mm, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == 3, cfg
+
+
+def test_every_sampled_direct_to_lds_member_compiles_to_a_small_code_object():
+    """Full unrolling shows in the size of the code object: about 20 KiB; a member whose loops
+    survive takes hundreds of KiB (and is refused by opevo_kernel_build)."""
+    op = _op((P.OPEVO_MATMUL, (512, 4096, 1024)), P.OPEVO_BF16)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4)
+    rng = P.opevo_rng_create(77)
+    seen, built = set(), 0
+    for _ in range(200000):
+        cfg = P.opevo_space_random(sp, rng)
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        key = (tuple(plan.tile), tuple(plan.wave_tile), plan.block)
+        if plan.status != P.OPEVO_OK or plan.path != 3 or key in seen:
+            continue
+        seen.add(key)
+        kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4, cfg)
+        assert P.opevo_kernel_code_size(kernel) < 128 * 1024, (list(cfg), P.opevo_kernel_code_size(kernel))
+        P.opevo_kernel_destroy(kernel)
+        built += 1
+        if built >= 6:
+            break
+    assert built == 6
+    P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
