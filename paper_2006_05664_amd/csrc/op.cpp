@@ -139,10 +139,19 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
 
     // ---- template choice
     int path = 0;   // scalar
+    int64_t BKP = BK;   // width of a K slab as the MFMA template stages and multiplies it
     if (four_level && op.dtype != OPEVO_F32) {
-        const bool align_ok = (op.K % 8 == 0) && (op.kind == OPEVO_CONV2D || op.N % 8 == 0);
-        if (align_ok && TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0) path = 1;
-        else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
+        if (op.kind == OPEVO_CONV2D) {
+            // The convolution's reduction axis Cin*Hk*Wk rarely has a factor 16 (3*11*11 = 363): a slab
+            // of BK taps is staged zero-padded to the next multiple of the MFMA K step, and its
+            // operands are gathered element by element, so no alignment is asked of it.
+            if (TM % 32 == 0 && TN % 32 == 0) { path = 1; BKP = (BK + 15) / 16 * 16; }
+            else if (TM % 16 == 0 && TN % 16 == 0) { path = 2; BKP = (BK + 31) / 32 * 32; }
+        } else {
+            const bool align_ok = (op.K % 8 == 0) && (op.N % 8 == 0);
+            if (align_ok && TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0) path = 1;
+            else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
+        }
     }
     const bool stage_lds = !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
     // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
@@ -180,7 +189,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
     else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
-    else if (stage_lds) lds = nstage * (BM + BN) * (BK + kPad) * 2;
+    else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2;
 
     p.path = path;
     p.grid[0] = int32_t(n1); p.grid[1] = int32_t(m1); p.grid[2] = int32_t(b1);
@@ -198,8 +207,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (m1 > 65535 || b1 > 65535) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
     else if (path != 0 && path != 3 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
-        const int64_t a_chunks = (BM * (BK / 8) + NT - 1) / NT;
-        const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BK / 8) + NT - 1) / NT
+        const int64_t a_chunks = (BM * (BKP / 8) + NT - 1) / NT;
+        const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BKP / 8) + NT - 1) / NT
                                                            : 8 * (((BK / 8) * (BN / 8) + NT - 1) / NT);
         if ((a_chunks + b_chunks) * 4 > 256)
             invalid(p, "%ld staging registers per lane > 256", long((a_chunks + b_chunks) * 4));
@@ -229,7 +238,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         D << " -DCIN=" << op.cin << " -DHIN=" << op.hin << " -DWIN=" << op.win << " -DHK=" << op.hk
           << " -DWK=" << op.wk << " -DSTRIDE=" << op.stride << " -DPAD_CONV=" << op.pad
           << " -DHOUT=" << op.hout << " -DWOUT=" << op.wout << " -DNB2=" << nb2 << " -DBH=" << BH
-          << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1;
+          << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1 << " -DBKP=" << BKP;
     }
     out.defines = D.str();
     return OPEVO_OK;

@@ -22,6 +22,10 @@
 //           software-pipelined (fragments of the next step are read while this step's MFMAs run).
 // FLAG = 0: one stage, load -> barrier -> compute -> barrier; K loop not unrolled.
 // BMM only, STAGE_LDS = 0: no LDS at all, fragments are read straight from global memory.
+// Conv2d only: the reduction axis Cin*Hk*Wk rarely has a factor 16, so a slab of BK taps is
+//           staged BKP = BK rounded up to the MFMA K step wide, its tail filled with zeros; when
+//           BKP != BK the kernel tensor is read element by element (its rows are not 16-byte
+//           aligned then) with the same bounds as the image gather.
 
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
@@ -43,19 +47,22 @@ typedef f32x4 acc_t;
 #define MFMA(a, b, c) MFMA_16(a, b, c)
 #endif
 
+#ifndef BKP
+#define BKP BK
+#endif
 constexpr int MI = TM / ATOM, NI = TN / ATOM;                 // atoms per wave tile
 constexpr int FMI = (FM % ATOM == 0) ? FM / ATOM : 1;         // atoms per basic tile
 constexpr int FNI = (FN % ATOM == 0) ? FN / ATOM : 1;
-constexpr int LDA = BK + PAD, LDB = BK + PAD;
+constexpr int LDA = BKP + PAD, LDB = BKP + PAD;
 __device__ __forceinline__ int lds_off(int row, int k)   // element offset of (row, k) in a stage
 {
-    return row * (BK + PAD) + k;
+    return row * (BKP + PAD) + k;
 }
 constexpr int A_STAGE = BM * LDA, B_STAGE = BN * LDB;
-constexpr int A_CHUNKS = BM * (BK / 8);                       // 16-byte pieces of the A slab
+constexpr int A_CHUNKS = BM * (BKP / 8);                      // 16-byte pieces of the A slab
 constexpr int NA = (A_CHUNKS + NT - 1) / NT;
 #if OP == OP_CONV
-constexpr int B_CHUNKS = BN * (BK / 8);                       // (column, 8 taps) gathers
+constexpr int B_CHUNKS = BN * (BKP / 8);                      // (column, 8 taps) gathers
 constexpr int KB = 8;
 #else
 // B slab in KB(k) x 8(n) blocks; KB shrinks (8 -> 4 -> 2) until every thread owns a block
@@ -86,8 +93,19 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
-            const int row = q / (BK / 8), kc = q % (BK / 8);
-            s.a[i] = *(const u32x4 *)(Ab + (long)(m0 + row) * K + k0 + kc * 8);
+            const int row = q / (BKP / 8), kc = q % (BKP / 8);
+            if (BKP == BK) {
+                s.a[i] = *(const u32x4 *)(Ab + (long)(m0 + row) * K + k0 + kc * 8);
+            } else {   // padded slab: taps past BK are zeros, rows start at any 2-byte offset
+                u32 h[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    h[t] = (kc * 8 + t < BK) ? (u32)Ab[(long)(m0 + row) * K + k0 + kc * 8 + t] : 0u;
+                u32x4 v;
+                v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
+                v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+                s.a[i] = v;
+            }
         }
     }
 #pragma unroll
@@ -98,7 +116,7 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
             const int c = q % BN, kc = q / BN;
             u32 h[8];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) h[t] = conv_b(Bb, cb, k0 + kc * 8 + t, c);
+            for (int t = 0; t < 8; ++t) h[t] = (BKP == BK || kc * 8 + t < BK) ? (u32)conv_b(Bb, cb, k0 + kc * 8 + t, c) : 0u;
             u32x4 v;
             v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
             v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
@@ -122,7 +140,7 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
-            const int row = q / (BK / 8), kc = q % (BK / 8);
+            const int row = q / (BKP / 8), kc = q % (BKP / 8);
             *(u32x4 *)(As + lds_off(row, kc * 8)) = s.a[i];
         }
     }
@@ -175,7 +193,7 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As
                                              int a_row0, int b_row0, int lk)
 {
     constexpr int TJ = NI / FNI, TI = MI / FMI;
-    constexpr int STEPS = (BK / KA) * TI * TJ;
+    constexpr int STEPS = (BKP / KA) * TI * TJ;
 #if FLAG
     // fully unrolled, fragments of step t+1 are read before the MFMAs of step t are issued
     // (two register sets), so LDS latency hides behind the matrix pipe inside one wave
@@ -193,7 +211,7 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As
     }
 #else
 #pragma unroll 1
-    for (int kk = 0; kk < BK / KA; ++kk) {
+    for (int kk = 0; kk < BKP / KA; ++kk) {
 #pragma unroll
         for (int tt = 0; tt < TI * TJ; ++tt) {
             frag_t af[FMI], bf[FNI];

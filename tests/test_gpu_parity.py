@@ -263,7 +263,8 @@ CONV56_CASES = [
     ("mfma32 single stage", [1, 1, 2, 1, 1, 32, 7, 1, 1, 8, 2, 1, 1, 28, 18, 32, 0]),
     ("mfma16 7-pixel pieces", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1]),
     ("mfma16 slab 96", [1, 1, 4, 1, 1, 16, 14, 1, 1, 4, 1, 1, 7, 8, 6, 96, 1]),
-    ("scalar", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
+    ("mfma16, slab 24 zero-padded to 32", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
+    ("scalar", [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
     ("scalar one pixel tiles", [1, 1, 8, 1, 1, 8, 56, 1, 1, 1, 8, 1, 1, 7, 64, 9, 1]),
 ]
 
@@ -295,6 +296,23 @@ def test_conv_stride_padding_kernel_shapes(torch_cuda):
     for label, cfg in [("stride 2 mfma16 slab 48 -> scalar", [1, 2, 1, 1, 2, 16, 1, 1, 1, 5, 5, 1, 1, 1, 3, 48, 1]),
                        ("stride 2 scalar", [2, 1, 2, 2, 2, 4, 5, 1, 1, 1, 1, 1, 5, 1, 9, 16, 0])]:
         w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+    # reduction axis 3*11*11 = 363 (no factor 16): K slabs are staged zero-padded to the MFMA step
+    w = Workload(torch_cuda, "conv2d", (16, 3, 35, 35, 16, 11, 11, 4, 0), "bf16", 44)   # out 7x7, 16 images per tile
+    for label, cfg in [("mfma16, slab 33 padded to 64", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 11, 33, 1]),
+                       ("mfma16, slab 121 padded to 128, single stage", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 3, 121, 0]),
+                       ("mfma16, one slab of 363 padded to 384", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 363, 0]),
+                       ("mfma16, 7 waves, slab 11 padded to 32", [1, 16, 1, 1, 1, 16, 1, 7, 1, 1, 7, 1, 1, 1, 33, 11, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(0, 2)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (32, 3, 19, 19, 32, 11, 11, 4, 0), "bf16", 45)   # out 3x3, 32 images per tile
+    for label, cfg in [("mfma32, slab 121 padded to 128", [1, 32, 1, 1, 1, 32, 3, 1, 1, 1, 3, 1, 1, 1, 3, 121, 1]),
+                       ("mfma32, 3 waves, slab 33 padded to 48", [1, 32, 1, 1, 1, 32, 1, 3, 1, 1, 1, 1, 3, 1, 11, 33, 1])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=707, want_paths=(0, 1, 2)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
     w.close()
 
 
@@ -364,8 +382,8 @@ PAPER_SHAPES = [
      [("direct-to-LDS, 15 grid rows of 64 batches", [15, 64, 2, 1, 2, 32, 1, 1, 1, 64, 2, 64, 1]),
       ("mfma16, 480 batches per workgroup", [2, 480, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0])]),
     ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (1, 2), []),
-    # C1's reduction axis 3*11*11 = 363 has no factor 16: only the scalar template applies
-    ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (),
+    # C1's reduction axis 3*11*11 = 363 has no factor 16: MFMA members stage zero-padded K slabs
+    ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (1, 2),
      [("scalar, 16 x 484 tile", [128, 4, 4, 1, 4, 4, 5, 11, 1, 1, 5, 1, 11, 1, 11, 33, 1])]),
 ]
 

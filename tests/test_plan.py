@@ -112,7 +112,10 @@ COMPILE_CASES = [
     ("bmm lds register-staged", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 4, 16, 1], 1),
     ("bmm direct", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0], 1),
     ("conv mfma", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1], 2),
-    ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
+    ("conv mfma16, slab 24 padded to 32", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 2),
+    ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
+    ("conv mfma32, odd reduction axis, slab 121 padded to 128", (P.OPEVO_CONV2D, (32, 3, 19, 19, 32, 11, 11, 4, 0)), P.OPEVO_BF16,
+     P.OPEVO_TILE4, [1, 32, 1, 1, 1, 32, 3, 1, 1, 1, 3, 1, 1, 1, 3, 121, 1], 1),
     ("conv batch mfma", CONV14, P.OPEVO_BF16, P.OPEVO_TILE4, [8, 4, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 36, 64, 1], 2),
 ]
 
