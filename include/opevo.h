@@ -170,8 +170,16 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         BMM     B(2) M(4) N(4) K(2) lds{0,1}      (stage operands through LDS or not)
  *         Conv2d  B(2) Cout(4) H(4) W(4) R(2) unroll{0,1},  R = Cin*Hk*Wk
  *         MFMA kernels (bf16/fp16 inputs) where the per-wave tile is made of 32x32 or 16x16
- *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise. */
-typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1 } opevo_variant;
+ *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise.
+ *  TILE4X: TILE4 plus the two remaining parameter types of Sec. 3 as launch tunables.  The
+ *         workgroups are launched as a one-dimensional grid and walk the grid axes (0 = N tiles,
+ *         1 = M tiles, 2 = batch blocks of a BMM) in the order given by a PERMUTATION parameter
+ *         `order` (first = fastest varying); a DISCRETE parameter `group` in {1, 2, 4, 8, 16}
+ *         is the number of consecutive tiles of the second axis that are walked together (each
+ *         group goes through the whole first axis before the next group starts), which decides
+ *         what the workgroups resident at one time share in L2.  Flat encoding: the TILE4 slots,
+ *         then the permutation (2 or 3 slots), then the index of the group width. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]

@@ -33,6 +33,25 @@ static opevo_param_desc factor(const char *name, int64_t C, int nu)
     return d;
 }
 
+static const double kGroupValues[] = {1, 2, 4, 8, 16};
+static const int kNumGroupValues = 5;
+
+static opevo_param_desc permutation(const char *name, int n)
+{
+    opevo_param_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.type = OPEVO_PERMUTATION; d.n_values = n; d.name = name;
+    return d;
+}
+
+static opevo_param_desc discrete(const char *name, const double *values, int n)
+{
+    opevo_param_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.type = OPEVO_DISCRETE; d.n_values = n; d.values = values; d.name = name;
+    return d;
+}
+
 static opevo_param_desc flag(const char *name)
 {
     opevo_param_desc d;
@@ -49,7 +68,7 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
         descs = {factor("M", op.M, 2), factor("N", op.N, 2), factor("K", op.K, 2)};
         return OPEVO_OK;
     }
-    if (variant != OPEVO_TILE4) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
+    if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
     switch (op.kind) {
     case OPEVO_MATMUL:
         descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 2), flag("unroll")};
@@ -64,6 +83,13 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
         break;
     default:
         return fail(OPEVO_E_ARG, "unknown operator kind %d", op.kind);
+    }
+    if (variant == OPEVO_TILE4X) {
+        // the order in which a one-dimensional launch walks the grid axes (N tiles, M tiles and,
+        // for BMM, batch blocks; first = fastest), and the width of the groups of second-axis
+        // tiles it walks together
+        descs.push_back(permutation("order", op.kind == OPEVO_BMM ? 3 : 2));
+        descs.push_back(discrete("group", kGroupValues, kNumGroupValues));
     }
     return OPEVO_OK;
 }
@@ -92,9 +118,17 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                 if (prod != d.C)
                     return fail(OPEVO_E_ILLEGAL, "factors of %s do not multiply to %lld", d.name, (long long)d.C);
                 off += d.nu;
+            } else if (d.type == OPEVO_PERMUTATION) {
+                unsigned seen = 0;
+                for (int j = 0; j < d.n_values; ++j) {
+                    if (cfg[off + j] < 0 || cfg[off + j] >= d.n_values || (seen >> cfg[off + j] & 1u))
+                        return fail(OPEVO_E_ILLEGAL, "%s is not a permutation of 0..%d", d.name, d.n_values - 1);
+                    seen |= 1u << cfg[off + j];
+                }
+                off += d.n_values;
             } else {
                 if (cfg[off] < 0 || cfg[off] >= d.n_values)
-                    return fail(OPEVO_E_ILLEGAL, "flag %s out of range", d.name);
+                    return fail(OPEVO_E_ILLEGAL, "%s out of range", d.name);
                 off += 1;
             }
         }
@@ -110,7 +144,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t BM = 1, BN = 1, BK = 1, ksteps = 1, WM = 1, WN = 1, TM = 1, TN = 1, FM = 1, FN = 1;
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
-    bool four_level = (variant == OPEVO_TILE4);
+    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X);
+    int tile4_width = 0;   // slots of the four-level part, after which the launch-order parameters follow
 
     if (!four_level) {
         m1 = cfg[0]; BM = cfg[1]; n1 = cfg[2]; BN = cfg[3]; ksteps = cfg[4]; BK = cfg[5];
@@ -122,6 +157,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         n1 = c[4]; WN = c[5]; TN = int64_t(c[6]) * c[7]; FN = c[7];
         ksteps = c[8]; BK = c[9]; flagv = c[10];
         BM = WM * TM; BN = WN * TN;
+        tile4_width = int(c - cfg) + 11;
     } else {   // conv: B(2) Cout(4) H(4) W(4) R(2) flag
         const int32_t *c = cfg;
         const int64_t nb1 = c[0]; nb2 = c[1];
@@ -135,6 +171,16 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         n1 = nb1 * h1 * w1;
         ksteps = c[14]; BK = c[15]; flagv = c[16];
         BM = WM * TM; BN = WN * TN;
+        tile4_width = 17;
+    }
+    // extended variant: launch order and group width
+    const bool linear = (variant == OPEVO_TILE4X);
+    int order[3] = {0, 1, 2};
+    int64_t group = 1;
+    if (linear) {
+        const int n_axes = op.kind == OPEVO_BMM ? 3 : 2;
+        for (int j = 0; j < n_axes; ++j) order[j] = cfg[tile4_width + j];
+        group = int64_t(kGroupValues[cfg[tile4_width + n_axes]]);
     }
 
     // ---- template choice
@@ -192,7 +238,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2;
 
     p.path = path;
-    p.grid[0] = int32_t(n1); p.grid[1] = int32_t(m1); p.grid[2] = int32_t(b1);
+    const int64_t n_blocks = n1 * m1 * b1;
+    if (linear) { p.grid[0] = int32_t(n_blocks > INT32_MAX ? INT32_MAX : n_blocks); p.grid[1] = 1; p.grid[2] = 1; }
+    else { p.grid[0] = int32_t(n1); p.grid[1] = int32_t(m1); p.grid[2] = int32_t(b1); }
     p.block = int32_t(NT > INT32_MAX ? INT32_MAX : NT);
     p.lds_bytes = int32_t(lds > INT32_MAX ? INT32_MAX : lds);
     p.acc_per_lane = int32_t(acc > INT32_MAX ? INT32_MAX : acc);
@@ -204,7 +252,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (acc > kMaxAcc) invalid(p, "%ld accumulators per lane > %ld", long(acc), long(kMaxAcc));
     else if (lds + (path == 0 ? 16 : 0) > kMaxLds)   // the scalar template adds a static flag word
         invalid(p, "%ld bytes of LDS > %ld", long(lds), long(kMaxLds));
-    else if (m1 > 65535 || b1 > 65535) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
+    else if (!linear && (m1 > 65535 || b1 > 65535)) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
+    else if (linear && n_blocks > INT32_MAX) invalid(p, "%ld workgroups in a one-dimensional grid", long(n_blocks));
     else if (path != 0 && path != 3 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
         const int64_t a_chunks = (BM * (BKP / 8) + NT - 1) / NT;
@@ -221,7 +270,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? "bmm" : "conv")
            << (four_level ? "4" : "2");
         int width = 0;
-        for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : 1;
+        for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
         out.kernel_name = nm.str();
     }
@@ -240,6 +289,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
           << " -DHOUT=" << op.hout << " -DWOUT=" << op.wout << " -DNB2=" << nb2 << " -DBH=" << BH
           << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1 << " -DBKP=" << BKP;
     }
+    if (linear)
+        D << " -DGRID_LINEAR=1 -DGRID_N1=" << n1 << " -DGRID_M1=" << m1 << " -DGRID_B1=" << b1 << " -DORDER0=" << order[0]
+          << " -DORDER1=" << order[1] << " -DORDER2=" << order[2] << " -DGROUP=" << group;
     out.defines = D.str();
     return OPEVO_OK;
 }

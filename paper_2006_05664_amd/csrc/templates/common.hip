@@ -13,7 +13,7 @@
 //         n = output pixel (image, y, x); B[k][n] is gathered from the NCHW image on the fly
 //         and is zero where the tap falls outside the image.
 //
-// Workgroup (bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z) owns rows [by*BM, +BM) and
+// Workgroup (bx, by, bz) = block_id() (by default blockIdx.x, .y, .z) owns rows [by*BM, +BM) and
 // columns "bx-th block of BN columns".  For conv a block of columns is a box of
 // NB2 images x BH rows x BW pixels; column c of the block is image c/(BH*BW), row (c/BW)%BH,
 // pixel c%BW of that box.
@@ -38,6 +38,35 @@ __device__ __forceinline__ float to_f32(in_t x) { return __builtin_bit_cast(floa
 typedef u16 in_t;   // fp16 bits
 __device__ __forceinline__ float to_f32(in_t x) { return (float)__builtin_bit_cast(_Float16, x); }
 #endif
+
+// Which tile a workgroup owns: n = block of BN columns, m = block of BM rows, b = batch block.
+// Default launch: a three-dimensional grid (n, m, b).  With GRID_LINEAR the launch is
+// one-dimensional and the linear workgroup number walks the axes 0 = n, 1 = m, 2 = b in the order
+// ORDER0 (fastest), ORDER1, ORDER2; GROUP consecutive tiles of axis ORDER1 are walked together:
+// a group goes through the whole of axis ORDER0 (second-axis index fastest inside the group)
+// before the next group starts; a ragged last group is narrower.
+struct BlockId { int n, m, b; };
+__device__ __forceinline__ BlockId block_id()
+{
+    BlockId id;
+#ifdef GRID_LINEAR
+    constexpr int ext[3] = {GRID_N1, GRID_M1, GRID_B1};
+    constexpr int e0 = ext[ORDER0], e1 = ext[ORDER1];
+    const int L = blockIdx.x;
+    const int rest = L / (e0 * e1), pid = L % (e0 * e1);
+    const int gid = pid / (GROUP * e0), in_group = pid % (GROUP * e0);
+    const int first = gid * GROUP;
+    const int gsz = (e1 - first < GROUP) ? e1 - first : GROUP;
+    int idx[3];
+    idx[ORDER0] = in_group / gsz;
+    idx[ORDER1] = first + in_group % gsz;
+    idx[ORDER2] = rest;
+    id.n = idx[0]; id.m = idx[1]; id.b = idx[2];
+#else
+    id.n = blockIdx.x; id.m = blockIdx.y; id.b = blockIdx.z;
+#endif
+    return id;
+}
 
 #if OP == OP_CONV
 struct ColBlock { int nb0, y0, x0; };

@@ -236,18 +236,19 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane % ATOM, lk = (lane / ATOM) * 8;
-    const int m0 = blockIdx.y * BM;
+    const BlockId bid = block_id();
+    const int m0 = bid.m * BM;
 #if OP == OP_CONV
-    const ColBlock cb = col_block(blockIdx.x);
+    const ColBlock cb = col_block(bid.n);
 #else
-    const int n0 = blockIdx.x * BN;
+    const int n0 = bid.n * BN;
 #endif
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
 #if OP == OP_CONV
         const u16 *Ab = A, *Bb = B;
 #else
-        const long batch = (long)blockIdx.z * BATCH_INNER + bi;
+        const long batch = (long)bid.b * BATCH_INNER + bi;
         const u16 *Ab = A + batch * M * K;
         const u16 *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;

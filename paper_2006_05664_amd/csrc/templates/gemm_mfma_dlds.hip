@@ -136,7 +136,8 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     const unsigned ring_addr = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long)(__attribute__((address_space(3))) u16 *)ring);   // LDS byte address
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const BlockId bid = block_id();
+    const int m0 = bid.m * BM, n0 = bid.n * BN;
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     const int slot = uwave;
     unsigned aoff[NA], boff[NB];
@@ -146,7 +147,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     for (int t = 0; t < NB; ++t) boff[t] = b_lane_off(slot * LB + t, lane);
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
-        const long batch = (long)blockIdx.z * BATCH_INNER + bi;
+        const long batch = (long)bid.b * BATCH_INNER + bi;
         const u16 *Ab = A + batch * M * K;
         const u16 *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;

@@ -24,20 +24,21 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
     __shared__ int expired;
     const int tid = threadIdx.x;
     if (tid == 0) expired = 0;
-    const int m0 = blockIdx.y * BM;
+    const BlockId bid = block_id();
+    const int m0 = bid.m * BM;
     constexpr int E = (BM * BN + NT - 1) / NT;
 
 #if OP == OP_CONV
-    const ColBlock cb = col_block(blockIdx.x);
+    const ColBlock cb = col_block(bid.n);
 #else
-    const int n0 = blockIdx.x * BN;
+    const int n0 = bid.n * BN;
 #endif
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
 #if OP == OP_CONV
         const in_t *Ab = A;   // kernel tensor [M][K]
 #else
-        const long batch = (long)blockIdx.z * BATCH_INNER + bi;
+        const long batch = (long)bid.b * BATCH_INNER + bi;
         const in_t *Ab = A + batch * M * K;
         const in_t *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;

@@ -369,6 +369,39 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
     w.close()
 
 
+# ------------------------------------------------------------------ extended variant: launch order and group width
+def test_extended_variant_every_launch_order_and_group_width(torch_cuda):
+    """The PERMUTATION (order of the grid axes) and DISCRETE (group width) parameters only change
+    which workgroup computes which tile: every order and width must give the full, correct tensor
+    (NaN pre-fill: a tile nobody owns fails; a tile owned twice is harmless but a wrong mapping
+    leaves another one unowned)."""
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
+    bases = [("direct-to-LDS, 8 x 16 tiles", [8, 1, 2, 32, 16, 1, 2, 32, 32, 32, 1]),        # grid 16 x 8
+             ("register-staged, 4 x 8 tiles", [4, 2, 2, 32, 8, 2, 2, 32, 64, 16, 1]),
+             ("scalar, 16 x 3-ragged groups", [16, 2, 2, 8, 64, 1, 4, 4, 64, 16, 0])]
+    for label, base in bases:
+        for order in ([0, 1], [1, 0]):
+            for g in (0, 2, 4):              # group widths 1, 4, 16
+                w.check(P.OPEVO_TILE4X, base + order + [g], "%s order %s group %d" % (label, order, (1, 2, 4, 8, 16)[g]))
+    for cfg in w.random_valid(P.OPEVO_TILE4X, 8, seed=808):
+        w.check(P.OPEVO_TILE4X, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "bmm", (15, 48, 80, 96), "bf16", 31)       # 3 axes: 3! orders, ragged groups
+    base = [5, 3, 3, 1, 1, 16, 5, 1, 1, 16, 3, 32, 1]
+    for order in ([0, 1, 2], [0, 2, 1], [1, 0, 2], [1, 2, 0], [2, 0, 1], [2, 1, 0]):
+        for g in (0, 1, 3):
+            w.check(P.OPEVO_TILE4X, base + order + [g], "bmm order %s group %d" % (order, (1, 2, 4, 8, 16)[g]))
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (1, 64, 56, 56, 64, 3, 3, 1, 1), "bf16", 1237)
+    base = [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1]
+    for order in ([0, 1], [1, 0]):
+        for g in (0, 3):
+            w.check(P.OPEVO_TILE4X, base + order + [g], "conv order %s group %d" % (order, (1, 2, 4, 8, 16)[g]))
+    for cfg in w.random_valid(P.OPEVO_TILE4X, 6, seed=909):
+        w.check(P.OPEVO_TILE4X, cfg, "random")
+    w.close()
+
+
 # ------------------------------------------------------------------ the paper's own operator shapes
 PAPER_SHAPES = [
     # name, kind, dims, seed, units of the leading index the oracle computes, template paths of the

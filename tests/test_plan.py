@@ -168,3 +168,56 @@ def test_every_sampled_direct_to_lds_member_compiles_to_a_small_code_object():
             break
     assert built == 6
     P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+
+
+# ------------------------------------------------------------------ extended variant: launch order and group width
+def test_extended_variant_adds_a_permutation_and_a_discrete_parameter():
+    for kd, n_axes in ((MM1, 2), (BMM, 3), (CONV56, 2)):
+        op = _op(kd, P.OPEVO_BF16)
+        sp4, spx = P.opevo_op_space(op, P.OPEVO_TILE4), P.opevo_op_space(op, P.OPEVO_TILE4X)
+        assert P.opevo_space_width(spx) == P.opevo_space_width(sp4) + n_axes + 1
+        assert P.opevo_space_num_params(spx) == P.opevo_space_num_params(sp4) + 2
+        fact = 1
+        for i in range(2, n_axes + 1):
+            fact *= i
+        assert P.opevo_space_size(spx) == P.opevo_space_size(sp4) * fact * 5
+        assert P.opevo_space_param_name(spx, P.opevo_space_num_params(spx) - 2) == "order"
+        assert P.opevo_space_param_name(spx, P.opevo_space_num_params(spx) - 1) == "group"
+        P.opevo_space_destroy(sp4); P.opevo_space_destroy(spx)
+
+
+def test_extended_variant_decodes_to_a_linear_grid_with_the_same_tiles():
+    op = _op(MM1, P.OPEVO_BF16)
+    base = [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1]
+    p4 = P.opevo_kernel_plan(op, P.OPEVO_TILE4, base)
+    for order in ([0, 1], [1, 0]):
+        for g in range(5):
+            px = P.opevo_kernel_plan(op, P.OPEVO_TILE4X, base + order + [g])
+            assert px.status == P.OPEVO_OK and px.path == p4.path
+            assert list(px.tile) == list(p4.tile) and px.block == p4.block and px.lds_bytes == p4.lds_bytes
+            assert list(px.grid) == [p4.grid[0] * p4.grid[1] * p4.grid[2], 1, 1]
+            d = P.opevo_kernel_defines(op, P.OPEVO_TILE4X, base + order + [g])
+            assert "-DGRID_LINEAR=1" in d and "-DORDER0=%d" % order[0] in d and "-DGROUP=%d" % (1, 2, 4, 8, 16)[g] in d
+    for bad in (base + [0, 0, 0], base + [0, 2, 0], base + [0, 1, 5], base + [0, 1, -1]):
+        with pytest.raises(P.OpevoError) as ei:
+            P.opevo_kernel_plan(op, P.OPEVO_TILE4X, bad)
+        assert ei.value.status == P.OPEVO_E_ILLEGAL
+
+
+EXT_COMPILE_CASES = [
+    ("direct-to-LDS, m fastest, groups of 4", MM1, [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1, 1, 0, 2], 3),
+    ("register-staged, n fastest, groups of 16", MM1, [2, 2, 2, 64, 8, 2, 2, 32, 64, 16, 1, 0, 1, 4], 1),
+    ("scalar, m fastest", MM1, [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1, 1, 0, 0], 0),
+    ("bmm, batch fastest", BMM, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1, 2, 0, 1, 1], 3),
+    ("conv mfma, cout blocks fastest", CONV56, [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1, 1, 0, 3], 2),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg,path", EXT_COMPILE_CASES, ids=[c[0] for c in EXT_COMPILE_CASES])
+def test_extended_variant_templates_compile(label, kd, cfg, path):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4X, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4X, cfg)
+    assert P.opevo_kernel_code_size(kernel) > 1000
+    P.opevo_kernel_destroy(kernel)
