@@ -67,7 +67,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = synth.WORKLOADS[args.workload]
-    kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
+    kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
     variant = P.OPEVO_TILE2 if dtype == "f32" else (P.OPEVO_TILE4X if args.extended else P.OPEVO_TILE4)
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
@@ -95,8 +95,10 @@ def main() -> int:
     if w["kind"] == "matmul":
         ref = oracle_tensor.matmul(a_host, b_host) if rows is None else oracle_tensor.matmul_rows(a_host, b_host, rows)
         unit = "rows"
-    elif w["kind"] == "bmm":
-        ref = oracle_tensor.bmm(a_host, b_host) if rows is None else oracle_tensor.bmm(a_host[rows], b_host[rows])
+    elif w["kind"] in ("bmm", "bmm_ta"):
+        # a transposed first operand is handed to the oracle untransposed (a copy, no arithmetic)
+        a_or = a_host if w["kind"] == "bmm" else np.ascontiguousarray(a_host.transpose(0, 2, 1))
+        ref = oracle_tensor.bmm(a_or, b_host) if rows is None else oracle_tensor.bmm(a_or[rows], b_host[rows])
         unit = "batches"
     else:
         img = b_host if rows is None else b_host[rows]

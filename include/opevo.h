@@ -157,7 +157,7 @@ int opevo_tuner_history(const opevo_tuner *tuner, int32_t *cfgs_out, double *fit
                         int cap_trials, int *n);
 
 /* --------------------------------------------------------- operators (App. B.1 - B.3) */
-typedef enum { OPEVO_MATMUL = 0, OPEVO_BMM = 1, OPEVO_CONV2D = 2 } opevo_op_kind;
+typedef enum { OPEVO_MATMUL = 0, OPEVO_BMM = 1, OPEVO_CONV2D = 2, OPEVO_BMM_TA = 3 } opevo_op_kind;
 typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
 
 /* Which configuration space / kernel template family an operator is tuned in.
@@ -183,6 +183,9 @@ typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2 } opevo_varian
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
+ *        BMM_TA {B, M, N, K}         C[b] = A[b]^T B[b] with the first operand stored as [B][K][M]
+ *                                    (App. B.2: "transposed first"); same configuration spaces as
+ *                                    BMM; runs on the scalar and the direct-to-LDS MFMA template
  *        CONV2D {B, Cin, H, W, Cout, Hk, Wk, stride, pad}  NCHW image, OIHW kernel,
  *               out[B,Cout,Hout,Wout], Hout = floor((H+2*pad-Hk)/stride)+1 (App. B.3).
  * All tensors dense row-major.  `in` is the element type of both inputs; accumulation and

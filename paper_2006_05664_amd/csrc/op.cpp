@@ -206,7 +206,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     if (path == 1 && flagv == 1 && stage_lds && op.kind != OPEVO_CONV2D && 64 * WM * WN <= kMaxThreads) {
         const int64_t nw = WM * WN;
         const bool bk_ok = (BK == 32 || BK == 64 || BK == 128);
-        const bool bn_ok = (BN % 128 == 0 || BN == 64 || BN == 32);
+        const bool bn_ok = (BN % 128 == 0 || BN == 64 || BN == 32) &&
+                           (!op.trans_a || BM % 128 == 0 || BM == 64 || BM == 32);   // A rows are M-contiguous then
         const bool split_ok = (BM * BK * 2) % (1024 * nw) == 0 && (BK * BN * 2) % (1024 * nw) == 0;
         if (bk_ok && bn_ok && split_ok) {
             const int64_t per = (BM * BK * 2 + BK * BN * 2) / (1024 * nw);
@@ -218,11 +219,13 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             // past this size were seen not to unroll (code objects of 0.5-1.5 MB instead of 20 KB);
             // such members use the register-staged template instead.
             const int64_t mi = TM / 32, ni = TN / 32, kk = BK / 16;
-            const int64_t body = nstage_dlds * (kk * (mi * ni + mi + 2 * ni) + per);
+            const int64_t body = nstage_dlds * (kk * (mi * ni + (op.trans_a ? 2 : 1) * mi + 2 * ni) + per);
             if (body > kMaxDldsBody) nstage_dlds = 0;
         }
         if (nstage_dlds) path = 3;
     }
+    // a transposed first operand is read by the scalar and the direct-to-LDS template only
+    if (op.trans_a && path != 3) path = 0;
 
     int64_t NT;
     if (four_level) NT = 64 * WM * WN;
@@ -267,7 +270,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     // one symbol per configuration, so profiles list each instantiated kernel on its own line
     {
         std::ostringstream nm;
-        nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? "bmm" : "conv")
+        nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
            << (four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
@@ -277,7 +280,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     D << "-DKERNEL_NAME=" << out.kernel_name << " ";
     D << "-DOP=" << op.kind << " -DIN_DTYPE=" << op.dtype << " -DM=" << op.M << " -DN=" << op.N
       << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
-      << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv;
+      << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv << " -DA_TRANS=" << (op.trans_a ? 1 : 0);
     if (path != 0) {
         D << " -DATOM=" << (path == 2 ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
@@ -305,6 +308,7 @@ int opevo_op_create(int kind, const int64_t *dims, int n_dims, int in_dtype, ope
     if (!dims || !out) return fail(OPEVO_E_ARG, "op_create: NULL argument");
     if (in_dtype < OPEVO_F32 || in_dtype > OPEVO_F16) return fail(OPEVO_E_ARG, "op_create: unknown dtype %d", in_dtype);
     opevo_op op;
+    if (kind == OPEVO_BMM_TA) { kind = OPEVO_BMM; op.trans_a = true; }
     op.kind = kind; op.dtype = in_dtype;
     const int need = kind == OPEVO_MATMUL ? 3 : kind == OPEVO_BMM ? 4 : kind == OPEVO_CONV2D ? 9 : -1;
     if (need < 0) return fail(OPEVO_E_ARG, "op_create: unknown operator kind %d", kind);

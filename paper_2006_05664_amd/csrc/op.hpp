@@ -14,6 +14,7 @@ struct opevo_op {
     int dtype = OPEVO_BF16;
     // GEMM view: C[batch][M][N] = sum_K A[batch][M][K] B[batch][K][N]
     int64_t batch = 1, M = 0, N = 0, K = 0;
+    bool trans_a = false;   // BMM only: A stored as [batch][K][M] (OPEVO_BMM_TA)
     // conv only
     int64_t cin = 0, hin = 0, win = 0, hk = 0, wk = 0, stride = 1, pad = 0, hout = 0, wout = 0, nimg = 0;
 

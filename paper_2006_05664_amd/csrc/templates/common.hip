@@ -18,6 +18,9 @@
 // NB2 images x BH rows x BW pixels; column c of the block is image c/(BH*BW), row (c/BW)%BH,
 // pixel c%BW of that box.
 
+#ifndef A_TRANS
+#define A_TRANS 0
+#endif
 #define OP_MATMUL 0
 #define OP_BMM 1
 #define OP_CONV 2

@@ -43,15 +43,25 @@ constexpr int NW = NT / 64;
 constexpr int MI = TM / 32, NI = TN / 32;
 constexpr int KK = BK / 16;                                   // MFMA K steps per slab
 constexpr int A_STAGE = BM * BK, B_STAGE = BK * BN, STAGE = A_STAGE + B_STAGE;   // elements
+#if A_TRANS   // first operand stored [K][M]: its stage part is [BK][BM], laid out and read like B's
+constexpr int ACH = BM / 8;                                   // 16-byte chunks per A row (a row is one k)
+constexpr int A_RPW = (16 / ACH) > 0 ? (16 / ACH) : 1;
+constexpr int A_SWM = (4 / A_RPW) > 0 ? (4 / A_RPW) : 1;
+#else
 constexpr int ACH = BK / 8;                                   // 16-byte chunks per A row
 constexpr int A_RPW = (16 / ACH) > 0 ? (16 / ACH) : 1;        // A rows per 256-byte bank window
+#endif
 constexpr int BCH = BN / 8;                                   // chunks per B row
 constexpr int B_RPW = (16 / BCH) > 0 ? (16 / BCH) : 1;
 constexpr int B_SWM = (4 / B_RPW) > 0 ? (4 / B_RPW) : 1;
 constexpr int LA = BM * BK * 2 / 1024 / NW, LB = BK * BN * 2 / 1024 / NW;   // loads per wave and slab
 constexpr int PER = LA + LB;
 
+#if A_TRANS
+__device__ __forceinline__ int a_swz(int krow) { return ((krow / A_RPW) % A_SWM) << 2; }
+#else
 __device__ __forceinline__ int a_swz(int row) { return (row / A_RPW) % ACH; }
+#endif
 __device__ __forceinline__ int b_swz(int krow) { return ((krow / B_RPW) % B_SWM) << 2; }
 
 // One wave-wide 16-byte-per-lane load whose destination is LDS: lane i's 16 bytes, read from
@@ -76,13 +86,21 @@ constexpr int lane_period(int per_row, int swz_rows)
     while ((p * 64) % per_row != 0 || (p * 64 / per_row) % swz_rows != 0) ++p;
     return p;
 }
+#if A_TRANS
+constexpr int PA = lane_period(ACH, A_RPW * A_SWM), PB = lane_period(BCH, B_RPW * B_SWM);
+#else
 constexpr int PA = lane_period(ACH, A_RPW * ACH), PB = lane_period(BCH, B_RPW * B_SWM);
+#endif
 constexpr int NA = LA < PA ? LA : PA, NB = LB < PB ? LB : PB;
 
 __device__ __forceinline__ unsigned a_lane_off(int instr, int lane)
 {
     const int p = instr * 64 + lane, row0 = instr * 64 / ACH, row = p / ACH;
+#if A_TRANS
+    return (unsigned)((row - row0) * M + (((p % ACH) ^ a_swz(row)) << 3)) * 2u;
+#else
     return (unsigned)((row - row0) * K + (((p % ACH) ^ a_swz(row)) << 3)) * 2u;
+#endif
 }
 __device__ __forceinline__ unsigned b_lane_off(int instr, int lane)
 {
@@ -99,7 +117,11 @@ __device__ __forceinline__ void issue_piece(int t, const u16 *__restrict__ Ab, c
 {
     if (t < LA) {
         const int instr = slot * LA + t;
+#if A_TRANS
+        dma16(Ab + (long)(k0 + instr * 64 / ACH) * M + m0, aoff[t % PA], stage + instr * 1024);
+#else
         dma16(Ab + (long)(m0 + instr * 64 / ACH) * K + k0, aoff[t % PA], stage + instr * 1024);
+#endif
     } else {
         const int u = t - LA, instr = slot * LB + u;
         dma16(Bb + (long)(k0 + instr * 64 / BCH) * N + n0, boff[u % PB], stage + (A_STAGE + instr * 512) * 2);
@@ -111,6 +133,17 @@ __device__ __forceinline__ frag_t read_a(const u16 *stage, int wm, int lane, int
     const int kc = kk * 2 + (lane >> 5);
     return __builtin_bit_cast(frag_t, *(const u32x4 *)(stage + row * BK + ((kc ^ a_swz(row)) << 3)));
 }
+#if A_TRANS
+// half an A fragment from the [BK][BM] stage part, with the transposing read (as for B)
+__device__ __forceinline__ v4s read_a_half(const u16 *stage, int wm, int lane, int kk, int i, int r)
+{
+    const int s = lane & 15;
+    const int m = wm * TM + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const int krow = kk * 16 + 8 * (lane >> 5) + 4 * r + (s >> 2);
+    const u16 *p = stage + krow * BM + (((m >> 3) ^ a_swz(krow)) << 3) + (m & 7);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)p);
+}
+#endif
 __device__ __forceinline__ v4s read_b_half(const u16 *stage, int wn, int lane, int kk, int j, int r)
 {
     const int s = lane & 15;
@@ -172,16 +205,30 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                 issue_piece(t, Ab, Bb, ring_addr + s * STAGE * 2, m0, n0, KCLAMP(s) * BK, slot, aoff, boff);
         WAIT_VMCNT((NSTG - 1) * PER);
         BARRIER();
-        frag_t af[2][MI];
         v4s bh[2][NI][2];
-        constexpr int NR = MI + 2 * NI;            // fragment reads per MFMA step
         constexpr int SLOTS = MI * NI;             // MFMAs per step
+#if A_TRANS
+        v4s ah[2][MI][2];
+        constexpr int NR = 2 * MI + 2 * NI;        // fragment reads per MFMA step
+        // read number k of the fragments of step (stage, kk) into buffer set b: A fragment 0, the B
+        // fragments, the other A fragments (the order the step's MFMAs need them in)
+        auto frag_read = [&](int b, const u16 *stage, int kk, int k) {
+            if (k < 2) ah[b][0][k] = read_a_half(stage, wm, lane, kk, 0, k);
+            else if (k < 2 + 2 * NI) bh[b][(k - 2) / 2][(k - 2) % 2] = read_b_half(stage, wn, lane, kk, (k - 2) / 2, (k - 2) % 2);
+            else ah[b][(k - 2 * NI) / 2][(k - 2 * NI) % 2] = read_a_half(stage, wm, lane, kk, (k - 2 * NI) / 2, (k - 2 * NI) % 2);
+        };
+#define A_FRAG(b, i) __builtin_bit_cast(frag_t, __builtin_shufflevector(ah[b][i][0], ah[b][i][1], 0, 1, 2, 3, 4, 5, 6, 7))
+#else
+        frag_t af[2][MI];
+        constexpr int NR = MI + 2 * NI;            // fragment reads per MFMA step
         // read number k of the fragments of step (stage, kk) into buffer set b
         auto frag_read = [&](int b, const u16 *stage, int kk, int k) {
             if (k == 0) af[b][0] = read_a(stage, wm, lane, kk, 0);
             else if (k <= 2 * NI) bh[b][(k - 1) / 2][(k - 1) % 2] = read_b_half(stage, wn, lane, kk, (k - 1) / 2, (k - 1) % 2);
             else af[b][k - 2 * NI] = read_a(stage, wm, lane, kk, k - 2 * NI);
         };
+#define A_FRAG(b, i) af[b][i]
+#endif
 #pragma unroll
         for (int k = 0; k < NR; ++k) frag_read(0, ring, 0, k);
 
@@ -199,7 +246,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                 for (int m = 0; m < SLOTS; ++m) {
                     const int i = m / NI, j = m % NI;
                     const frag_t bfr = __builtin_bit_cast(frag_t, __builtin_shufflevector(bh[kk & 1][j][0], bh[kk & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
-                    acc[i][j] = MFMA(af[kk & 1][i], bfr, acc[i][j]);
+                    acc[i][j] = MFMA(A_FRAG(kk & 1, i), bfr, acc[i][j]);
                     if (m == 0 && last) {
                         WAIT_LGKM_VMCNT((NSTG - 2) * PER);
                         BARRIER();

@@ -56,7 +56,11 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
             __syncthreads();
             if (expired) return;
             for (int i = tid; i < BM * BK; i += NT)
+#if A_TRANS   // first operand stored [K][M]: walk it along M so that the loads stay coalesced
+                As[(i % BM) * BK + i / BM] = to_f32(Ab[(long)(k0 + i / BM) * M + m0 + i % BM]);
+#else
                 As[i] = to_f32(Ab[(long)(m0 + i / BK) * K + k0 + i % BK]);
+#endif
             for (int i = tid; i < BK * BN; i += NT) {
 #if OP == OP_CONV
                 Bs[i] = to_f32(conv_b(B, cb, k0 + i / BN, i % BN));

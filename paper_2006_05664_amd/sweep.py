@@ -36,7 +36,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "sweep.py needs the GPU"
     w = synth.WORKLOADS[args.workload]
-    kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
+    kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
     variant = P.OPEVO_TILE2 if dtype == "f32" else P.OPEVO_TILE4
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])

@@ -50,6 +50,14 @@ def bmm_inputs(batch: int, M: int, N: int, K: int, dtype: str, seed: int) -> Tup
     return round_to(A, dtype), round_to(B, dtype)
 
 
+def bmm_ta_inputs(batch: int, M: int, N: int, K: int, dtype: str, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """First operand stored transposed: At[b,K,M], B[b,K,N] ~ N(0,1); C[b] = At[b]^T B[b]."""
+    rng = np.random.default_rng(seed)
+    At = rng.standard_normal((batch, K, M), dtype=np.float32)
+    B = rng.standard_normal((batch, K, N), dtype=np.float32)
+    return round_to(At, dtype), round_to(B, dtype)
+
+
 def conv_inputs(B: int, Cin: int, H: int, W: int, Cout: int, Hk: int, Wk: int, dtype: str, seed: int
                 ) -> Tuple[np.ndarray, np.ndarray]:
     """image[B,Cin,H,W] ~ U[0,1), kernel[Cout,Cin,Hk,Wk] ~ N(0, 0.05^2)."""
@@ -71,6 +79,8 @@ WORKLOADS: Dict[str, dict] = {
     "mm2_bf16": dict(kind="matmul", dims=(512, 4096, 1024), dtype="bf16", seed=1240, dist="normal"),
     "mm3_bf16": dict(kind="matmul", dims=(512, 1024, 4096), dtype="bf16", seed=1241, dist="normal"),
     "bmm1_bf16": dict(kind="bmm", dims=(960, 128, 64, 128), dtype="bf16", seed=1242),
+    "bmm2_bf16": dict(kind="bmm_ta", dims=(960, 128, 64, 128), dtype="bf16", seed=1245),   # (128x128)^T . (128x64)
+    "bmm3_bf16": dict(kind="bmm_ta", dims=(960, 64, 64, 128), dtype="bf16", seed=1246),    # (128x64)^T . (128x64)
     "c1_bf16": dict(kind="conv2d", dims=(512, 3, 227, 227, 64, 11, 11, 4, 0), dtype="bf16", seed=1243),
     "c2_bf16": dict(kind="conv2d", dims=(512, 64, 27, 27, 192, 5, 5, 1, 2), dtype="bf16", seed=1244),
 }
@@ -78,7 +88,7 @@ WORKLOADS: Dict[str, dict] = {
 
 def workload_inputs(name: str) -> Tuple[np.ndarray, np.ndarray]:
     """(first operand, second operand) in the order the kernels take them: MatMul/BMM (A, B);
-    Conv2d (kernel tensor, image)."""
+    BMM with a transposed first operand (At, B); Conv2d (kernel tensor, image)."""
     w = WORKLOADS[name]
     if w["kind"] == "matmul":
         M, N, K = w["dims"]
@@ -86,6 +96,9 @@ def workload_inputs(name: str) -> Tuple[np.ndarray, np.ndarray]:
     if w["kind"] == "bmm":
         b, M, N, K = w["dims"]
         return bmm_inputs(b, M, N, K, w["dtype"], w["seed"])
+    if w["kind"] == "bmm_ta":
+        b, M, N, K = w["dims"]
+        return bmm_ta_inputs(b, M, N, K, w["dtype"], w["seed"])
     B, Cin, H, W, Cout, Hk, Wk, _, _ = w["dims"]
     img, ker = conv_inputs(B, Cin, H, W, Cout, Hk, Wk, w["dtype"], w["seed"])
     return ker, img

@@ -20,7 +20,7 @@ pytestmark = pytest.mark.gpu
 
 TOL16 = (2e-2, 5e-3)
 TOL32 = (1e-4, 1e-4)
-KIND = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "conv2d": P.OPEVO_CONV2D}
+KIND = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}
 
 
 def _say(msg):
@@ -64,6 +64,10 @@ class Workload:
             B, M, N, K = dims
             a, b = synth.bmm_inputs(B, M, N, K, dtype, seed)
             self.ref = T.bmm(a, b) if oracle else None
+        elif kind == "bmm_ta":      # first operand stored [B][K][M]; the oracle gets it untransposed
+            B, M, N, K = dims
+            a, b = synth.bmm_ta_inputs(B, M, N, K, dtype, seed)
+            self.ref = T.bmm(np.ascontiguousarray(a.transpose(0, 2, 1)), b) if oracle else None
         else:
             B, Cin, H, W, Cout, Hk, Wk, S, Pd = dims
             img, ker = synth.conv_inputs(B, Cin, H, W, Cout, Hk, Wk, dtype, seed)
@@ -369,6 +373,28 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
     w.close()
 
 
+# ------------------------------------------------------------------ BatchMatMul with a transposed first operand
+def test_bmm_with_transposed_first_operand(torch_cuda):
+    """App. B.2, BMM2 / BMM3: the first operand is stored [B][K][M].  Scalar template and the
+    direct-to-LDS MFMA template (A staged as [BK][BM] and read with the transposing LDS load)."""
+    w = Workload(torch_cuda, "bmm_ta", (24, 128, 64, 128), "bf16", 51)          # BMM2's matrices, 24 batches
+    for label, cfg in [("direct-to-LDS 128x64, slab 64, 2 waves", [6, 4, 1, 2, 2, 32, 1, 1, 2, 32, 2, 64, 1]),
+                       ("64x64 tile, slab 128: body too large for direct-to-LDS, scalar", [24, 1, 2, 1, 2, 32, 1, 1, 1, 64, 1, 128, 1]),
+                       ("direct-to-LDS 32x32 tiles, slab 32", [3, 8, 4, 1, 1, 32, 2, 1, 1, 32, 4, 32, 1]),
+                       ("scalar", [4, 6, 8, 2, 2, 4, 4, 2, 4, 2, 8, 16, 1]),
+                       ("flag 0 (scalar for this operand layout)", [24, 1, 2, 2, 1, 32, 1, 2, 1, 32, 1, 128, 0])]:
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 10, seed=111, want_paths=(0, 3)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "bmm_ta", (15, 64, 64, 128), "bf16", 52)           # BMM3's matrices, odd batch
+    for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=112, want_paths=(0, 3)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    for cfg in w.random_valid(P.OPEVO_TILE4X, 4, seed=113, want_paths=(0, 3)):
+        w.check(P.OPEVO_TILE4X, cfg, "random")
+    w.close()
+
+
 # ------------------------------------------------------------------ extended variant: launch order and group width
 def test_extended_variant_every_launch_order_and_group_width(torch_cuda):
     """The PERMUTATION (order of the grid axes) and DISCRETE (group width) parameters only change
@@ -414,6 +440,8 @@ PAPER_SHAPES = [
     ("BMM1", "bmm", (960, 128, 64, 128), 1242, 6, (0, 1, 2, 3),
      [("direct-to-LDS, 15 grid rows of 64 batches", [15, 64, 2, 1, 2, 32, 1, 1, 1, 64, 2, 64, 1]),
       ("mfma16, 480 batches per workgroup", [2, 480, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0])]),
+    ("BMM2", "bmm_ta", (960, 128, 64, 128), 1245, 6, (0, 3), []),
+    ("BMM3", "bmm_ta", (960, 64, 64, 128), 1246, 6, (0, 3), []),
     ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (1, 2), []),
     # C1's reduction axis 3*11*11 = 363 has no factor 16: MFMA members stage zero-padded K slabs
     ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (1, 2),
@@ -422,7 +450,7 @@ PAPER_SHAPES = [
 
 
 def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
-    """MM2, MM3, BMM1, C1, C2 of App. B at full size (multi-prime axes: 960 = 2^6*3*5, 55 = 5*11,
+    """MM2, MM3, BMM1-3, C1, C2 of App. B at full size (multi-prime axes: 960 = 2^6*3*5, 55 = 5*11,
     27 = 3^3, 192 = 2^6*3, 363 = 3*11^2, 1600 = 2^6*5^2).  The oracle computes a seeded sample of
     rows / batches / images; the whole output must be finite (NaN pre-fill)."""
     torch = torch_cuda
@@ -435,6 +463,8 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
             ref = T.matmul_rows(w.a_host, w.b_host, idx)
         elif kind == "bmm":
             ref = T.bmm(w.a_host[idx], w.b_host[idx])
+        elif kind == "bmm_ta":
+            ref = T.bmm(np.ascontiguousarray(w.a_host[idx].transpose(0, 2, 1)), w.b_host[idx])
         else:
             ref = T.conv2d(w.b_host[idx], w.a_host, dims[7], dims[8])
         cases = [(label, cfg) for label, cfg in picked]

@@ -204,6 +204,26 @@ def test_extended_variant_decodes_to_a_linear_grid_with_the_same_tiles():
         assert ei.value.status == P.OPEVO_E_ILLEGAL
 
 
+def test_transposed_first_operand_uses_the_scalar_or_the_direct_to_lds_template():
+    op = P.opevo_op_create(P.OPEVO_BMM_TA, (960, 128, 64, 128), P.OPEVO_BF16)
+    assert P.opevo_op_sizes(op) == (960 * 128 * 128, 960 * 128 * 64, 960 * 128 * 64)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4)
+    rng = P.opevo_rng_create(5)
+    paths = set()
+    for _ in range(4000):
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, P.opevo_space_random(sp, rng))
+        if plan.status == P.OPEVO_OK:
+            paths.add(plan.path)
+    assert paths == {0, 3}
+    for cfg, path in (([160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 2, 64, 1], 3), ([160, 6, 8, 2, 2, 4, 4, 2, 4, 2, 8, 16, 1], 0)):
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == path, (cfg, plan.path, plan.reason)
+        kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4, cfg)
+        assert "-DA_TRANS=1" in P.opevo_kernel_defines(op, P.OPEVO_TILE4, cfg)
+        P.opevo_kernel_destroy(kernel)
+    P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp); P.opevo_op_destroy(op)
+
+
 EXT_COMPILE_CASES = [
     ("direct-to-LDS, m fastest, groups of 4", MM1, [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1, 1, 0, 2], 3),
     ("register-staged, n fastest, groups of 16", MM1, [2, 2, 2, 64, 8, 2, 2, 32, 64, 16, 1, 0, 1, 4], 1),
