@@ -186,13 +186,18 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     // ---- template choice
     int path = 0;   // scalar
     int64_t BKP = BK;   // width of a K slab as the MFMA template stages and multiplies it
+    int64_t TMacc = TM, TNacc = TN;   // wave tile in whole atoms (accumulator registers)
+    bool ragged = false;
     if (four_level && op.dtype != OPEVO_F32) {
         if (op.kind == OPEVO_CONV2D) {
             // The convolution's reduction axis Cin*Hk*Wk rarely has a factor 16 (3*11*11 = 363): a slab
             // of BK taps is staged zero-padded to the next multiple of the MFMA K step, and its
             // operands are gathered element by element, so no alignment is asked of it.
+            // Likewise a wave tile that is no multiple of 16 is rounded up to whole 16x16 atoms as long
+            // as that at most doubles the work (pixel tiles come from factors of 55, 27, ...).
+            const int64_t TMp = (TM + 15) / 16 * 16, TNp = (TN + 15) / 16 * 16;
             if (TM % 32 == 0 && TN % 32 == 0) { path = 1; BKP = (BK + 15) / 16 * 16; }
-            else if (TM % 16 == 0 && TN % 16 == 0) { path = 2; BKP = (BK + 31) / 32 * 32; }
+            else if (TMp * TNp <= 2 * TM * TN) { path = 2; BKP = (BK + 31) / 32 * 32; ragged = (TMp != TM || TNp != TN); TMacc = TMp; TNacc = TNp; }
         } else {
             const bool align_ok = (op.K % 8 == 0) && (op.N % 8 == 0);
             if (align_ok && TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0) path = 1;
@@ -233,12 +238,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         NT = ((BM * BN + 63) / 64) * 64;
         if (NT > 256) NT = 256;
     }
-    int64_t acc = (path == 0) ? (BM * BN + NT - 1) / NT : (TM * TN) / 64;
+    int64_t acc = (path == 0) ? (BM * BN + NT - 1) / NT : (TMacc * TNacc) / 64;
     const int nstage = path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
     else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
-    else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2;
+    else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
     p.path = path;
     const int64_t n_blocks = n1 * m1 * b1;

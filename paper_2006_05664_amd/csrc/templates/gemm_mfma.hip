@@ -22,7 +22,8 @@
 //           software-pipelined (fragments of the next step are read while this step's MFMAs run).
 // FLAG = 0: one stage, load -> barrier -> compute -> barrier; K loop not unrolled.
 // BMM only, STAGE_LDS = 0: no LDS at all, fragments are read straight from global memory.
-// Conv2d only: the reduction axis Cin*Hk*Wk rarely has a factor 16, so a slab of BK taps is
+// Conv2d only: wave tiles that are no multiple of the atom are rounded up to whole atoms (the
+//           overhang is computed and thrown away), and the reduction axis Cin*Hk*Wk rarely has a factor 16, so a slab of BK taps is
 //           staged BKP = BK rounded up to the MFMA K step wide, its tail filled with zeros; when
 //           BKP != BK the kernel tensor is read element by element (its rows are not 16-byte
 //           aligned then) with the same bounds as the image gather.
@@ -50,9 +51,13 @@ typedef f32x4 acc_t;
 #ifndef BKP
 #define BKP BK
 #endif
-constexpr int MI = TM / ATOM, NI = TN / ATOM;                 // atoms per wave tile
-constexpr int FMI = (FM % ATOM == 0) ? FM / ATOM : 1;         // atoms per basic tile
-constexpr int FNI = (FN % ATOM == 0) ? FN / ATOM : 1;
+// Atoms per wave tile.  A Conv2d wave tile need not be a multiple of the atom (pixel tiles come
+// from factors of 55, 27, ...): the last atom row / column then hangs over the tile; what it
+// computes from its neighbours' rows (or from whatever follows the stage in LDS) is never stored.
+constexpr int MI = (TM + ATOM - 1) / ATOM, NI = (TN + ATOM - 1) / ATOM;
+constexpr bool RAGGED_M = TM % ATOM != 0, RAGGED_N = TN % ATOM != 0;
+constexpr int FMI = (!RAGGED_M && FM % ATOM == 0) ? FM / ATOM : 1;   // atoms per basic tile
+constexpr int FNI = (!RAGGED_N && FN % ATOM == 0) ? FN / ATOM : 1;
 constexpr int LDA = BKP + PAD, LDB = BKP + PAD;
 __device__ __forceinline__ int lds_off(int row, int k)   // element offset of (row, k) in a stage
 {
@@ -337,6 +342,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
                 for (int r = 0; r < (ATOM == 32 ? 16 : 4); ++r) {
                     const int row = (ATOM == 32) ? 8 * (r / 4) + 4 * (lane / 32) + r % 4 : 4 * (lane / 16) + r;
+                    if ((RAGGED_M && i * ATOM + row >= TM) || (RAGGED_N && j * ATOM + lrow >= TN)) continue;
                     const int gm = m0 + wm * TM + i * ATOM + row;
                     const int cn = wn * TN + j * ATOM + lrow;   // column inside the workgroup tile
 #if OP == OP_CONV

@@ -268,7 +268,8 @@ CONV56_CASES = [
     ("mfma16 7-pixel pieces", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1]),
     ("mfma16 slab 96", [1, 1, 4, 1, 1, 16, 14, 1, 1, 4, 1, 1, 7, 8, 6, 96, 1]),
     ("mfma16, slab 24 zero-padded to 32", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
-    ("scalar", [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
+    ("mfma16, 8 x 112 wave tile rounded up to 16 x 112", [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
+    ("scalar", [1, 1, 8, 2, 1, 4, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
     ("scalar one pixel tiles", [1, 1, 8, 1, 1, 8, 56, 1, 1, 1, 8, 1, 1, 7, 64, 9, 1]),
 ]
 
@@ -306,7 +307,10 @@ def test_conv_stride_padding_kernel_shapes(torch_cuda):
     for label, cfg in [("mfma16, slab 33 padded to 64", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 11, 33, 1]),
                        ("mfma16, slab 121 padded to 128, single stage", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 3, 121, 0]),
                        ("mfma16, one slab of 363 padded to 384", [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 363, 0]),
-                       ("mfma16, 7 waves, slab 11 padded to 32", [1, 16, 1, 1, 1, 16, 1, 7, 1, 1, 7, 1, 1, 1, 33, 11, 1])]:
+                       ("mfma16, 7 waves, slab 11 padded to 32", [1, 16, 1, 1, 1, 16, 1, 7, 1, 1, 7, 1, 1, 1, 33, 11, 1]),
+                       ("mfma16, 28-pixel wave tile rounded up to 32", [4, 4, 1, 1, 1, 16, 7, 1, 1, 1, 1, 1, 1, 7, 11, 33, 1]),
+                       ("mfma16, 7 waves of 16 x 8 rounded up to 16 x 16", [2, 8, 1, 1, 2, 8, 1, 7, 1, 1, 7, 1, 1, 1, 3, 121, 0]),
+                       ("mfma16, one wave, 784 pixels", [1, 16, 1, 1, 1, 16, 1, 1, 1, 7, 1, 1, 7, 1, 33, 11, 1])]:
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(0, 2)):
         w.check(P.OPEVO_TILE4, cfg, "random")

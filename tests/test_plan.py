@@ -92,7 +92,12 @@ def test_four_level_spaces_cover_the_output_once_and_are_not_mostly_invalid(kd):
             assert plan.block <= 1024 and plan.lds_bytes <= 160 * 1024 and plan.acc_per_lane <= 256
             if plan.path:
                 atom = 16 if plan.path == 2 else 32
-                assert plan.wave_tile[0] % atom == 0 and plan.wave_tile[1] % atom == 0
+                if kd[0] == P.OPEVO_CONV2D and plan.path == 2:
+                    # convolution wave tiles are rounded up to whole atoms when that at most doubles the work
+                    up = [(t + 15) // 16 * 16 for t in plan.wave_tile]
+                    assert up[0] * up[1] <= 2 * plan.wave_tile[0] * plan.wave_tile[1]
+                else:
+                    assert plan.wave_tile[0] % atom == 0 and plan.wave_tile[1] % atom == 0
         else:
             assert plan.reason
     assert n_valid > 0.04 * total, "space almost entirely invalid: Eq. 2 would have nothing to select"
@@ -113,7 +118,8 @@ COMPILE_CASES = [
     ("bmm direct", BMM, P.OPEVO_BF16, P.OPEVO_TILE4, [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0], 1),
     ("conv mfma", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1], 2),
     ("conv mfma16, slab 24 padded to 32", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 2),
-    ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
+    ("conv mfma16, 8-row wave tile rounded up to one atom", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 2),
+    ("conv scalar", CONV56, P.OPEVO_BF16, P.OPEVO_TILE4, [1, 1, 8, 2, 1, 4, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
     ("conv mfma32, odd reduction axis, slab 121 padded to 128", (P.OPEVO_CONV2D, (32, 3, 19, 19, 32, 11, 11, 4, 0)), P.OPEVO_BF16,
      P.OPEVO_TILE4, [1, 32, 1, 1, 1, 32, 3, 1, 1, 1, 3, 1, 1, 1, 3, 121, 1], 1),
     ("conv batch mfma", CONV14, P.OPEVO_BF16, P.OPEVO_TILE4, [8, 4, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 36, 64, 1], 2),
