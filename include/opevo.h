@@ -171,6 +171,9 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         Conv2d  B(2) Cout(4) H(4) W(4) R(2) unroll{0,1},  R = Cin*Hk*Wk
  *         MFMA kernels (bf16/fp16 inputs) where the per-wave tile is made of 32x32 or 16x16
  *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise.
+ *         Conv2d widens this: an LDS tile of any length is zero-padded to whole K-steps, and a
+ *         per-wave tile that is no multiple of 16 is rounded up to whole 16x16 atoms as long as
+ *         that at most doubles the work (the overhang is computed and not stored).
  *  TILE4X: TILE4 plus the two remaining parameter types of Sec. 3 as launch tunables.  The
  *         workgroups are launched as a one-dimensional grid and walk the grid axes (0 = N tiles,
  *         1 = M tiles, 2 = batch blocks of a BMM) in the order given by a PERMUTATION parameter
@@ -231,9 +234,30 @@ int opevo_compile_pool_kind(int *kind);
 
 /* Instantiate: render + hipRTC-compile for gfx950 (works without a GPU).  Returns
  * OPEVO_E_INVALID for an invalid configuration (no kernel), OPEVO_E_HIPRTC on a compile
- * failure.  The module is loaded on the first launch. */
+ * failure.  The module is loaded on the first launch.  Two checks on the compiled code of the
+ * direct-to-LDS template (path 3), whose hand-placed waits count the loads in flight and so
+ * need the fully unrolled, spill-free code: a code object above 128 KiB (the compiler did not
+ * unroll the schedule) makes this call return OPEVO_E_INVALID, and a kernel that uses private
+ * scratch memory makes its first launch / timing return OPEVO_E_INVALID; opevo_tune scores
+ * both as invalid trials. */
 int opevo_kernel_build(const opevo_op *op, int variant, const int32_t *cfg,
                        opevo_kernel **out, double *compile_ms);
+/* Compiling is by far the longest part of a trial (Sec. 6 gives it 8 CPU threads), and runs of
+ * Alg. 1 that differ in seed, q or lambda revisit many configurations.  opevo_kernel_build (and
+ * through it opevo_tune) therefore keeps every code object it compiled, keyed by the template
+ * text, the member's constants and the compiler options: in memory, up to max_memory_bytes
+ * (default 256 MiB, oldest dropped first, 0 switches it off, negative keeps the current limit),
+ * and, if dir is not NULL / empty, also as one file per entry in that directory (created if
+ * missing; files appear by rename, so processes may share it; a file that does not match its key
+ * or is damaged is ignored and compiled again).  Without this call the directory is taken from the
+ * environment variable OPEVO_CODE_CACHE_DIR, if set.  A hit makes compile_ms the look-up time.
+ * OPEVO_E_ARG if dir cannot be created or written.  _clear drops the in-memory entries (files
+ * stay).  _stats: look-ups answered from the cache (disk_hits of them from a file), look-ups that
+ * had to compile, entries and bytes held in memory; any pointer may be NULL. */
+int opevo_code_cache_configure(const char *dir, int64_t max_memory_bytes);
+int opevo_code_cache_clear(void);
+int opevo_code_cache_stats(int64_t *hits, int64_t *disk_hits, int64_t *misses, int64_t *entries,
+                           int64_t *bytes);
 int opevo_kernel_destroy(opevo_kernel *kernel);
 int opevo_kernel_code_size(const opevo_kernel *kernel, size_t *bytes);
 /* Registers / scratch the compiler used (available after the first launch loaded it). */

@@ -124,6 +124,9 @@ _SIGNATURES = {
     "opevo_kernel_build": [_vp, C.c_int, _i32p, C.POINTER(_vp), _f64p],
     "opevo_kernel_destroy": [_vp],
     "opevo_kernel_code_size": [_vp, C.POINTER(C.c_size_t)],
+    "opevo_code_cache_configure": [C.c_char_p, C.c_int64],
+    "opevo_code_cache_clear": [],
+    "opevo_code_cache_stats": [C.POINTER(C.c_int64)] * 5,
     "opevo_kernel_resources": [_vp, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)],
     "opevo_kernel_launch": [_vp, _vp, _vp, _vp, _vp],
     "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_double, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
@@ -449,6 +452,20 @@ def opevo_compile_pool_kind() -> int:
     k = C.c_int()
     _check(lib.opevo_compile_pool_kind(C.byref(k)))
     return k.value
+
+
+def opevo_code_cache_configure(directory=None, max_memory_bytes: int = -1) -> None:
+    _check(lib.opevo_code_cache_configure(directory.encode() if directory else None, max_memory_bytes))
+
+
+def opevo_code_cache_clear() -> None:
+    _check(lib.opevo_code_cache_clear())
+
+
+def opevo_code_cache_stats() -> dict:
+    v = [C.c_int64() for _ in range(5)]
+    _check(lib.opevo_code_cache_stats(*[C.byref(x) for x in v]))
+    return dict(zip(("hits", "disk_hits", "misses", "entries", "bytes"), (x.value for x in v)))
 
 
 def opevo_kernel_plan(op, variant: int, cfg) -> opevo_plan:

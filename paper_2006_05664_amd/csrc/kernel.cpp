@@ -9,6 +9,7 @@
 #include <new>
 #include <sstream>
 
+#include "code_cache.hpp"
 #include "pool.hpp"
 
 namespace opevo {
@@ -30,7 +31,10 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     if (int rc = decode(op, variant, cfg, d)) return rc;
     if (d.plan.status != OPEVO_OK) return fail(OPEVO_E_INVALID, "invalid configuration: %s", d.plan.reason);
     const auto t0 = std::chrono::steady_clock::now();
-    CompileResult r = pool_compile(d.tmpl, d.defines);
+    const std::string key = code_cache_key(d.tmpl, d.defines);
+    CompileResult r;
+    const bool cached = code_cache_get(key, r.code);
+    if (!cached) r = pool_compile(d.tmpl, d.defines);
     if (r.status != OPEVO_OK)
         return fail(r.status, "hipRTC failed for [%s]: %s", d.defines.c_str(), r.log.c_str());
     // A direct-to-LDS member whose K loop did not unroll compiles into a code object of hundreds of
@@ -40,6 +44,7 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     if (d.plan.path == 3 && r.code.size() > (128u << 10))
         return fail(OPEVO_E_INVALID, "direct-to-LDS template did not unroll (code object of %zu bytes) [%s]",
                     r.code.size(), d.defines.c_str());
+    if (!cached) code_cache_put(key, r.code);
     opevo_kernel *k = new (std::nothrow) opevo_kernel;
     if (!k) return fail(OPEVO_E_ARG, "out of memory");
     k->code = std::move(r.code);

@@ -23,6 +23,23 @@ namespace opevo {
 
 const char *template_source(const char *name);
 
+namespace {
+const char *const kFixedOptions[] = {"--offload-arch=gfx950", "-O3", "-std=c++17",
+                                     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                                     "-mllvm", "-pragma-unroll-threshold=400000"};
+}
+
+// The fixed options as one string: part of the key under which a code object is cached.
+const char *compile_options_tag()
+{
+    static const std::string tag = [] {
+        std::string t;
+        for (const char *o : kFixedOptions) t += std::string(o) + " ";
+        return t;
+    }();
+    return tag.c_str();
+}
+
 CompileResult compile_source(const std::string &tmpl, const std::string &defines)
 {
     CompileResult res;
@@ -62,9 +79,7 @@ CompileResult compile_source(const std::string &tmpl, const std::string &defines
     // mark every loop over them for full unrolling; the compiler's default size limit for such
     // loops makes it give up on the larger members, which then compile (slowly) into code objects
     // of megabytes that index those arrays through select chains.
-    opts.insert(opts.end(), {"--offload-arch=gfx950", "-O3", "-std=c++17",
-                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                             "-mllvm", "-pragma-unroll-threshold=400000"});
+    for (const char *o : kFixedOptions) opts.push_back(o);
     std::vector<const char *> optv;
     for (const auto &o : opts) optv.push_back(o.c_str());
     r = hiprtcCompileProgram(prog, int(optv.size()), optv.data());
