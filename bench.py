@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mm8192_bf16")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--split-reduction", action="store_true",
+                    help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
     ap.add_argument("--extended", action="store_true",
                     help="tune in the extended space (launch order as a permutation, group width as a discrete parameter)")
     ap.add_argument("--oracle-rows", type=int, default=96, help="rows of C the CPU oracle computes (8192^3 only)")
@@ -70,6 +72,11 @@ def main() -> int:
     kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
     variant = P.OPEVO_TILE2 if dtype == "f32" else (P.OPEVO_TILE4X if args.extended else P.OPEVO_TILE4)
+    if args.split_reduction:
+        if w["kind"] != "conv2d":
+            print("bench.py: --split-reduction is a Conv2d space", file=sys.stderr)
+            return 2
+        variant = P.OPEVO_TILE4P
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
     flops = P.opevo_op_flops(op)
     a_host, b_host = synth.workload_inputs(args.workload)
@@ -183,7 +190,7 @@ def main() -> int:
         "ms_per_step": round(wall / max(1, res["n_trials"]) * 1e3, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s %s dims=%s" % (args.workload, w["kind"], list(w["dims"])), "trials": int(res["n_trials"]),
-                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": "TILE4X" if variant == P.OPEVO_TILE4X else ("TILE2" if variant == P.OPEVO_TILE2 else "TILE4"),
+                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {P.OPEVO_TILE2: "TILE2", P.OPEVO_TILE4: "TILE4", P.OPEVO_TILE4X: "TILE4X", P.OPEVO_TILE4P: "TILE4P"}[variant],
                    "best_cfg": [int(x) for x in res["best_cfg"]], "frac_of_peak": round(best / PEAK_TFLOPS[dtype], 4),
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),

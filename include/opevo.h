@@ -181,8 +181,18 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         is the number of consecutive tiles of the second axis that are walked together (each
  *         group goes through the whole first axis before the next group starts), which decides
  *         what the workgroups resident at one time share in L2.  Flat encoding: the TILE4 slots,
- *         then the permutation (2 or 3 slots), then the index of the group width. */
-typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2 } opevo_variant;
+ *         then the permutation (2 or 3 slots), then the index of the group width.
+ *  TILE4P: Conv2d only, the space as App. B.3 lays it out: the reduction axes are split
+ *         separately,
+ *         Conv2d  B(2) Cout(4) H(4) W(4) Cin(2) Hk(2) Wk(2) unroll{0,1} unroll_steps{1,2,4,8}
+ *         so a K slab is a box of Cin_inner x Hk_inner x Wk_inner taps and the kernel walks the
+ *         Cin_outer x Hk_outer x Wk_outer boxes in row-major order (a different summation order
+ *         from TILE4's flattened walk, the same sum).  unroll_steps (DISCRETE) is the number of
+ *         reduction steps unrolled together where the reduction is a loop: the scalar template's
+ *         K loop when unroll = 1 (explicit pragma), the MFMA template's loop over the K steps of
+ *         a slab when unroll = 0 (with unroll = 1 that template is fully unrolled and pipelined
+ *         anyway).  Kernel templates, padding of slabs and rounding of wave tiles as for TILE4. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]

@@ -35,6 +35,8 @@ static opevo_param_desc factor(const char *name, int64_t C, int nu)
 
 static const double kGroupValues[] = {1, 2, 4, 8, 16};
 static const int kNumGroupValues = 5;
+static const double kUnrollSteps[] = {1, 2, 4, 8};
+static const int kNumUnrollSteps = 4;
 
 static opevo_param_desc permutation(const char *name, int n)
 {
@@ -66,6 +68,16 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
     if (variant == OPEVO_TILE2) {
         if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the two-level space exists for MatMul only");
         descs = {factor("M", op.M, 2), factor("N", op.N, 2), factor("K", op.K, 2)};
+        return OPEVO_OK;
+    }
+    if (variant == OPEVO_TILE4P) {
+        // App. B.3: C_out, H_out, W_out in four factors, C_in, H_k, W_k in two factors each, the binary
+        // choice of an explicit unroll and the discrete bound on the unrolled steps; the batch
+        // split is kept from the four-level space
+        if (op.kind != OPEVO_CONV2D) return fail(OPEVO_E_ARG, "the separately split reduction space exists for Conv2d only");
+        descs = {factor("B", op.nimg, 2), factor("Cout", op.M, 4), factor("H", op.hout, 4), factor("W", op.wout, 4),
+                 factor("Cin", op.cin, 2), factor("Hk", op.hk, 2), factor("Wk", op.wk, 2), flag("unroll"),
+                 discrete("unroll_steps", kUnrollSteps, kNumUnrollSteps)};
         return OPEVO_OK;
     }
     if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
@@ -144,7 +156,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t BM = 1, BN = 1, BK = 1, ksteps = 1, WM = 1, WN = 1, TM = 1, TN = 1, FM = 1, FN = 1;
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
-    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X);
+    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P);
+    int64_t box[6] = {1, 1, 1, 1, 1, 1};   // C_in, H_k, W_k as (boxes, box extent) pairs
+    bool tap_box = false;
+    int64_t kunroll = 0;                   // 0: the template's default
     int tile4_width = 0;   // slots of the four-level part, after which the launch-order parameters follow
 
     if (!four_level) {
@@ -169,9 +184,22 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         TN = nb2 * h[2] * h[3] * w[2] * w[3];
         FN = nb2 * h[3] * w[3];
         n1 = nb1 * h1 * w1;
-        ksteps = c[14]; BK = c[15]; flagv = c[16];
+        if (variant == OPEVO_TILE4P) {
+            for (int j = 0; j < 6; ++j) box[j] = c[14 + j];
+            ksteps = box[0] * box[2] * box[4];
+            BK = box[1] * box[3] * box[5];
+            flagv = c[20];
+            kunroll = int64_t(kUnrollSteps[c[21]]);
+            // a box that spans whole kernel rows (and whole kernel planes if it holds several
+            // channels) is a contiguous run of the flattened reduction axis: the plain walk
+            const bool contiguous = (box[5] == op.wk || (box[3] == 1 && box[1] == 1)) && (box[3] == op.hk || box[1] == 1);
+            tap_box = !contiguous;
+            tile4_width = 22;
+        } else {
+            ksteps = c[14]; BK = c[15]; flagv = c[16];
+            tile4_width = 17;
+        }
         BM = WM * TM; BN = WN * TN;
-        tile4_width = 17;
     }
     // extended variant: launch order and group width
     const bool linear = (variant == OPEVO_TILE4X);
@@ -276,7 +304,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     {
         std::ostringstream nm;
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
-           << (four_level ? "4" : "2");
+           << (variant == OPEVO_TILE4P ? "p" : four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
@@ -297,6 +325,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
           << " -DHOUT=" << op.hout << " -DWOUT=" << op.wout << " -DNB2=" << nb2 << " -DBH=" << BH
           << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1 << " -DBKP=" << BKP;
     }
+    if (tap_box)
+        D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
+          << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
+    if (kunroll) D << " -DKUNROLL=" << kunroll;
     if (linear)
         D << " -DGRID_LINEAR=1 -DGRID_N1=" << n1 << " -DGRID_M1=" << m1 << " -DGRID_B1=" << b1 << " -DORDER0=" << order[0]
           << " -DORDER1=" << order[1] << " -DORDER2=" << order[2] << " -DGROUP=" << group;

@@ -81,9 +81,26 @@ __device__ __forceinline__ ColBlock col_block(int bx)
     cb.nb0 = (bx / (W1 * H1)) * NB2;
     return cb;
 }
-// B[k][c] of the implicit GEMM: image value under tap k for column c of the block.
-__device__ __forceinline__ in_t conv_b(const in_t *__restrict__ img, const ColBlock &cb, int k, int c)
+// Position k of the reduction as the kernel walks it -> flattened tap (ci*HK + r)*WK + s.
+// By default the walk is the flattened order itself.  With TAP_BOX the three reduction axes are
+// split separately (App. B.3: C_in, H_k and W_k in two factors each): slab k / BK is the box
+// number (cio, ro, so), row-major over CI_O x HK_O x WK_O boxes, and k % BK is the place
+// (a, b, c) inside the CI_I x HK_I x WK_I box, row-major as well.
+__device__ __forceinline__ int conv_tap(int k)
 {
+#ifdef TAP_BOX
+    const int kt = k / BK, j = k % BK;
+    const int so = kt % WK_O, ro = (kt / WK_O) % HK_O, cio = kt / (WK_O * HK_O);
+    const int c = j % WK_I, b = (j / WK_I) % HK_I, a = j / (WK_I * HK_I);
+    return ((cio * CI_I + a) * HK + ro * HK_I + b) * WK + so * WK_I + c;
+#else
+    return k;
+#endif
+}
+// B[k][c] of the implicit GEMM: image value under position k of the reduction for column c of the block.
+__device__ __forceinline__ in_t conv_b(const in_t *__restrict__ img, const ColBlock &cb, int kpos, int c)
+{
+    const int k = conv_tap(kpos);
     const int ci = k / (HK * WK), r = (k / WK) % HK, s = k % WK;
     const int nb = cb.nb0 + c / (BH * BW);
     const int y = (cb.y0 + (c / BW) % BH) * STRIDE + r - PAD_CONV;

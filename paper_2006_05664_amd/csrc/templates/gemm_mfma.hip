@@ -20,13 +20,15 @@
 //           before the MFMAs of slab kt, slab kt+1 (loaded one step earlier) is written to the
 //           other stage after them (one barrier per slab); the MFMA loop is fully unrolled and
 //           software-pipelined (fragments of the next step are read while this step's MFMAs run).
-// FLAG = 0: one stage, load -> barrier -> compute -> barrier; K loop not unrolled.
+// FLAG = 0: one stage, load -> barrier -> compute -> barrier; KUNROLL MFMA K steps of a slab are
+//           unrolled together (1 unless the configuration space has a parameter for it).
 // BMM only, STAGE_LDS = 0: no LDS at all, fragments are read straight from global memory.
 // Conv2d only: wave tiles that are no multiple of the atom are rounded up to whole atoms (the
 //           overhang is computed and thrown away), and the reduction axis Cin*Hk*Wk rarely has a factor 16, so a slab of BK taps is
 //           staged BKP = BK rounded up to the MFMA K step wide, its tail filled with zeros; when
 //           BKP != BK the kernel tensor is read element by element (its rows are not 16-byte
-//           aligned then) with the same bounds as the image gather.
+//           aligned then) with the same bounds as the image gather, and so it is when the slabs
+//           are boxes of separately split C_in, H_k and W_k (TAP_BOX: not contiguous in memory).
 
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
@@ -48,6 +50,18 @@ typedef f32x4 acc_t;
 #define MFMA(a, b, c) MFMA_16(a, b, c)
 #endif
 
+#if OP == OP_CONV && defined(TAP_BOX)
+#define GATHER_A 1
+#define A_TAP(k) conv_tap(k)
+#else
+#define GATHER_A 0
+#define A_TAP(k) (k)
+#endif
+#ifndef KUNROLL
+#define KUNROLL 1   // reduction steps of the non-pipelined (FLAG = 0) loop unrolled together
+#endif
+#define PRAGMA_(x) _Pragma(#x)
+#define PRAGMA_UNROLL(n) PRAGMA_(unroll n)
 #ifndef BKP
 #define BKP BK
 #endif
@@ -99,13 +113,14 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
         const int q = tid + i * NT;
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
             const int row = q / (BKP / 8), kc = q % (BKP / 8);
-            if (BKP == BK) {
+            if (BKP == BK && !GATHER_A) {
                 s.a[i] = *(const u32x4 *)(Ab + (long)(m0 + row) * K + k0 + kc * 8);
-            } else {   // padded slab: taps past BK are zeros, rows start at any 2-byte offset
+            } else {   // padded slab: taps past BK are zeros, rows start at any 2-byte offset;
+                       // boxed reduction walk: the taps of a slab are not contiguous
                 u32 h[8];
 #pragma unroll
                 for (int t = 0; t < 8; ++t)
-                    h[t] = (kc * 8 + t < BK) ? (u32)Ab[(long)(m0 + row) * K + k0 + kc * 8 + t] : 0u;
+                    h[t] = (kc * 8 + t < BK) ? (u32)Ab[(long)(m0 + row) * K + A_TAP(k0 + kc * 8 + t)] : 0u;
                 u32x4 v;
                 v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
                 v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
@@ -215,7 +230,7 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As
                 acc[i0 + i][j0 + j] = MFMA(af[t & 1][i], bf[t & 1][j], acc[i0 + i][j0 + j]);
     }
 #else
-#pragma unroll 1
+    PRAGMA_UNROLL(KUNROLL)
     for (int kk = 0; kk < BKP / KA; ++kk) {
 #pragma unroll
         for (int tt = 0; tt < TI * TJ; ++tt) {

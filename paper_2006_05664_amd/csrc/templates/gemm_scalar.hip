@@ -14,6 +14,12 @@
 // after the slab's first barrier, the whole workgroup leaves together.  The host then
 // scores the trial as invalid (fitness 0).
 
+#ifndef KUNROLL
+#define KUNROLL 4   // reduction steps unrolled together where the flag asks for unrolling
+#endif
+#define PRAGMA_(x) _Pragma(#x)
+#define PRAGMA_UNROLL(n) PRAGMA_(unroll n)
+
 extern "C" __global__ __launch_bounds__(NT)
 void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *__restrict__ C,
                   unsigned long long *ctl)
@@ -58,6 +64,8 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
             for (int i = tid; i < BM * BK; i += NT)
 #if A_TRANS   // first operand stored [K][M]: walk it along M so that the loads stay coalesced
                 As[(i % BM) * BK + i / BM] = to_f32(Ab[(long)(k0 + i / BM) * M + m0 + i % BM]);
+#elif OP == OP_CONV
+                As[i] = to_f32(Ab[(long)(m0 + i / BK) * K + conv_tap(k0 + i % BK)]);
 #else
                 As[i] = to_f32(Ab[(long)(m0 + i / BK) * K + k0 + i % BK]);
 #endif
@@ -70,7 +78,7 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
             }
             __syncthreads();
 #if FLAG
-#pragma unroll 4
+            PRAGMA_UNROLL(KUNROLL)
 #else
 #pragma unroll 1
 #endif

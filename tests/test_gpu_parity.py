@@ -489,6 +489,61 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
         w.close()
 
 
+# ------------------------------------------------------------------ Conv2d space of App. B.3: C_in, H_k, W_k split separately
+HEAD_C2 = [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2]            # 32 x 32 wave tile, 4 images per tile
+HEAD_C2_SCALAR = [4, 1, 4, 2, 1, 4, 3, 1, 2, 2, 3, 2, 1, 2]      # 4 x 8 wave tile
+HEAD_C1 = [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1]           # 16 x 16 wave tile: one pixel of 16 images
+
+
+def test_conv_with_separately_split_reduction_axes(torch_cuda):
+    """K slabs that are boxes of C_in x H_k x W_k taps (a different summation order, the same sum),
+    every value of the discrete unroll bound on both kinds of template, and one run of Alg. 1 over
+    the nine-parameter space whose trajectory the oracle's Alg. 1 reproduces."""
+    V = P.OPEVO_TILE4P
+    w = Workload(torch_cuda, "conv2d", (4, 16, 12, 12, 32, 5, 5, 1, 2), "bf16", 46)     # R = 16*5*5
+    cases = [("mfma32, box 4x1x5 padded to 32, pipelined", HEAD_C2 + [4, 4, 5, 1, 1, 5, 1, 0]),
+             ("mfma32, box 8x5x1 padded to 48", HEAD_C2 + [2, 8, 1, 5, 5, 1, 1, 2]),
+             ("mfma32, box of one tap", HEAD_C2 + [16, 1, 5, 1, 5, 1, 1, 0]),
+             ("mfma32, box 16x1x1 (one tap of every channel)", HEAD_C2 + [1, 16, 5, 1, 5, 1, 0, 1]),
+             ("mfma32, whole reduction in one box", HEAD_C2 + [1, 16, 1, 5, 1, 5, 0, 3])]
+    cases += [("mfma32, box 2x5x5 (contiguous), loop unrolled by %d" % (1 << i), HEAD_C2 + [8, 2, 1, 5, 1, 5, 0, i]) for i in range(4)]
+    cases += [("mfma32, box 4x5x1, loop unrolled by %d" % (1 << i), HEAD_C2 + [4, 4, 1, 5, 5, 1, 0, i]) for i in range(4)]
+    cases += [("scalar, box 4x1x5, unrolled by %d" % (1 << i), HEAD_C2_SCALAR + [4, 4, 5, 1, 1, 5, 1, i]) for i in range(4)]
+    cases += [("scalar, box 2x5x1, rolled", HEAD_C2_SCALAR + [8, 2, 1, 5, 5, 1, 0, 2])]
+    for label, cfg in cases:
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 12, seed=808, want_paths=(0, 1, 2)):
+        w.check(V, cfg, "random")
+    # Alg. 1 over the nine parameters, parity-gated, against the oracle's search given the same fitness
+    ref = torch_cuda.from_numpy(w.ref.astype(np.float32).ravel()).cuda()
+    res = P.opevo_tune(w.op, V, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), ref.data_ptr(), w.stream,
+                       trials=40, lambda_=8, rho=8, q=0.5, seed=3, compile_threads=8, warmup=2, samples=3,
+                       trial_timeout_ms=100.0)
+    logs = res["logs"]
+    assert res["n_trials"] == 40 and res["n_parity_fail"] == 0 and res["n_compile_fail"] == 0
+    from oracle import search as S
+    osp = S.Space([S.Factor(4, 2), S.Factor(32, 4), S.Factor(12, 4), S.Factor(12, 4), S.Factor(16, 2),
+                   S.Factor(5, 2), S.Factor(5, 2), S.Categorical(2), S.Discrete([1, 2, 4, 8])])
+    t, i = S.OpEvo(osp, 8, 8, 0.5, 3), 0
+    while i < 40:
+        xs = t.ask(40 - i)
+        assert [osp.flat(x) for x in xs] == [list(c) for c in logs["cfg"][i:i + len(xs)]]
+        t.tell(xs, list(logs["fitness"][i:i + len(xs)]))
+        i += len(xs)
+    w.check(V, res["best_cfg"], "tuned best")
+    _say("  best %.2f TFLOP/s: %s" % (res["best_tflops"], list(res["best_cfg"])))
+    w.close()
+    # 11 x 11 kernel, stride 4, three channels: boxes of one kernel row / one kernel column
+    w = Workload(torch_cuda, "conv2d", (16, 3, 35, 35, 16, 11, 11, 4, 0), "bf16", 47)
+    for label, cfg in [("mfma16, box 1x1x11 (one kernel row) padded to 32", HEAD_C1 + [3, 1, 11, 1, 1, 11, 1, 0]),
+                       ("mfma16, box 3x1x1 padded to 32, single stage", HEAD_C1 + [1, 3, 11, 1, 11, 1, 0, 3]),
+                       ("mfma16, box 3x11x1 (one kernel column of every channel)", HEAD_C1 + [1, 3, 1, 11, 11, 1, 1, 1])]:
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 6, seed=909, want_paths=(0, 2)):
+        w.check(V, cfg, "random")
+    w.close()
+
+
 # ------------------------------------------------------------------ harness pieces
 def test_compare_f32_matches_numpy(torch_cuda):
     torch = torch_cuda

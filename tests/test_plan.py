@@ -247,3 +247,69 @@ def test_extended_variant_templates_compile(label, kd, cfg, path):
     kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4X, cfg)
     assert P.opevo_kernel_code_size(kernel) > 1000
     P.opevo_kernel_destroy(kernel)
+
+
+# ------------------------------------------------------------------ Conv2d space with separately split reduction axes
+C2_SMALL = (P.OPEVO_CONV2D, (4, 16, 12, 12, 32, 5, 5, 1, 2))
+C1_SMALL = (P.OPEVO_CONV2D, (16, 3, 35, 35, 16, 11, 11, 4, 0))
+
+
+def test_separately_split_reduction_space_follows_app_b3():
+    """App. B.3: C_out, H_out, W_out in four factors, C_in, H_k, W_k in two, a binary unroll choice
+    and a discrete bound on the unrolled steps (the batch split is this build's addition)."""
+    op = _op(C2_SMALL, P.OPEVO_BF16)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4P)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["B", "Cout", "H", "W", "Cin", "Hk", "Wk", "unroll", "unroll_steps"]
+    assert P.opevo_space_width(sp) == 22
+    sizes = [P.opevo_space_param_size(sp, i) for i in range(9)]
+    # ordered 2-factorisations: 4 = 2^2 -> 3, 16 = 2^4 -> 5, 5 -> 2; 4-factorisations: 32 = 2^5 -> C(8,3),
+    # 12 = 2^2*3 -> C(5,3)*C(4,3)
+    assert sizes == [3, 56, 40, 40, 5, 2, 2, 2, 4]
+    P.opevo_space_destroy(sp)
+    # the other operators have no such space
+    with pytest.raises(P.OpevoError):
+        P.opevo_op_space(_op(MM1, P.OPEVO_BF16), P.OPEVO_TILE4P)
+    with pytest.raises(P.OpevoError):
+        P.opevo_op_space(_op(BMM, P.OPEVO_BF16), P.OPEVO_TILE4P)
+
+
+def test_boxes_that_are_contiguous_runs_use_the_plain_walk():
+    op = _op(C2_SMALL, P.OPEVO_BF16)
+    head = [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2]
+    boxed = head + [4, 4, 5, 1, 1, 5, 1, 0]            # 4 channels x 1 row x 5 taps
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4P, boxed)
+    assert plan.status == P.OPEVO_OK and plan.path == 1 and plan.tile[2] == 20
+    d = P.opevo_kernel_defines(op, P.OPEVO_TILE4P, boxed)
+    assert "-DTAP_BOX=1" in d and "-DCI_O=4 -DCI_I=4 -DHK_O=5 -DHK_I=1 -DWK_O=1 -DWK_I=5" in d
+    assert "-DKSTEPS=20" in d and "-DBKP=32" in d and "-DKUNROLL=1" in d
+    for box, bk in (([8, 2, 1, 5, 1, 5], 50),          # whole kernel planes of 2 channels
+                    ([16, 1, 5, 1, 1, 5], 5),          # one kernel row
+                    ([16, 1, 5, 1, 5, 1], 1)):         # one tap
+        cfg = head + box + [0, 3]
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4P, cfg)
+        d = P.opevo_kernel_defines(op, P.OPEVO_TILE4P, cfg)
+        assert plan.status == P.OPEVO_OK and plan.tile[2] == bk and "TAP_BOX" not in d and "-DKUNROLL=8" in d
+    # illegal: Hk factors must multiply to 5, the step index must exist
+    with pytest.raises(P.OpevoError):
+        P.opevo_kernel_plan(op, P.OPEVO_TILE4P, head + [4, 4, 2, 2, 1, 5, 1, 0])
+    with pytest.raises(P.OpevoError):
+        P.opevo_kernel_plan(op, P.OPEVO_TILE4P, head + [4, 4, 5, 1, 1, 5, 1, 4])
+
+
+BOX_COMPILE_CASES = [
+    ("mfma32 boxed, pipelined", C2_SMALL, [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 4, 4, 5, 1, 1, 5, 1, 0], 1),
+    ("mfma32 boxed, loop unrolled by 2", C2_SMALL, [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 2, 8, 1, 5, 5, 1, 0, 1], 1),
+    ("mfma16 boxed C1-like", C1_SMALL, [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 3, 1, 11, 1, 1, 11, 1, 0], 2),
+    ("scalar boxed, unrolled by 8", C2_SMALL, [4, 1, 4, 2, 1, 4, 3, 1, 2, 2, 3, 2, 1, 2, 4, 4, 1, 5, 5, 1, 1, 3], 0),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg,path", BOX_COMPILE_CASES, ids=[c[0] for c in BOX_COMPILE_CASES])
+def test_separately_split_reduction_templates_compile(label, kd, cfg, path):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4P, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4P, cfg)
+    assert P.opevo_kernel_code_size(kernel) > 1000
+    P.opevo_kernel_destroy(kernel)
