@@ -324,6 +324,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
           << " -DWK=" << op.wk << " -DSTRIDE=" << op.stride << " -DPAD_CONV=" << op.pad
           << " -DHOUT=" << op.hout << " -DWOUT=" << op.wout << " -DNB2=" << nb2 << " -DBH=" << BH
           << " -DBW=" << BW << " -DH1=" << h1 << " -DW1=" << w1 << " -DBKP=" << BKP;
+        // the MFMA template gathers the image through a compile-time table of tap offsets where its
+        // fields are wide enough (byte offsets into the image tensor in 32 bits, padded image
+        // coordinates in 15) and the table stays small (8 bytes per position of the reduction walk)
+        const bool table = path != 0 && op.b_elems() < (int64_t(1) << 31) && op.hin + 2 * op.pad < 32768 &&
+                           op.win + 2 * op.pad < 32768 && op.hk < 32768 && op.wk < 32768 && ksteps * BKP <= 8192;
+        if (path != 0) D << " -DCONV_TABLE=" << (table ? 1 : 0);
     }
     if (tap_box)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]

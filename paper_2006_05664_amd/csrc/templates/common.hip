@@ -86,7 +86,7 @@ __device__ __forceinline__ ColBlock col_block(int bx)
 // split separately (App. B.3: C_in, H_k and W_k in two factors each): slab k / BK is the box
 // number (cio, ro, so), row-major over CI_O x HK_O x WK_O boxes, and k % BK is the place
 // (a, b, c) inside the CI_I x HK_I x WK_I box, row-major as well.
-__device__ __forceinline__ int conv_tap(int k)
+__host__ __device__ constexpr int conv_tap(int k)
 {
 #ifdef TAP_BOX
     const int kt = k / BK, j = k % BK;

@@ -90,6 +90,62 @@ constexpr int B_CHUNKS = (BK / KB) * (BN / 8);
 #endif
 constexpr int NB = (B_CHUNKS + NT - 1) / NT;
 
+#if OP == OP_CONV
+#ifndef CONV_TABLE
+#define CONV_TABLE 0
+#endif
+#if CONV_TABLE
+// Image gather through a table.  Taken element by element, the gather spends some thirty integer
+// instructions per value on splitting the tap into (ci, r, s) and the column into (image, y, x),
+// several times what the MFMAs of the slab cost.  Both splits are hoisted.  The tap's part is
+// a table built at compile time, two words per position of the reduction walk as the slabs
+// stage it (KSTEPS slabs of BKP positions, the positions past BK of each slab unused):
+//   off2 = byte offset of the tap inside one image, 2*((ci*HIN + r)*WIN + s);   rs = r << 16 | s.
+// The column's part is {base2 = byte offset of the pixel under tap (0, 0, 0), which lies outside the
+// tensor for padded borders and is kept modulo 2^32; yx = that pixel's y << 16 | x as two
+// wrapping 16-bit fields}, computed once per thread before the K loop when the thread's columns
+// repeat with a short period over its pieces, else once per piece.  Per value that leaves one
+// packed add (yx + rs, the two fields independent), one packed minimum against (HIN-1, WIN-1) and
+// a compare (a coordinate below zero wraps to a large field), one add for the address, the load
+// and two selects.  The host only selects this path if the fields are wide enough.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+constexpr int NTAB = KSTEPS * BKP;
+struct ConvTable { u32 e[2 * NTAB]; };   // 8 positions = {off2[0..8), rs[0..8)}: 64 bytes
+constexpr ConvTable make_conv_table()
+{
+    ConvTable t{};
+    for (int kt = 0; kt < KSTEPS; ++kt)
+        for (int j = 0; j < BKP; ++j) {
+            u32 off2 = 0, rs = 0;
+            if (j < BK) {
+                const int k = conv_tap(kt * BK + j);
+                const int ci = k / (HK * WK), r = (k / WK) % HK, sx = k % WK;
+                off2 = 2u * (u32)((ci * HIN + r) * WIN + sx);
+                rs = ((u32)r << 16) | (u32)sx;
+            }
+            const int p = kt * BKP + j;
+            t.e[(p / 8) * 16 + p % 8] = off2;
+            t.e[(p / 8) * 16 + 8 + p % 8] = rs;
+        }
+    return t;
+}
+__constant__ __attribute__((aligned(64))) ConvTable conv_table = make_conv_table();
+
+struct ConvCol { u32 base2, yx; };
+__device__ __forceinline__ ConvCol conv_col(const ColBlock &cb, int c)
+{
+    ConvCol col;
+    const int nb = cb.nb0 + c / (BH * BW);
+    const int y0 = (cb.y0 + (c / BW) % BH) * STRIDE - PAD_CONV;
+    const int x0 = (cb.x0 + c % BW) * STRIDE - PAD_CONV;
+    col.base2 = 2u * (u32)((nb * CIN * HIN + y0) * WIN + x0);
+    col.yx = ((u32)y0 << 16) | ((u32)x0 & 0xFFFFu);
+    return col;
+}
+constexpr int gcd_(int a, int b) { return b ? gcd_(b, a % b) : a; }
+#endif
+#endif
+
 struct Slab {
     u32x4 a[NA];
 #if OP == OP_CONV
@@ -99,10 +155,21 @@ struct Slab {
 #endif
 };
 
+#if OP == OP_CONV && CONV_TABLE
+// piece i of a thread gathers column (tid + i*NT) % BN: the columns repeat every COL_PERIOD pieces
+constexpr int COL_PERIOD = BN / gcd_(NT, BN);
+constexpr int NCOL = COL_PERIOD < NB ? COL_PERIOD : NB;
+constexpr bool COLS_IN_REGS = NCOL <= 8;
+struct ConvCols { ConvCol c[COLS_IN_REGS ? NCOL : 1]; };
+#endif
+
 __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, const u16 *__restrict__ Bb,
                                           int m0, int k0, int tid
 #if OP == OP_CONV
                                           , const ColBlock &cb
+#if CONV_TABLE
+                                          , const ConvCols &cols
+#endif
 #else
                                           , int n0
 #endif
@@ -135,8 +202,28 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
 #if OP == OP_CONV
             const int c = q % BN, kc = q / BN;
             u32 h[8];
+#if CONV_TABLE
+            const ConvCol col = COLS_IN_REGS ? cols.c[i % NCOL] : conv_col(cb, c);
+            const u32x4 *tp = (const u32x4 *)(conv_table.e + 2 * (k0 / BK * BKP + kc * 8));
+            const u32x4 o0 = tp[0], o1 = tp[1], r0 = tp[2], r1 = tp[3];
+            const u32 off2[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
+            const u32 rs[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+            const u16x2 lim = {(unsigned short)(WIN - 1), (unsigned short)(HIN - 1)};   // element 0 = low half = x
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const u16x2 at = __builtin_bit_cast(u16x2, col.yx) + __builtin_bit_cast(u16x2, rs[t]);
+                const bool ok = __builtin_bit_cast(u32, __builtin_elementwise_min(at, lim)) == __builtin_bit_cast(u32, at) &&
+                                (BKP == BK || kc * 8 + t < BK);
+                // unconditional load (of the tensor's first element where the tap is outside the image)
+                // and two selects: straight-line code, all eight loads in flight together
+                const u32 o = ok ? col.base2 + off2[t] : 0u;
+                const u32 v = *(const u16 *)((const char *)Bb + (size_t)o);
+                h[t] = ok ? v : 0u;
+            }
+#else
 #pragma unroll
             for (int t = 0; t < 8; ++t) h[t] = (BKP == BK || kc * 8 + t < BK) ? (u32)conv_b(Bb, cb, k0 + kc * 8 + t, c) : 0u;
+#endif
             u32x4 v;
             v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
             v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
@@ -285,7 +372,16 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         u16 *As = smem, *Bs = smem + NSTAGE * A_STAGE;
         Slab slab;
 #if OP == OP_CONV
+#if CONV_TABLE
+        ConvCols cols;
+        if (COLS_IN_REGS) {
+#pragma unroll
+            for (int i = 0; i < NCOL; ++i) cols.c[i] = conv_col(cb, (tid + i * NT) % BN);
+        }
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, cb, cols)
+#else
 #define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, cb)
+#endif
 #else
 #define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, n0)
 #endif
