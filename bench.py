@@ -8,7 +8,7 @@ evaluates exactly K trials of one OpEvo run (lambda = rho = 8, q = 0.5) after `-
 untimed trials of a throw-away run.  Inputs are seeded, synthetic and resident in HBM before
 the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps 400] [--warmup 8] [--workload mm8192_bf16] [--seed 0]
+    python bench.py [--gpus 1] [--steps 500] [--warmup 8] [--workload mm8192_bf16] [--seed 0]
 """
 import argparse
 import json
@@ -33,7 +33,7 @@ MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1611022077.0, 268448413.0,
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mm8192_bf16")
     ap.add_argument("--seed", type=int, default=0)

@@ -324,6 +324,16 @@ def test_conv_stride_padding_kernel_shapes(torch_cuda):
     w.close()
 
 
+def test_conv_element_wise_gather_where_the_tap_table_would_be_too_large(torch_cuda):
+    # 1024 channels x 3 x 3 = 9216 taps: more positions than the gather table may hold
+    w = Workload(torch_cuda, "conv2d", (2, 1024, 8, 8, 32, 3, 3, 1, 1), "bf16", 48)
+    for label, cfg in [("mfma32, slab 32, pipelined", [1, 2, 1, 1, 1, 32, 2, 1, 1, 4, 2, 1, 1, 4, 288, 32, 1]),
+                       ("mfma32, slab 48, single stage", [1, 2, 1, 1, 1, 32, 2, 1, 1, 4, 2, 1, 1, 4, 192, 48, 0])]:
+        assert "-DCONV_TABLE=0" in P.opevo_kernel_defines(w.op, P.OPEVO_TILE4, cfg)
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.close()
+
+
 # ------------------------------------------------------------------ config 5: full sizes
 def test_conv14_batch32_bf16_full_size(torch_cuda):
     _say("  oracle for conv 32x256x14x14 (3.7e9 MACs) ...")

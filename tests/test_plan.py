@@ -313,3 +313,19 @@ def test_separately_split_reduction_templates_compile(label, kd, cfg, path):
     kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4P, cfg)
     assert P.opevo_kernel_code_size(kernel) > 1000
     P.opevo_kernel_destroy(kernel)
+
+
+def test_image_gather_table_is_used_where_it_fits():
+    """The MFMA template gathers the image through a compile-time table of 8 bytes per position of
+    the reduction walk; past 8192 positions it falls back to the element-wise gather."""
+    small = _op(C2_SMALL, P.OPEVO_BF16)
+    d = P.opevo_kernel_defines(small, P.OPEVO_TILE4, [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 25, 16, 1])
+    assert "-DCONV_TABLE=1" in d
+    assert "CONV_TABLE" not in P.opevo_kernel_defines(small, P.OPEVO_TILE4, [4, 1, 4, 2, 1, 4, 3, 1, 2, 2, 3, 2, 1, 2, 25, 16, 1])   # scalar
+    deep = _op((P.OPEVO_CONV2D, (2, 1024, 8, 8, 32, 3, 3, 1, 1)), P.OPEVO_BF16)     # 9216 taps
+    for cfg in ([1, 2, 1, 1, 1, 32, 2, 1, 1, 4, 2, 1, 1, 4, 288, 32, 1], [1, 2, 1, 1, 1, 32, 2, 1, 1, 4, 2, 1, 1, 4, 192, 48, 0]):
+        plan = P.opevo_kernel_plan(deep, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == 1
+        assert "-DCONV_TABLE=0" in P.opevo_kernel_defines(deep, P.OPEVO_TILE4, cfg)
+        kernel, _ = P.opevo_kernel_build(deep, P.OPEVO_TILE4, cfg)
+        P.opevo_kernel_destroy(kernel)
