@@ -26,7 +26,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}   # MI355X dense MFM
 # known-size elementwise pass (profiles/mm8192_bf16_best_kernel_counters.txt), keyed by (workload, BM, BN): the
 # traffic of an MFMA-template member is set by its workgroup tile, not by how the tile is split among waves.
 # --traffic overrides this with the figures of a fresh counter run.
-MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1611022077.0, 268448413.0, "opevo_mm4_32_2_8_16_32_4_2_32_256_32_1"),
+MEASURED_TRAFFIC = {("mm8192_bf16", 256, 256): (1613842042.0, 268551765.0, "opevo_mm4_32_1_256_1_32_4_4_16_256_32_1"),
                     # profiles/mm8192_bf16_tile_shapes_traffic.txt
                     ("mm8192_bf16", 128, 512): (1611516811.0, 268699732.0, "opevo_mm4_64_1_2_64_16_8_16_4_256_32_1"),
                     ("mm8192_bf16", 512, 128): (1613655132.0, 268488628.0, "opevo_mm4_16_8_16_4_64_1_2_64_256_32_1"),
