@@ -33,3 +33,10 @@ def test_status_names_and_error_text():
     else:
         raise AssertionError("bad operator kind accepted")
     assert "opevo" in P.opevo_version()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
