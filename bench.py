@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mm8192_bf16")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--split-k", action="store_true",
+                    help="MatMul only: tune in the space whose reduction axis has three factors, the first being the "
+                         "number of workgroups that share an output tile (partial sums added atomically)")
     ap.add_argument("--split-reduction", action="store_true",
                     help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
     ap.add_argument("--extended", action="store_true",
@@ -76,6 +79,11 @@ def main() -> int:
     kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
     variant = P.OPEVO_TILE2 if dtype == "f32" else (P.OPEVO_TILE4X if args.extended else P.OPEVO_TILE4)
+    if args.split_k:
+        if w["kind"] != "matmul" or dtype == "f32":
+            print("bench.py: --split-k is a bf16 / fp16 MatMul space", file=sys.stderr)
+            return 2
+        variant = P.OPEVO_TILE4K
     if args.split_reduction:
         if w["kind"] != "conv2d":
             print("bench.py: --split-reduction is a Conv2d space", file=sys.stderr)
@@ -194,7 +202,7 @@ def main() -> int:
         "ms_per_step": round(wall / max(1, res["n_trials"]) * 1e3, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s %s dims=%s" % (args.workload, w["kind"], list(w["dims"])), "trials": int(res["n_trials"]),
-                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {P.OPEVO_TILE2: "TILE2", P.OPEVO_TILE4: "TILE4", P.OPEVO_TILE4X: "TILE4X", P.OPEVO_TILE4P: "TILE4P"}[variant],
+                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {P.OPEVO_TILE2: "TILE2", P.OPEVO_TILE4: "TILE4", P.OPEVO_TILE4X: "TILE4X", P.OPEVO_TILE4P: "TILE4P", P.OPEVO_TILE4K: "TILE4K"}[variant],
                    "best_cfg": [int(x) for x in res["best_cfg"]], "frac_of_peak": round(best / PEAK_TFLOPS[dtype], 4),
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),

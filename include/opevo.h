@@ -191,8 +191,18 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         reduction steps unrolled together where the reduction is a loop: the scalar template's
  *         K loop when unroll = 1 (explicit pragma), the MFMA template's loop over the K steps of
  *         a slab when unroll = 0 (with unroll = 1 that template is fully unrolled and pipelined
- *         anyway).  Kernel templates, padding of slabs and rounding of wave tiles as for TILE4. */
-typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3 } opevo_variant;
+ *         anyway).  Kernel templates, padding of slabs and rounding of wave tiles as for TILE4.
+ *  TILE4K: MatMul only, the reduction axis in three factors as App. B.1 has it:
+ *         MatMul  M(4) N(4) K(3) unroll{0,1},   K = (partitions, steps, LDS tile)
+ *         The first factor is the number of workgroups (grid z) that share one output tile; each
+ *         reduces its own contiguous part of K and adds its partial sums into C with fp32 atomic
+ *         adds.  Members with more than one partition need C cleared first: opevo_kernel_launch /
+ *         opevo_kernel_time (and opevo_tune) enqueue a hipMemsetAsync of C before every launch of
+ *         such a member, and the time of that clear counts as part of the trial.  The sum is the
+ *         same up to the rounding of an fp32 addition order that varies from run to run.  For
+ *         operators whose output has fewer tiles than the chip has compute units (MM3 of App. B.1:
+ *         512 x 1024 from K = 4096) this is what fills the machine. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
@@ -247,9 +257,11 @@ int opevo_compile_pool_kind(int *kind);
  * failure.  The module is loaded on the first launch.  Two checks on the compiled code of the
  * direct-to-LDS template (path 3), whose hand-placed waits count the loads in flight and so
  * need the fully unrolled, spill-free code: a code object above 128 KiB (the compiler did not
- * unroll the schedule) makes this call return OPEVO_E_INVALID, and a kernel that uses private
- * scratch memory makes its first launch / timing return OPEVO_E_INVALID; opevo_tune scores
- * both as invalid trials. */
+ * unroll the schedule) makes this call return OPEVO_E_INVALID.  On every template, a kernel
+ * that the compiler gave private scratch memory (register spills) makes its first launch /
+ * timing return OPEVO_E_INVALID: it would be slow, it would break the load counting of path 3,
+ * and spill code of a register-staged member was seen to lose part of a value.  opevo_tune
+ * scores both as invalid trials. */
 int opevo_kernel_build(const opevo_op *op, int variant, const int32_t *cfg,
                        opevo_kernel **out, double *compile_ms);
 /* Compiling is by far the longest part of a trial (Sec. 6 gives it 8 CPU threads), and runs of

@@ -53,42 +53,44 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     k->tmpl = d.tmpl;
     k->defines = d.defines;
     k->name = d.kernel_name;
+    k->zero_bytes = size_t(d.zero_bytes);
     if (compile_ms)
         *compile_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = k;
     return OPEVO_OK;
 }
 
-int load_kernel(opevo_kernel *k)
+int load_kernel(opevo_kernel *k, bool refuse_spills)
 {
-    if (k->fn) return OPEVO_OK;
-    HIP_TRY(hipModuleLoadData(&k->module, k->code.data()));
-    hipError_t e = hipModuleGetFunction(&k->fn, k->module, k->name.c_str());
-    if (e != hipSuccess) {
-        (void)hipModuleUnload(k->module);
-        k->module = nullptr; k->fn = nullptr;
-        return hip_fail(e, "hipModuleGetFunction");
-    }
-    if (k->plan.path == 3) {
-        // The direct-to-LDS template counts its own outstanding loads (s_waitcnt vmcnt(n)).  Register
-        // spills would put scratch stores on the same counter, and stores may complete out of order
-        // with loads, so a count could be reached while a slab is still in flight.  A member that
-        // spills is therefore not run (it would be slow anyway).
-        int scratch_bytes = 0;
-        e = hipFuncGetAttribute(&scratch_bytes, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, k->fn);
-        if (e == hipSuccess && scratch_bytes > 0) {
+    if (!k->fn) {
+        HIP_TRY(hipModuleLoadData(&k->module, k->code.data()));
+        hipError_t e = hipModuleGetFunction(&k->fn, k->module, k->name.c_str());
+        if (e != hipSuccess) {
             (void)hipModuleUnload(k->module);
             k->module = nullptr; k->fn = nullptr;
-            return fail(OPEVO_E_INVALID, "direct-to-LDS member spills %d bytes of registers per lane", scratch_bytes);
+            return hip_fail(e, "hipModuleGetFunction");
         }
+        int scratch_bytes = 0;
+        e = hipFuncGetAttribute(&scratch_bytes, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, k->fn);
+        k->scratch_bytes = e == hipSuccess ? scratch_bytes : 0;
         (void)hipGetLastError();
+        if (k->plan.path != 3 && k->plan.lds_bytes > 32768) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k->fn),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, k->plan.lds_bytes);
+            if (e != hipSuccess && k->plan.lds_bytes > 65536) return hip_fail(e, "hipFuncSetAttribute(max dynamic LDS)");
+            (void)hipGetLastError();
+        }
     }
-    if (k->plan.path != 3 && k->plan.lds_bytes > 32768) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k->fn),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, k->plan.lds_bytes);
-        if (e != hipSuccess && k->plan.lds_bytes > 65536) return hip_fail(e, "hipFuncSetAttribute(max dynamic LDS)");
-        (void)hipGetLastError();
-    }
+    // A member whose kernel needs private scratch memory (register spills) is not run, on any
+    // template.  The direct-to-LDS template counts its own outstanding loads (s_waitcnt vmcnt(n)):
+    // spill stores would sit on the same counter and may complete out of order with loads, so a
+    // count could be reached while a slab is still in flight.  And on the register-staged template
+    // a member that filled all 512 registers was compiled into code that spills three dwords of a
+    // 16-byte staging value to scratch, parks the fourth in an accumulation register and never
+    // moves it back before the value is stored to LDS: wrong rows in the result, found by the
+    // parity gate.  Such members are slow anyway; they score as invalid (fitness 0).
+    if (refuse_spills && k->scratch_bytes > 0)
+        return fail(OPEVO_E_INVALID, "member spills %d bytes of registers per lane", k->scratch_bytes);
     return OPEVO_OK;
 }
 
@@ -96,6 +98,8 @@ int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStr
                   unsigned long long *ctl)
 {
     if (int rc = load_kernel(k)) return rc;
+    // members whose workgroups add partial sums into the output start from a cleared output
+    if (k->zero_bytes) HIP_TRY(hipMemsetAsync(c, 0, k->zero_bytes, stream));
     void *args[] = {(void *)&a, (void *)&b, (void *)&c, (void *)&ctl};
     // the direct-to-LDS template declares its stages statically; the others take dynamic LDS
     const unsigned dyn_lds = k->plan.path == 3 ? 0u : unsigned(k->plan.lds_bytes);
@@ -224,7 +228,7 @@ int opevo_kernel_code_size(const opevo_kernel *k, size_t *bytes)
 int opevo_kernel_resources(opevo_kernel *k, int *vgprs, int *sgprs, int *spill_bytes, int *static_lds)
 {
     if (!k) return fail(OPEVO_E_ARG, "kernel_resources: NULL argument");
-    if (int rc = load_kernel(k)) return rc;
+    if (int rc = load_kernel(k, false)) return rc;   // figures of a spilling member can still be read
     int v = 0;
     if (vgprs) { HIP_TRY(hipFuncGetAttribute(&v, HIP_FUNC_ATTRIBUTE_NUM_REGS, k->fn)); *vgprs = v; }
     if (sgprs) *sgprs = -1;   // not reported by the runtime

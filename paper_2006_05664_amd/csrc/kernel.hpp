@@ -14,8 +14,10 @@ struct opevo_kernel {
     double flops = 0.0;
     std::string tmpl, defines, name;
     std::vector<char> code;        // gfx950 code object from hipRTC
+    size_t zero_bytes = 0;         // > 0: the output is cleared before every launch (split reduction)
     hipModule_t module = nullptr;  // loaded on first launch
     hipFunction_t fn = nullptr;
+    int scratch_bytes = 0;         // private scratch per lane the compiler used (known once loaded)
 };
 
 namespace opevo {
@@ -24,7 +26,9 @@ namespace opevo {
 const char *template_source(const char *name);
 
 int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kernel **out, double *compile_ms);
-int load_kernel(opevo_kernel *k);
+// Loads the module on first use; with refuse_spills a kernel that uses private scratch memory is
+// answered with OPEVO_E_INVALID (it is never launched).
+int load_kernel(opevo_kernel *k, bool refuse_spills = true);
 int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStream_t stream,
                   unsigned long long *ctl = nullptr);
 // timeout_ms > 0 arms the deadline of the scalar template: a launch still running after that

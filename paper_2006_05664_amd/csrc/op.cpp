@@ -80,6 +80,13 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
                  discrete("unroll_steps", kUnrollSteps, kNumUnrollSteps)};
         return OPEVO_OK;
     }
+    if (variant == OPEVO_TILE4K) {
+        // MatMul with the reduction axis in three factors, as App. B.1 splits it; the outermost one is
+        // the number of workgroups that share an output tile, each reducing its own part of K
+        if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the split-reduction space exists for MatMul only");
+        descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 3), flag("unroll")};
+        return OPEVO_OK;
+    }
     if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
     switch (op.kind) {
     case OPEVO_MATMUL:
@@ -156,7 +163,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t BM = 1, BN = 1, BK = 1, ksteps = 1, WM = 1, WN = 1, TM = 1, TN = 1, FM = 1, FN = 1;
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
-    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P);
+    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P || variant == OPEVO_TILE4K);
+    int64_t ksplit = 1;
     int64_t box[6] = {1, 1, 1, 1, 1, 1};   // C_in, H_k, W_k as (boxes, box extent) pairs
     bool tap_box = false;
     int64_t kunroll = 0;                   // 0: the template's default
@@ -170,9 +178,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         if (op.kind == OPEVO_BMM) { b1 = c[0]; binner = c[1]; c += 2; }
         m1 = c[0]; WM = c[1]; TM = int64_t(c[2]) * c[3]; FM = c[3];
         n1 = c[4]; WN = c[5]; TN = int64_t(c[6]) * c[7]; FN = c[7];
-        ksteps = c[8]; BK = c[9]; flagv = c[10];
+        if (variant == OPEVO_TILE4K) { ksplit = c[8]; b1 = ksplit; ksteps = c[9]; BK = c[10]; flagv = c[11]; }
+        else { ksteps = c[8]; BK = c[9]; flagv = c[10]; }
         BM = WM * TM; BN = WN * TN;
-        tile4_width = int(c - cfg) + 11;
+        tile4_width = int(c - cfg) + (variant == OPEVO_TILE4K ? 12 : 11);
     } else {   // conv: B(2) Cout(4) H(4) W(4) R(2) flag
         const int32_t *c = cfg;
         const int64_t nb1 = c[0]; nb2 = c[1];
@@ -304,7 +313,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     {
         std::ostringstream nm;
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
-           << (variant == OPEVO_TILE4P ? "p" : four_level ? "4" : "2");
+           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
@@ -335,6 +344,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
           << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
     if (kunroll) D << " -DKUNROLL=" << kunroll;
+    if (ksplit > 1) D << " -DKSPLIT=" << ksplit;
+    out.zero_bytes = ksplit > 1 ? op.c_elems() * 4 : 0;
     if (linear)
         D << " -DGRID_LINEAR=1 -DGRID_N1=" << n1 << " -DGRID_M1=" << m1 << " -DGRID_B1=" << b1 << " -DORDER0=" << order[0]
           << " -DORDER1=" << order[1] << " -DORDER2=" << order[2] << " -DGROUP=" << group;

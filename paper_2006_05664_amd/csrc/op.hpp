@@ -32,6 +32,7 @@ struct Decoded {
     std::string tmpl;      // template name: "gemm_scalar" or "gemm_mfma"
     std::string defines;   // space separated -D options
     std::string kernel_name;   // symbol of the instantiated kernel
+    int64_t zero_bytes = 0;    // bytes of the output the host clears before every launch (split reduction), else 0
 };
 
 // OPEVO_OK (plan.status says valid/invalid) or OPEVO_E_ILLEGAL / OPEVO_E_ARG.

@@ -21,6 +21,9 @@
 #ifndef A_TRANS
 #define A_TRANS 0
 #endif
+#ifndef KSPLIT
+#define KSPLIT 1   // MatMul: workgroups along grid z that share one output tile, each reducing its own K range
+#endif
 #define OP_MATMUL 0
 #define OP_BMM 1
 #define OP_CONV 2
@@ -69,6 +72,18 @@ __device__ __forceinline__ BlockId block_id()
     id.n = blockIdx.x; id.m = blockIdx.y; id.b = blockIdx.z;
 #endif
     return id;
+}
+
+// One element of the result.  With the reduction split over KSPLIT workgroups the output has been
+// cleared by the host before the launch and every workgroup adds its partial sum (fp32 atomic add
+// in device scope, unordered: the rounding of the last bits depends on the arrival order).
+__device__ __forceinline__ void c_out(float *p, float v)
+{
+#if KSPLIT > 1
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
+    *p = v;
+#endif
 }
 
 #if OP == OP_CONV

@@ -355,10 +355,16 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #if OP == OP_CONV
         const u16 *Ab = A, *Bb = B;
 #else
+#if KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
+        const u16 *Ab = A + (long)bid.b * (KSTEPS * BK);
+        const u16 *Bb = B + (long)bid.b * (KSTEPS * BK) * N;
+        float *Cb = C;
+#else
         const long batch = (long)bid.b * BATCH_INNER + bi;
         const u16 *Ab = A + batch * M * K;
         const u16 *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;
+#endif
 #endif
         acc_t acc[MI][NI];
 #pragma unroll
@@ -459,7 +465,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #if OP == OP_CONV
                     C[conv_c_index(cb, gm, cn)] = acc[i][j][r];
 #else
-                    Cb[(long)gm * N + n0 + cn] = acc[i][j][r];
+                    c_out(&Cb[(long)gm * N + n0 + cn], acc[i][j][r]);
 #endif
                 }
             }

@@ -180,10 +180,16 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     for (int t = 0; t < NB; ++t) boff[t] = b_lane_off(slot * LB + t, lane);
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
+#if KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
+        const u16 *Ab = A + (long)bid.b * (KSTEPS * BK);
+        const u16 *Bb = B + (long)bid.b * (KSTEPS * BK) * N;
+        float *Cb = C;
+#else
         const long batch = (long)bid.b * BATCH_INNER + bi;
         const u16 *Ab = A + batch * M * K;
         const u16 *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;
+#endif
 
         acc_t acc[MI][NI];
 #pragma unroll
@@ -291,7 +297,12 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4;
-                    __builtin_nontemporal_store(acc[i][j][r], &Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)]);
+                    float *dst = &Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)];
+#if KSPLIT > 1
+                    c_out(dst, acc[i][j][r]);
+#else
+                    __builtin_nontemporal_store(acc[i][j][r], dst);
+#endif
                 }
     }
 }

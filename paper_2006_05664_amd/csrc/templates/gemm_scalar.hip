@@ -44,10 +44,16 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
 #if OP == OP_CONV
         const in_t *Ab = A;   // kernel tensor [M][K]
 #else
+#if KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
+        const in_t *Ab = A + (long)bid.b * (KSTEPS * BK);
+        const in_t *Bb = B + (long)bid.b * (KSTEPS * BK) * N;
+        float *Cb = C;
+#else
         const long batch = (long)bid.b * BATCH_INNER + bi;
         const in_t *Ab = A + batch * M * K;
         const in_t *Bb = B + batch * K * N;
         float *Cb = C + batch * M * N;
+#endif
 #endif
         float acc[E];
 #pragma unroll
@@ -98,7 +104,7 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
 #if OP == OP_CONV
                 C[conv_c_index(cb, m0 + idx / BN, idx % BN)] = acc[e];
 #else
-                Cb[(long)(m0 + idx / BN) * N + n0 + idx % BN] = acc[e];
+                c_out(&Cb[(long)(m0 + idx / BN) * N + n0 + idx % BN], acc[e]);
 #endif
             }
         }

@@ -329,3 +329,52 @@ def test_image_gather_table_is_used_where_it_fits():
         assert "-DCONV_TABLE=0" in P.opevo_kernel_defines(deep, P.OPEVO_TILE4, cfg)
         kernel, _ = P.opevo_kernel_build(deep, P.OPEVO_TILE4, cfg)
         P.opevo_kernel_destroy(kernel)
+
+
+# ------------------------------------------------------------------ MatMul space with the reduction axis in three factors
+MM3 = (P.OPEVO_MATMUL, (512, 1024, 4096))
+
+
+def test_split_reduction_space_has_three_k_factors_and_is_matmul_only():
+    op = _op(MM3, P.OPEVO_BF16)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4K)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["M", "N", "K", "unroll"] and P.opevo_space_width(sp) == 12
+    # 4096 = 2^12 in three ordered factors: C(14, 2) = 91
+    assert P.opevo_space_param_size(sp, 2) == 91
+    P.opevo_space_destroy(sp)
+    for kd in (BMM, CONV56):
+        with pytest.raises(P.OpevoError):
+            P.opevo_op_space(_op(kd, P.OPEVO_BF16), P.OPEVO_TILE4K)
+
+
+def test_split_reduction_members_put_the_partitions_on_grid_z():
+    op = _op(MM3, P.OPEVO_BF16)
+    cfg = [4, 2, 2, 32, 8, 2, 2, 32, 8, 16, 32, 1]            # 8 partitions of 16 slabs of 32
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4K, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == 3 and list(plan.grid) == [8, 4, 8] and list(plan.tile) == [128, 128, 32]
+    d = P.opevo_kernel_defines(op, P.OPEVO_TILE4K, cfg)
+    assert "-DKSPLIT=8" in d and "-DKSTEPS=16" in d and "-DK=4096" in d
+    one = [4, 2, 2, 32, 8, 2, 2, 32, 1, 128, 32, 1]           # one partition: the plain kernel
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4K, one)
+    assert list(plan.grid) == [8, 4, 1] and "KSPLIT" not in P.opevo_kernel_defines(op, P.OPEVO_TILE4K, one)
+    with pytest.raises(P.OpevoError):                          # 8 * 16 * 16 != 4096
+        P.opevo_kernel_plan(op, P.OPEVO_TILE4K, [4, 2, 2, 32, 8, 2, 2, 32, 8, 16, 16, 1])
+
+
+SPLITK_COMPILE_CASES = [
+    ("direct-to-LDS, 8 partitions", [4, 2, 2, 32, 8, 2, 2, 32, 8, 16, 32, 1], 3),
+    ("mfma32 register-staged, 8 partitions", [4, 2, 2, 32, 8, 2, 2, 32, 8, 32, 16, 1], 1),
+    ("mfma16, 4 partitions, single stage", [16, 2, 1, 16, 32, 2, 1, 16, 4, 32, 32, 0], 2),
+    ("scalar, 16 partitions", [16, 2, 4, 4, 32, 2, 4, 4, 16, 32, 8, 1], 0),
+]
+
+
+@pytest.mark.parametrize("label,cfg,path", SPLITK_COMPILE_CASES, ids=[c[0] for c in SPLITK_COMPILE_CASES])
+def test_split_reduction_templates_compile(label, cfg, path):
+    op = _op(MM3, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4K, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4K, cfg)
+    assert P.opevo_kernel_code_size(kernel) > 1000
+    P.opevo_kernel_destroy(kernel)
