@@ -140,6 +140,13 @@ int opevo_recombine(const opevo_space *space, const int32_t *parents, const doub
 int opevo_tuner_create(const opevo_space *space, int lambda, int rho, double q, uint64_t seed,
                        opevo_tuner **out);
 int opevo_tuner_destroy(opevo_tuner *tuner);
+/* Which mutation ask() applies to a recombined child.  0 (default): the q-random walk on every
+ * parameter's graph (Sec. 4.3).  1: a control that ignores the graphs, as a plain evolutionary
+ * algorithm would mutate: per parameter, in order, draw next_double(); if it is < q the
+ * parameter becomes the vertex number next_below(|X_i|) of its feasible set.  Used to measure what
+ * the topology-aware walk buys (Sec. 5.5 compares hyperparameters, not this).  The no-duplicate
+ * rule applies to both. */
+int opevo_tuner_set_mutation(opevo_tuner *tuner, int kind);
 /* Next configurations to evaluate, at most max_n (max_n <= 0: no cap): the first call gives
  * lambda random members, later calls give rho children of the top-lambda of everything told
  * so far (ties: earlier trial first).  No configuration is ever returned twice, whether it was
@@ -362,6 +369,7 @@ typedef struct {
                                    environment prints one line per trial before its kernel runs
                                    (kernel name = configuration), so that the log of a run that
                                    died names what was on the GPU                                   */
+    int32_t     mutation;       /* as opevo_tuner_set_mutation: 0 the paper's q-random walk, 1 control */
 } opevo_tune_args;
 
 typedef struct {

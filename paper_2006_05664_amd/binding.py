@@ -56,7 +56,7 @@ class opevo_tune_args(C.Structure):
                 ("cfg_log", C.POINTER(C.c_int32)), ("fitness_log", C.POINTER(C.c_double)),
                 ("status_log", C.POINTER(C.c_int32)), ("compile_ms_log", C.POINTER(C.c_double)),
                 ("run_ms_log", C.POINTER(C.c_double)), ("wall_s_log", C.POINTER(C.c_double)),
-                ("progress_every", C.c_int32)]
+                ("progress_every", C.c_int32), ("mutation", C.c_int32)]
 
 
 class opevo_tune_result(C.Structure):
@@ -105,6 +105,7 @@ _SIGNATURES = {
     "opevo_recombine": [_vp, _i32p, _f64p, C.c_int, _vp, _i32p],
     "opevo_tuner_create": [_vp, C.c_int, C.c_int, C.c_double, C.c_uint64, C.POINTER(_vp)],
     "opevo_tuner_destroy": [_vp],
+    "opevo_tuner_set_mutation": [_vp, C.c_int],
     "opevo_tuner_ask": [_vp, _i32p, C.c_int, C.POINTER(C.c_int)],
     "opevo_tuner_tell": [_vp, _i32p, _f64p, C.c_int],
     "opevo_tuner_num_trials": [_vp, C.POINTER(C.c_int)],
@@ -366,6 +367,10 @@ def opevo_tuner_destroy(tuner) -> None:
     _check(lib.opevo_tuner_destroy(tuner))
 
 
+def opevo_tuner_set_mutation(tuner, kind: int) -> None:
+    _check(lib.opevo_tuner_set_mutation(tuner, kind))
+
+
 def opevo_tuner_ask(tuner, max_n: int = 0) -> np.ndarray:
     out = np.empty((tuner._cap, tuner._width), dtype=np.int32)
     n = C.c_int()
@@ -545,7 +550,7 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                trials: int = 500, lambda_: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0,
                compile_threads: int = 8, warmup: int = 3, launches_per_sample: int = 0, samples: int = 5,
                warmup_ms: float = 25.0, trial_timeout_ms: float = 0.0, tol_max_scaled: float = 2e-2, tol_rel_fro: float = 5e-3,
-               progress_every: int = 0) -> dict:
+               progress_every: int = 0, mutation: int = 0) -> dict:
     """Runs Alg. 1 on the GPU; returns the result struct fields, the best configuration and the
     per-trial logs as numpy arrays."""
     space = opevo_op_space(op, variant)
@@ -563,7 +568,7 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                            warmup_ms=warmup_ms, trial_timeout_ms=trial_timeout_ms, tol_max_scaled=tol_max_scaled, tol_rel_fro=tol_rel_fro,
                            cfg_log=_ip(logs["cfg"]), fitness_log=_dp(logs["fitness"]),
                            status_log=_ip(logs["status"]), compile_ms_log=_dp(logs["compile_ms"]),
-                           run_ms_log=_dp(logs["run_ms"]), wall_s_log=_dp(logs["wall_s"]), progress_every=progress_every)
+                           run_ms_log=_dp(logs["run_ms"]), wall_s_log=_dp(logs["wall_s"]), progress_every=progress_every, mutation=mutation)
     best = np.zeros(w, dtype=np.int32)
     res = opevo_tune_result()
     _check(lib.opevo_tune(op, variant, C.byref(args), _ip(best), C.byref(res)))

@@ -272,6 +272,15 @@ void opevo_space::mutate(double q, Rng &rng, int32_t *cfg) const
     for (const Param &p : params) p.walk(q, rng, cfg + p.offset, scratch);
 }
 
+void opevo_space::mutate_uniform(double q, Rng &rng, int32_t *cfg) const
+{
+    for (const Param &p : params) {
+        if (!(rng.next_double() < q)) continue;
+        uint32_t i = rng.next_below(uint32_t(p.n_verts));
+        std::memcpy(cfg + p.offset, p.vertex(i), sizeof(int32_t) * p.width);
+    }
+}
+
 // ------------------------------------------------------------------------------ C ABI
 extern "C" {
 

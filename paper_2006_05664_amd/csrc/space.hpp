@@ -44,4 +44,6 @@ struct opevo_space {
     void unrank(int64_t r, int32_t *cfg) const;
     void random(opevo::Rng &rng, int32_t *cfg) const;
     void mutate(double q, opevo::Rng &rng, int32_t *cfg) const;
+    // Control mutation that ignores the graphs: per parameter, with probability q a uniformly random vertex.
+    void mutate_uniform(double q, opevo::Rng &rng, int32_t *cfg) const;
 };

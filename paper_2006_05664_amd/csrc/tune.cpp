@@ -54,6 +54,13 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
         opevo_space_destroy(space);
         return rc;
     }
+    if (args->mutation != 0) {
+        if (int rc = opevo_tuner_set_mutation(tuner, args->mutation)) {
+            opevo_tuner_destroy(tuner);
+            opevo_space_destroy(space);
+            return rc;
+        }
+    }
     const int w = space->width;
     const int gen_cap = std::max(args->lambda, args->rho);
     const int n_threads = std::max(1, args->compile_threads);

@@ -111,12 +111,12 @@ int opevo_tuner::ask(int32_t *out, int max_n)
     }
     for (; n < want; ++n) {
         recombine(*space, pc.data(), pf.data(), int(par.size()), rng, x.data());
-        space->mutate(q, rng, x.data());
+        mutate(x.data());
         int tries = 0;
         bool ok = true;
         while (sampled.count(x)) {                 // already sampled: mutate again (Sec. 4.4)
             if (tries == kRemutateCap) { ok = random_unsampled(x); break; }
-            space->mutate(q, rng, x.data());
+            mutate(x.data());
             ++tries;
         }
         if (!ok) break;
@@ -167,6 +167,14 @@ int opevo_tuner_create(const opevo_space *space, int lambda, int rho, double q, 
 }
 
 int opevo_tuner_destroy(opevo_tuner *tuner) { delete tuner; return OPEVO_OK; }
+
+int opevo_tuner_set_mutation(opevo_tuner *tuner, int kind)
+{
+    if (!tuner) return fail(OPEVO_E_ARG, "tuner_set_mutation: NULL argument");
+    if (kind != 0 && kind != 1) return fail(OPEVO_E_ARG, "tuner_set_mutation: kind must be 0 (q-random walk) or 1 (uniform resampling)");
+    tuner->mutation = kind;
+    return OPEVO_OK;
+}
 
 int opevo_tuner_ask(opevo_tuner *tuner, int32_t *cfgs_out, int max_n, int *n_out)
 {

@@ -30,6 +30,7 @@ struct opevo_tuner {
     int lambda, rho;
     double q;
     opevo::Rng rng;
+    int mutation = 0;       // 0: q-random walk on the parameter graphs (Sec. 4.3); 1: uniform resampling (control)
     bool started = false;
     std::vector<std::vector<int32_t>> configs;   // Q in trial order
     std::vector<double> fitness;
@@ -43,4 +44,5 @@ struct opevo_tuner {
     bool random_unsampled(std::vector<int32_t> &cfg);
     int ask(int32_t *out, int max_n);
     void tell(const int32_t *cfgs, const double *fit, int n);
+    void mutate(int32_t *cfg) { if (mutation == 1) space->mutate_uniform(q, rng, cfg); else space->mutate(q, rng, cfg); }
 };

@@ -1,6 +1,8 @@
 #!/usr/bin/env python3
 """Hyperparameter sensitivity of OpEvo on one MI355X (Sec. 5.5 of the paper: mutation rate q and
-parent size lambda), with uniform random search without replacement as the control.
+parent size lambda), with two controls: Alg. 1 with a mutation that ignores the parameter graphs
+(per parameter, with probability p, a uniformly random value: a plain evolutionary algorithm) and
+uniform random search without replacement.
 
 Every setting runs `--trials` trials of Alg. 1 through `opevo_tune` for each seed; the control is
 the same call with lambda = trials, i.e. the whole budget is the initial, uniformly random
@@ -26,6 +28,8 @@ def main() -> int:
     ap.add_argument("--seeds", default="0,1,2")
     ap.add_argument("--q", default="0.1,0.3,0.5,0.7,0.9", help="mutation rates tried at lambda = rho = 8")
     ap.add_argument("--lam", default="4,16,32", help="parent sizes tried at q = 0.5 (rho = 8)")
+    ap.add_argument("--uniform-mutation", default="0.3,0.5", help="per-parameter resampling probabilities of the plain-EA control")
+    ap.add_argument("--variant", default=None, help="TILE4 (default for 16-bit inputs), TILE4X, TILE4P or TILE4K")
     args = ap.parse_args()
 
     import numpy as np
@@ -39,6 +43,9 @@ def main() -> int:
     kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
     variant = P.OPEVO_TILE2 if dtype == "f32" else P.OPEVO_TILE4
+    if args.variant:
+        variant = {"TILE2": P.OPEVO_TILE2, "TILE4": P.OPEVO_TILE4, "TILE4X": P.OPEVO_TILE4X, "TILE4P": P.OPEVO_TILE4P,
+                   "TILE4K": P.OPEVO_TILE4K}[args.variant]
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
     flops = P.opevo_op_flops(op)
     a_host, b_host = synth.workload_inputs(args.workload)
@@ -49,10 +56,14 @@ def main() -> int:
     seeds = [int(s) for s in args.seeds.split(",")]
     marks = [m for m in (50, 100, 200, 300, 400, 500, 750, 1000) if m <= args.trials]
 
-    settings = [("q=%s lambda=8" % q, float(q), 8) for q in args.q.split(",")]
-    settings += [("q=0.5 lambda=%s" % lam, 0.5, int(lam)) for lam in args.lam.split(",")]
-    settings += [("uniform random search", 0.5, args.trials)]
-    for name, q, lam in settings:
+    settings = [("q=%s lambda=8" % q, float(q), 8) for q in args.q.split(",") if q]
+    settings += [("q=0.5 lambda=%s" % lam, 0.5, int(lam)) for lam in args.lam.split(",") if lam]
+    settings = [(n, q, lam, 0) for n, q, lam in settings]
+    # controls: Alg. 1 with a mutation that ignores the parameter graphs (a plain evolutionary
+    # algorithm), and no evolution at all
+    settings += [("uniform mutation p=%s lambda=8" % q, float(q), 8, 1) for q in args.uniform_mutation.split(",") if q]
+    settings += [("uniform random search", 0.5, args.trials, 0)]
+    for name, q, lam, mutation in settings:
         curves = []
         for seed in seeds:
             # no reference tensor: parity of every template path is the test suite's business,
@@ -60,7 +71,7 @@ def main() -> int:
             res = P.opevo_tune(op, variant, da.data_ptr(), db.data_ptr(), dc.data_ptr(), None, stream,
                                trials=args.trials, lambda_=lam, rho=8, q=q, seed=seed, compile_threads=8,
                                warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=timeout_ms,
-                               progress_every=100)
+                               progress_every=100, mutation=mutation)
             fit = res["logs"]["fitness"][: int(res["n_trials"])]
             curve = [float(np.max(fit[:m])) if m <= fit.size else float(np.max(fit)) for m in marks]
             curves.append(curve)

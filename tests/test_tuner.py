@@ -118,3 +118,34 @@ def test_tuner_error_paths():
     assert ei.value.status == P.OPEVO_E_ILLEGAL
     P.opevo_tuner_tell(t, xs, [1.0] * len(xs))
     P.opevo_tuner_destroy(t); P.opevo_space_destroy(sp)
+
+
+def test_uniform_mutation_control_resamples_whole_parameters_and_keeps_the_rules():
+    """The plain-EA control: per parameter, with probability q, a uniformly random vertex.  It obeys
+    the same no-duplicate rule, is reproducible from the seed, and differs from the q-random walk."""
+    sp = P.opevo_space_create([dict(type=P.OPEVO_FACTOR, C=512, nu=4), dict(type=P.OPEVO_FACTOR, C=1024, nu=4),
+                               dict(type=P.OPEVO_FACTOR, C=1024, nu=2), dict(type=P.OPEVO_CATEGORICAL, n_values=2)])
+    w = P.opevo_space_width(sp)
+
+    def run(kind, seed):
+        t = P.opevo_tuner_create(sp, 8, 8, 0.5, seed)
+        P.opevo_tuner_set_mutation(t, kind)
+        seen, traj = set(), []
+        for _ in range(12):
+            cfgs = P.opevo_tuner_ask(t)
+            for c in cfgs:
+                assert P.opevo_space_is_legal(sp, c)
+                assert tuple(c) not in seen
+                seen.add(tuple(c))
+            traj += [tuple(c) for c in cfgs]
+            P.opevo_tuner_tell(t, cfgs, [float(sum(c[:w]) % 17) for c in cfgs])
+        P.opevo_tuner_destroy(t)
+        return traj
+
+    a, b, c = run(1, 7), run(1, 7), run(0, 7)
+    assert a == b and a[:8] == c[:8] and a[8:] != c[8:]      # same first generation, different children
+    t = P.opevo_tuner_create(sp, 8, 8, 0.5, 1)
+    with pytest.raises(P.OpevoError):
+        P.opevo_tuner_set_mutation(t, 2)
+    P.opevo_tuner_destroy(t)
+    P.opevo_space_destroy(sp)
