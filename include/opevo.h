@@ -204,8 +204,8 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         The first factor is the number of workgroups (grid z) that share one output tile; each
  *         reduces its own contiguous part of K and adds its partial sums into C with fp32 atomic
  *         adds.  Members with more than one partition need C cleared first: opevo_kernel_launch /
- *         opevo_kernel_time (and opevo_tune) enqueue a hipMemsetAsync of C before every launch of
- *         such a member, and the time of that clear counts as part of the trial.  The sum is the
+ *         opevo_kernel_time (and opevo_tune) enqueue a small fill kernel over C before every
+ *         launch of such a member, and the time of that clear counts as part of the trial.  The sum is the
  *         same up to the rounding of an fp32 addition order that varies from run to run.  For
  *         operators whose output has fewer tiles than the chip has compute units (MM3 of App. B.1:
  *         512 x 1024 from K = 4096) this is what fills the machine. */

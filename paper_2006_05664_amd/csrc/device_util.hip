@@ -6,12 +6,15 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdint>
 #include <mutex>
 #include <vector>
 
 #include "kernel.hpp"
 
 namespace {
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBlocks = 1024;
 constexpr int kThreads = 256;
@@ -55,6 +58,18 @@ __global__ void stamp_deadline(unsigned long long *ctl, unsigned long long ticks
     ctl[0] = wall_clock64();
     ctl[1] = ticks;
     ctl[2] = 0;
+}
+
+// Clears n_vec4 16-byte words: the output of a member whose workgroups add partial sums into it.
+// A kernel rather than hipMemsetAsync, so that a caller may record launches into a HIP graph.
+__global__ __launch_bounds__(256) void zero_words(f32x4_t *p, long n_vec4)
+{
+    const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_vec4; i += (long)gridDim.x * 256) p[i] = z;
+}
+__global__ void zero_tail(float *p, int n)
+{
+    if ((int)threadIdx.x < n) p[threadIdx.x] = 0.f;
 }
 
 std::mutex g_ws_mutex;
@@ -121,6 +136,21 @@ int deadline_ctl(unsigned long long **ctl)
     }
     *ctl = g_ctl[dev];
     return OPEVO_OK;
+}
+
+int zero_f32(float *p, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return OPEVO_OK;
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return fail(OPEVO_E_ARG, "output pointer is not 16-byte aligned");
+    const long n4 = long(n / 4);
+    if (n4 > 0) {
+        const long want = (n4 + 255) / 256;
+        const unsigned blocks = unsigned(want < 2048 ? want : 2048);
+        hipLaunchKernelGGL(zero_words, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4_t *>(p), n4);
+    }
+    if (n % 4) hipLaunchKernelGGL(zero_tail, dim3(1), dim3(64), 0, stream, p + n4 * 4, int(n % 4));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? OPEVO_OK : hip_fail(e, "zero_f32 launch");
 }
 
 int deadline_arm(unsigned long long *ctl, double timeout_ms, hipStream_t stream)

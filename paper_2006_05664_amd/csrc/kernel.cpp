@@ -99,7 +99,8 @@ int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStr
 {
     if (int rc = load_kernel(k)) return rc;
     // members whose workgroups add partial sums into the output start from a cleared output
-    if (k->zero_bytes) HIP_TRY(hipMemsetAsync(c, 0, k->zero_bytes, stream));
+    if (k->zero_bytes)
+        if (int rc = zero_f32(static_cast<float *>(c), int64_t(k->zero_bytes / 4), stream)) return rc;
     void *args[] = {(void *)&a, (void *)&b, (void *)&c, (void *)&ctl};
     // the direct-to-LDS template declares its stages statically; the others take dynamic LDS
     const unsigned dyn_lds = k->plan.path == 3 ? 0u : unsigned(k->plan.lds_bytes);

@@ -40,6 +40,8 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
 int deadline_ctl(unsigned long long **ctl);
 int deadline_arm(unsigned long long *ctl, double timeout_ms, hipStream_t stream);
 int deadline_expired(unsigned long long *ctl, hipStream_t stream, bool *expired);
+// Clears n floats at p (16-byte aligned) with a small kernel on `stream`.
+int zero_f32(float *p, int64_t n, hipStream_t stream);
 int hip_fail(hipError_t e, const char *what);
 
 }  // namespace opevo
