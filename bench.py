@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}   # MI355X dense MFMA / fp32 vector peaks
+HBM_PEAK_GBPS = 8000.0                                       # MI355X HBM3E
 
 # HBM-side bytes per launch (fetch, write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
 # known-size elementwise pass (profiles/mm8192_bf16_best_kernel_counters.txt), keyed by (workload, BM, BN): the
@@ -189,12 +190,25 @@ def main() -> int:
             traffic = {"fetch_bytes": measured[0], "write_bytes": measured[1], "total_bytes": measured[0] + measured[1],
                        "algorithmic_bytes": P.opevo_op_bytes(op),
                        "source": "rocprofv3 counters of %s (same %dx%d workgroup tile)" % (measured[2], plan.tile[0], plan.tile[1])}
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_TFLOPS[dtype], 4), "traffic": traffic,
+        # the roofline that binds: the larger of flops / MFMA peak and algorithmic bytes / HBM peak
+        # (8 TB/s).  The small batched operators move more bytes per flop than the chip's ratio.
+        alg_bytes = P.opevo_op_bytes(op)
+        gbps = alg_bytes / (ms * 1e-3) * 1e-9
+        frac_mfma, frac_hbm = achieved / PEAK_TFLOPS[dtype], gbps / HBM_PEAK_GBPS
+        if frac_hbm > frac_mfma:
+            head = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(frac_hbm, 4)}
+        else:
+            head = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                    "frac": round(frac_mfma, 4)}
+        roofline = {**head, "traffic": traffic, "frac_mfma": round(frac_mfma, 4), "frac_hbm": round(frac_hbm, 4),
+                    "algorithmic_bytes": alg_bytes,
+                    # back-to-back launches re-read the same inputs: a working set below the 256 MiB
+                    # memory-side cache never goes to HBM, and the byte rate can then exceed the HBM peak
+                    "fits_memory_side_cache": bool(alg_bytes <= 256 * 2 ** 20),
                     "kernel_ms": round(ms, 5), "kernel": kname,
                     "mfma_only_ceiling": round(ceiling, 1) if ceiling else None,
                     "mfma_only_ceiling_zero_operands": round(ceiling0, 1) if ceiling0 else None,
-                    "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}
+                    "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}   # achieved TFLOP/s over the MFMA-only ceiling
 
     out = {
         "metric": "best-found TFLOP/s after K OpEvo trials (and fraction of bf16 dense MFMA peak)",

@@ -215,7 +215,8 @@ typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P 
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
  *        BMM_TA {B, M, N, K}         C[b] = A[b]^T B[b] with the first operand stored as [B][K][M]
  *                                    (App. B.2: "transposed first"); same configuration spaces as
- *                                    BMM; runs on the scalar and the direct-to-LDS MFMA template
+ *                                    BMM; runs on every template (members with lds = 0 on the
+ *                                    scalar one)
  *        CONV2D {B, Cin, H, W, Cout, Hk, Wk, stride, pad}  NCHW image, OIHW kernel,
  *               out[B,Cout,Hout,Wout], Hout = floor((H+2*pad-Hk)/stride)+1 (App. B.3).
  * All tensors dense row-major.  `in` is the element type of both inputs; accumulation and

@@ -266,8 +266,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         }
         if (nstage_dlds) path = 3;
     }
-    // a transposed first operand is read by the scalar and the direct-to-LDS template only
-    if (op.trans_a && path != 3) path = 0;
+    // a transposed first operand is staged by the MFMA templates like B (rows of 8 along M), so it
+    // needs M % 8 == 0 and LDS staging; other members run on the scalar template
+    if (op.trans_a && (path == 1 || path == 2) && (op.M % 8 != 0 || !stage_lds)) path = 0;
 
     int64_t NT;
     if (four_level) NT = 64 * WM * WN;
@@ -301,7 +302,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (linear && n_blocks > INT32_MAX) invalid(p, "%ld workgroups in a one-dimensional grid", long(n_blocks));
     else if (path != 0 && path != 3 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
-        const int64_t a_chunks = (BM * (BKP / 8) + NT - 1) / NT;
+        const int64_t a_chunks = op.trans_a ? 8 * (((BK / 8) * (BM / 8) + NT - 1) / NT) : (BM * (BKP / 8) + NT - 1) / NT;
         const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BKP / 8) + NT - 1) / NT
                                                            : 8 * (((BK / 8) * (BN / 8) + NT - 1) / NT);
         if ((a_chunks + b_chunks) * 4 > 256)

@@ -146,14 +146,73 @@ constexpr int gcd_(int a, int b) { return b ? gcd_(b, a % b) : a; }
 #endif
 #endif
 
+#if A_TRANS && !STAGE_LDS
+#error "a transposed first operand needs LDS staging"
+#endif
+#if A_TRANS
+// first operand stored [K][M] (M contiguous): its slab travels like B's, in KBA(k) x 8(m) blocks
+constexpr int KBA = ((BK / 8) * (BM / 8) >= NT) ? 8 : ((BK / 4) * (BM / 8) >= NT) ? 4 : 2;
+constexpr int AT_CHUNKS = (BK / KBA) * (BM / 8);
+constexpr int NAT = (AT_CHUNKS + NT - 1) / NT;
+#endif
+
 struct Slab {
+#if A_TRANS
+    u32x4 at[NAT][KBA];
+#else
     u32x4 a[NA];
+#endif
 #if OP == OP_CONV
     u32x4 b[NB];
 #else
     u32x4 b[NB][KB];
 #endif
 };
+
+// An operand whose rows run along the reduction axis in memory (B[k][n]; A[k][m] when the first
+// operand is stored transposed): thread-owned blocks of KBX(k) x 8 elements, loaded as KBX 16-byte
+// rows.  Consecutive lanes take consecutive k-blocks of the same 8 columns: their transposed LDS
+// rows are then contiguous (no bank conflicts) and each global row still gets whole 128-byte
+// segments from the 8 lanes that share a k-block.  base points at element [k0][first column of the tile].
+template <int KBX, int CHUNKS, int NX>
+__device__ __forceinline__ void load_kmajor(u32x4 (&r)[NX][KBX], const u16 *__restrict__ base, long ld, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+        const int q = tid + i * NT;
+        if (CHUNKS % NT == 0 || q < CHUNKS) {
+            const int kb = q % (BK / KBX), xb = q / (BK / KBX);
+#pragma unroll
+            for (int j = 0; j < KBX; ++j) r[i][j] = *(const u32x4 *)(base + (long)(kb * KBX + j) * ld + xb * 8);
+        }
+    }
+}
+// ... and stored into a stage part laid out [column][k]: each block is transposed in registers
+// (row j of the block is k = kb*KBX + j holding columns xb*8 .. +7) and written as 8 rows of KBX k.
+template <int KBX, int CHUNKS, int NX>
+__device__ __forceinline__ void store_kmajor(const u32x4 (&r)[NX][KBX], u16 *S, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+        const int q = tid + i * NT;
+        if (CHUNKS % NT == 0 || q < CHUNKS) {
+            const int kb = q % (BK / KBX), xb = q / (BK / KBX);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int d = c / 2;
+                u32 o[KBX / 2];
+#pragma unroll
+                for (int t = 0; t < KBX / 2; ++t)
+                    o[t] = (c % 2 == 0) ? ((r[i][2 * t][d] & 0xffffu) | (r[i][2 * t + 1][d] << 16))
+                                        : ((r[i][2 * t][d] >> 16) | (r[i][2 * t + 1][d] & 0xffff0000u));
+                u16 *dst = S + lds_off(xb * 8 + c, kb * KBX);
+                if (KBX == 8) { u32x4 v; v.x = o[0]; v.y = o[1 % (KBX / 2)]; v.z = o[2 % (KBX / 2)]; v.w = o[3 % (KBX / 2)]; *(u32x4 *)dst = v; }
+                else if (KBX == 4) { typedef __attribute__((ext_vector_type(2))) unsigned int u32x2; u32x2 v; v.x = o[0]; v.y = o[1 % (KBX / 2)]; *(u32x2 *)dst = v; }
+                else { *(u32 *)dst = o[0]; }
+            }
+        }
+    }
+}
 
 #if OP == OP_CONV && CONV_TABLE
 // piece i of a thread gathers column (tid + i*NT) % BN: the columns repeat every COL_PERIOD pieces
@@ -175,6 +234,9 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
 #endif
 )
 {
+#if A_TRANS
+    load_kmajor<KBA, AT_CHUNKS, NAT>(s.at, Ab + (long)k0 * M + m0, M, tid);
+#else
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
@@ -195,11 +257,14 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
             }
         }
     }
+#endif
+#if OP != OP_CONV
+    load_kmajor<KB, B_CHUNKS, NB>(s.b, Bb + (long)k0 * N + n0, N, tid);
+#else
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int q = tid + i * NT;
         if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
-#if OP == OP_CONV
             const int c = q % BN, kc = q / BN;
             u32 h[8];
 #if CONV_TABLE
@@ -228,21 +293,16 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
             v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
             v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
             s.b[i] = v;
-#else
-            // consecutive lanes take consecutive k-blocks of the same 8 columns: their transposed
-            // LDS rows are then contiguous (no bank conflicts) and each global row still gets
-            // whole 128-byte segments from the 8 lanes that share a k-block
-            const int kb = q % (BK / KB), nb = q / (BK / KB);
-#pragma unroll
-            for (int j = 0; j < KB; ++j)
-                s.b[i][j] = *(const u32x4 *)(Bb + (long)(k0 + kb * KB + j) * N + n0 + nb * 8);
-#endif
         }
     }
+#endif
 }
 
 __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int tid)
 {
+#if A_TRANS
+    store_kmajor<KBA, AT_CHUNKS, NAT>(s.at, As, tid);
+#else
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
@@ -251,32 +311,19 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
             *(u32x4 *)(As + lds_off(row, kc * 8)) = s.a[i];
         }
     }
+#endif
+#if OP == OP_CONV
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int q = tid + i * NT;
         if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
-#if OP == OP_CONV
             const int c = q % BN, kc = q / BN;
             *(u32x4 *)(Bs + lds_off(c, kc * 8)) = s.b[i];
-#else
-            const int kb = q % (BK / KB), nb = q / (BK / KB);
-            // KB x 8 transpose: row j of the block is k = kb*KB+j holding n = nb*8 .. +7
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const int d = c / 2;
-                u32 o[KB / 2];
-#pragma unroll
-                for (int t = 0; t < KB / 2; ++t)
-                    o[t] = (c % 2 == 0) ? ((s.b[i][2 * t][d] & 0xffffu) | (s.b[i][2 * t + 1][d] << 16))
-                                        : ((s.b[i][2 * t][d] >> 16) | (s.b[i][2 * t + 1][d] & 0xffff0000u));
-                u16 *dst = Bs + lds_off(nb * 8 + c, kb * KB);
-                if (KB == 8) { u32x4 v; v.x = o[0]; v.y = o[1 % (KB / 2)]; v.z = o[2 % (KB / 2)]; v.w = o[3 % (KB / 2)]; *(u32x4 *)dst = v; }
-                else if (KB == 4) { typedef __attribute__((ext_vector_type(2))) unsigned int u32x2; u32x2 v; v.x = o[0]; v.y = o[1 % (KB / 2)]; *(u32x2 *)dst = v; }
-                else { *(u32 *)dst = o[0]; }
-            }
-#endif
         }
     }
+#else
+    store_kmajor<KB, B_CHUNKS, NB>(s.b, Bs, tid);
+#endif
 }
 
 // MFMAs of one LDS-resident slab.  Lane l of a wave supplies, for atom row/column l % ATOM,

@@ -393,22 +393,27 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
 
 # ------------------------------------------------------------------ BatchMatMul with a transposed first operand
 def test_bmm_with_transposed_first_operand(torch_cuda):
-    """App. B.2, BMM2 / BMM3: the first operand is stored [B][K][M].  Scalar template and the
-    direct-to-LDS MFMA template (A staged as [BK][BM] and read with the transposing LDS load)."""
+    """App. B.2, BMM2 / BMM3: the first operand is stored [B][K][M].  Scalar template, the
+    register-staged MFMA template (A blocks transposed in registers like B's) and the direct-to-LDS
+    template (A staged as [BK][BM] and read with the transposing LDS load)."""
     w = Workload(torch_cuda, "bmm_ta", (24, 128, 64, 128), "bf16", 51)          # BMM2's matrices, 24 batches
     for label, cfg in [("direct-to-LDS 128x64, slab 64, 2 waves", [6, 4, 1, 2, 2, 32, 1, 1, 2, 32, 2, 64, 1]),
-                       ("64x64 tile, slab 128: body too large for direct-to-LDS, scalar", [24, 1, 2, 1, 2, 32, 1, 1, 1, 64, 1, 128, 1]),
+                       ("64x64 tile, slab 128: body too large for direct-to-LDS, register-staged", [24, 1, 2, 1, 2, 32, 1, 1, 1, 64, 1, 128, 1]),
+                       ("register-staged mfma32, slab 16, 2 waves", [6, 4, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1]),
+                       ("register-staged mfma32, one wave, 32x32", [24, 1, 4, 1, 1, 32, 2, 1, 1, 32, 8, 16, 1]),
+                       ("register-staged mfma16, 4 waves of 16x16", [6, 4, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 1]),
+                       ("register-staged mfma16, single stage would be lds=0: scalar", [6, 4, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0]),
                        ("direct-to-LDS 32x32 tiles, slab 32", [3, 8, 4, 1, 1, 32, 2, 1, 1, 32, 4, 32, 1]),
                        ("scalar", [4, 6, 8, 2, 2, 4, 4, 2, 4, 2, 8, 16, 1]),
                        ("flag 0 (scalar for this operand layout)", [24, 1, 2, 2, 1, 32, 1, 2, 1, 32, 1, 128, 0])]:
         w.check(P.OPEVO_TILE4, cfg, label)
-    for cfg in w.random_valid(P.OPEVO_TILE4, 10, seed=111, want_paths=(0, 3)):
+    for cfg in w.random_valid(P.OPEVO_TILE4, 16, seed=111, want_paths=(0, 1, 2, 3)):
         w.check(P.OPEVO_TILE4, cfg, "random")
     w.close()
     w = Workload(torch_cuda, "bmm_ta", (15, 64, 64, 128), "bf16", 52)           # BMM3's matrices, odd batch
-    for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=112, want_paths=(0, 3)):
+    for cfg in w.random_valid(P.OPEVO_TILE4, 12, seed=112, want_paths=(0, 1, 2, 3)):
         w.check(P.OPEVO_TILE4, cfg, "random")
-    for cfg in w.random_valid(P.OPEVO_TILE4X, 4, seed=113, want_paths=(0, 3)):
+    for cfg in w.random_valid(P.OPEVO_TILE4X, 4, seed=113, want_paths=(0, 1, 2, 3)):
         w.check(P.OPEVO_TILE4X, cfg, "random")
     w.close()
 
@@ -458,8 +463,8 @@ PAPER_SHAPES = [
     ("BMM1", "bmm", (960, 128, 64, 128), 1242, 6, (0, 1, 2, 3),
      [("direct-to-LDS, 15 grid rows of 64 batches", [15, 64, 2, 1, 2, 32, 1, 1, 1, 64, 2, 64, 1]),
       ("mfma16, 480 batches per workgroup", [2, 480, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0])]),
-    ("BMM2", "bmm_ta", (960, 128, 64, 128), 1245, 6, (0, 3), []),
-    ("BMM3", "bmm_ta", (960, 64, 64, 128), 1246, 6, (0, 3), []),
+    ("BMM2", "bmm_ta", (960, 128, 64, 128), 1245, 6, (0, 1, 2, 3), []),
+    ("BMM3", "bmm_ta", (960, 64, 64, 128), 1246, 6, (0, 1, 2, 3), []),
     ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (1, 2), []),
     # C1's reduction axis 3*11*11 = 363 has no factor 16: MFMA members stage zero-padded K slabs
     ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (1, 2),

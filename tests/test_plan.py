@@ -210,7 +210,7 @@ def test_extended_variant_decodes_to_a_linear_grid_with_the_same_tiles():
         assert ei.value.status == P.OPEVO_E_ILLEGAL
 
 
-def test_transposed_first_operand_uses_the_scalar_or_the_direct_to_lds_template():
+def test_transposed_first_operand_runs_on_every_template():
     op = P.opevo_op_create(P.OPEVO_BMM_TA, (960, 128, 64, 128), P.OPEVO_BF16)
     assert P.opevo_op_sizes(op) == (960 * 128 * 128, 960 * 128 * 64, 960 * 128 * 64)
     sp = P.opevo_op_space(op, P.OPEVO_TILE4)
@@ -220,8 +220,11 @@ def test_transposed_first_operand_uses_the_scalar_or_the_direct_to_lds_template(
         plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, P.opevo_space_random(sp, rng))
         if plan.status == P.OPEVO_OK:
             paths.add(plan.path)
-    assert paths == {0, 3}
-    for cfg, path in (([160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 2, 64, 1], 3), ([160, 6, 8, 2, 2, 4, 4, 2, 4, 2, 8, 16, 1], 0)):
+    assert paths == {0, 1, 2, 3}
+    for cfg, path in (([160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 2, 64, 1], 3), ([160, 6, 8, 2, 2, 4, 4, 2, 4, 2, 8, 16, 1], 0),
+                      ([160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1], 1),      # register-staged, A blocks transposed like B's
+                      ([160, 6, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 1], 2),
+                      ([160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 0], 0)):     # no LDS staging: scalar for this layout
         plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
         assert plan.status == P.OPEVO_OK and plan.path == path, (cfg, plan.path, plan.reason)
         kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4, cfg)
