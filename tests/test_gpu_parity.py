@@ -5,7 +5,6 @@ Tolerances (written out here): bf16/fp16 inputs, fp32 accumulate:
     max_i |c_i - ref_i| / (|ref_i| + 1) <= 2e-2   and   ||c - ref||_F / ||ref||_F <= 5e-3
 fp32 inputs:  both quantities <= 1e-4.
 """
-import os
 import sys
 from concurrent.futures import ThreadPoolExecutor
 

@@ -8,7 +8,6 @@ of Sec. 4.3 about its example graph, and the invariants of Alg. 1.
 import math
 import os
 from fractions import Fraction
-from itertools import product
 
 import numpy as np
 import pytest

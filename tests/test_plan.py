@@ -1,6 +1,5 @@
 """Configuration decoder: legality, validity, launch geometry, and that representative
 members of every template family compile for gfx950 through hipRTC (no GPU needed)."""
-import numpy as np
 import pytest
 
 import paper_2006_05664_amd as P
