@@ -304,7 +304,7 @@ int opevo_kernel_launch(opevo_kernel *kernel, const void *a, const void *b, void
  * one hipEvent between consecutive samples on `stream` and a single synchronisation at the
  * end, so the GPU never idles inside the measurement.  ms per launch of each sample into
  * samples_ms (may be NULL), median into *median_ms.  launches_per_sample <= 0: chosen so that
- * one sample spans at least 200 us.  A launch of 50 ms or more is taken as the measurement
+ * one sample spans at least 200 us.  A launch of 20 ms or more is taken as the measurement
  * on its own.  warmup_ms > 0 extends the warm-up until that much GPU time has been spent
  * (at most 4000 launches): after idling the device needs tens of milliseconds to reach its
  * sustained clocks, and a sample taken earlier under-reports the kernel by up to a quarter.
