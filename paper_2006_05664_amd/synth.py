@@ -83,6 +83,12 @@ WORKLOADS: Dict[str, dict] = {
     "bmm3_bf16": dict(kind="bmm_ta", dims=(960, 64, 64, 128), dtype="bf16", seed=1246),    # (128x64)^T . (128x64)
     "c1_bf16": dict(kind="conv2d", dims=(512, 3, 227, 227, 64, 11, 11, 4, 0), dtype="bf16", seed=1243),
     "c2_bf16": dict(kind="conv2d", dims=(512, 64, 27, 27, 192, 5, 5, 1, 2), dtype="bf16", seed=1244),
+    # the MatMul / BMM shapes at the paper's own precision (fp32 inputs, fp32 MFMA atoms)
+    "mm1_f32": dict(kind="matmul", dims=(512, 1024, 1024), dtype="f32", seed=1235, dist="normal"),
+    "mm2_f32": dict(kind="matmul", dims=(512, 4096, 1024), dtype="f32", seed=1240, dist="normal"),
+    "mm3_f32": dict(kind="matmul", dims=(512, 1024, 4096), dtype="f32", seed=1241, dist="normal"),
+    "bmm1_f32": dict(kind="bmm", dims=(960, 128, 64, 128), dtype="f32", seed=1242),
+    "mm8192_f32": dict(kind="matmul", dims=(8192, 8192, 8192), dtype="f32", seed=1238, dist="normal"),
 }
 
 

@@ -210,6 +210,34 @@ def test_matmul_fp16_inputs(torch_cuda):
     w.close()
 
 
+def test_matmul_and_bmm_fp32_inputs_on_the_fp32_mfma_template(torch_cuda):
+    """The paper's own precision: fp32 inputs on 32x32x2 fp32 atoms (tolerance 1e-4 on both measures),
+    both stage counts, several wave layouts, a split reduction, a batched operator, random members."""
+    w = Workload(torch_cuda, "matmul", (256, 384, 512), "f32", 78)
+    for label, cfg, path in [("fp32 mfma, 2x2 waves of 64x64, two stages", [2, 2, 2, 32, 3, 2, 2, 32, 16, 32, 1], 4),
+                             ("fp32 mfma, single stage", [2, 2, 2, 32, 3, 2, 2, 32, 16, 32, 0], 4),
+                             ("fp32 mfma, one wave, slab 8", [8, 1, 1, 32, 12, 1, 1, 32, 64, 8, 1], 4),
+                             ("fp32 mfma, 1x3 waves of 32x128, slab 32", [8, 1, 1, 32, 1, 3, 4, 32, 16, 32, 1], 4),
+                             ("fp32 mfma, deep slab 128, single stage", [4, 2, 1, 32, 6, 2, 1, 32, 4, 128, 0], 4),
+                             ("slab 4: scalar", [2, 2, 2, 32, 3, 2, 2, 32, 128, 4, 1], 0),
+                             ("16-wide wave tile: scalar", [8, 2, 1, 16, 12, 2, 1, 16, 16, 32, 1], 0)]:
+        plan = P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == path, (label, plan.path, plan.reason)
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.check(P.OPEVO_TILE4K, [2, 2, 2, 32, 3, 2, 2, 32, 4, 4, 32, 1], "fp32 mfma, reduction split over 4 workgroups")
+    for cfg in w.random_valid(P.OPEVO_TILE4, 12, seed=1212, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "bmm", (6, 128, 64, 128), "f32", 79)
+    for label, cfg in [("fp32 bmm, 3 batches per workgroup", [2, 3, 2, 2, 1, 32, 1, 2, 1, 32, 4, 32, 1]),
+                       ("fp32 bmm, lds flag 0 (single stage)", [6, 1, 4, 1, 1, 32, 2, 1, 1, 32, 8, 16, 0])]:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == 4, label
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=1313, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
 def test_matmul_multi_prime_axes(torch_cuda):
     # 96 = 2^5*3, 160 = 2^5*5, 224 = 2^5*7: factor moves of several primes, ragged thread shares
     w = Workload(torch_cuda, "matmul", (96, 160, 224), "bf16", 5)

@@ -380,3 +380,21 @@ def test_split_reduction_templates_compile(label, cfg, path):
     kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4K, cfg)
     assert P.opevo_kernel_code_size(kernel) > 1000
     P.opevo_kernel_destroy(kernel)
+
+
+def test_fp32_inputs_use_the_fp32_mfma_template_where_the_tile_allows():
+    op = _op(MM1, P.OPEVO_F32)
+    for cfg, path in (([4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1], 4), ([4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 0], 4),
+                      ([4, 2, 2, 32, 8, 2, 2, 32, 256, 4, 1], 0),        # slab not a multiple of 8
+                      ([16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 1], 0)):      # wave tile not made of 32 x 32 atoms
+        plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == path, (cfg, plan.path, plan.reason)
+    # two stages of (128 x 36 + 32 x 132) floats
+    assert P.opevo_kernel_plan(op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1]).lds_bytes == 2 * (128 * 36 + 32 * 132) * 4
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
+    assert "gemm_mfma_f32" in P.opevo_kernel_defines(op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
+    P.opevo_kernel_destroy(kernel)
+    # 16-bit inputs never take it; convolutions and a transposed first operand neither
+    assert P.opevo_kernel_plan(_op(MM1, P.OPEVO_BF16), P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1]).path in (1, 3)
+    ta = P.opevo_op_create(P.OPEVO_BMM_TA, (960, 128, 64, 128), P.OPEVO_F32)
+    assert P.opevo_kernel_plan(ta, P.OPEVO_TILE4, [160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1]).path == 0
