@@ -178,8 +178,10 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         Conv2d  B(2) Cout(4) H(4) W(4) R(2) unroll{0,1},  R = Cin*Hk*Wk
  *         MFMA kernels (bf16/fp16 inputs) where the per-wave tile is made of 32x32 or 16x16
  *         atoms and the LDS tile of whole MFMA K-steps; a scalar-FMA kernel otherwise.
- *         fp32 inputs (MatMul / BMM): 32x32x2 fp32 MFMA atoms where the per-wave tile is made of
- *         32x32 atoms and the LDS tile is a multiple of 8 (and K, N multiples of 4); else scalar.
+ *         fp32 inputs: 32x32x2 fp32 MFMA atoms; MatMul / BMM where the per-wave tile is made of
+ *         32x32 atoms and the LDS tile is a multiple of 8 (and the contiguous axes multiples of 4),
+ *         Conv2d with the same widening as above (slabs padded to 8, wave tiles rounded up to 32);
+ *         else scalar.
  *         Conv2d widens this: an LDS tile of any length is zero-padded to whole K-steps, and a
  *         per-wave tile that is no multiple of 16 is rounded up to whole 16x16 atoms as long as
  *         that at most doubles the work (the overhang is computed and not stored).

@@ -241,11 +241,19 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             else if (align_ok && TM % 16 == 0 && TN % 16 == 0 && BK % 32 == 0) path = 2;
         }
     }
-    // fp32 inputs: 32x32x2 fp32 atoms (MatMul / BMM, first operand not transposed), both operands in
-    // 16-byte pieces, K slabs in groups of 8
-    if (four_level && op.dtype == OPEVO_F32 && op.kind != OPEVO_CONV2D && !op.trans_a && TM % 32 == 0 && TN % 32 == 0 &&
-        BK % 8 == 0 && op.K % 4 == 0 && op.N % 4 == 0)
+    // fp32 inputs: 32x32x2 fp32 atoms (MatMul / BMM), both operands in 16-byte pieces along their
+    // contiguous axis, K slabs in groups of 8
+    if (four_level && op.dtype == OPEVO_F32 && op.kind != OPEVO_CONV2D && TM % 32 == 0 && TN % 32 == 0 &&
+        BK % 8 == 0 && op.N % 4 == 0 && (op.trans_a ? op.M % 4 == 0 : op.K % 4 == 0))
         path = 4;
+    // fp32 Conv2d: operands gathered value by value, so any slab length (staged padded to 8) and any
+    // wave tile whose round-up to whole 32x32 atoms at most doubles the work
+    if (four_level && op.dtype == OPEVO_F32 && op.kind == OPEVO_CONV2D) {
+        const int64_t TMp = (TM + 31) / 32 * 32, TNp = (TN + 31) / 32 * 32;
+        if (TMp * TNp <= 2 * TM * TN && op.b_elems() < (int64_t(1) << 31)) {
+            path = 4; BKP = (BK + 7) / 8 * 8; TMacc = TMp; TNacc = TNp;
+        }
+    }
     const bool stage_lds = path == 4 || !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
     // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
     // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.
@@ -285,7 +293,11 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     const int nstage = path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
-    else if (path == 4) lds = nstage * (BM * (BK + 4) + BK * (BN + 4)) * 4;
+    else if (path == 4 && op.kind == OPEVO_CONV2D) {
+        const int64_t a_rows = (WM - 1) * TM + TMacc, b_cols = ((WN - 1) * TN + TNacc + 3) / 4 * 4;   // with the overhang
+        lds = nstage * (a_rows * (BKP + 4) + BKP * (b_cols + 4)) * 4;
+    }
+    else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
@@ -307,7 +319,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (!linear && (m1 > 65535 || b1 > 65535)) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
     else if (linear && n_blocks > INT32_MAX) invalid(p, "%ld workgroups in a one-dimensional grid", long(n_blocks));
     else if (path == 4) {
-        const int64_t chunks = (BM * (BK / 4) + NT - 1) / NT + (BK * (BN / 4) + NT - 1) / NT;
+        const int64_t chunks = op.kind == OPEVO_CONV2D ? (BM * (BKP / 4) + NT - 1) / NT + (BKP * ((BN + 3) / 4) + NT - 1) / NT
+                                                       : (BM * (BK / 4) + NT - 1) / NT + (BK * (BN / 4) + NT - 1) / NT;
         if (chunks * 4 > 256) invalid(p, "%ld staging registers per lane > 256", long(chunks * 4));
     }
     else if (path != 0 && path != 3 && stage_lds) {

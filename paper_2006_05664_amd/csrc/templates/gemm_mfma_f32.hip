@@ -14,15 +14,45 @@
 //   Bs[BK][BN + 4]: for MFMA j a lane reads the value at row 8g + 4*(l / 32) + j of its column
 //                   (32 consecutive floats per half wave: conflict-free).
 // Which k are paired inside an instruction does not matter as long as both operands agree.
+// A_TRANS (first operand stored [K][M]): A is staged [BK][BM + 4] and read like B.
+// Conv2d (implicit GEMM, App. B.3): the kernel tensor is A, the image is gathered into B's layout
+// value by value (bounds-checked taps, zero padding).  A K slab of BK taps is staged BKP = BK
+// rounded up to 8 wide (rows of zeros), and a wave tile that is no multiple of 32 is rounded up to
+// whole atoms: the overhang reads rows / columns of its neighbours (or the slack behind the tile)
+// and is never stored.
 // FLAG = 1: two LDS stages; the 16-byte pieces of slab kt+1 are loaded into registers before the
 //           MFMAs of slab kt and written to the other stage after them (one barrier per slab).
 // FLAG = 0: one stage, load -> barrier -> store -> barrier -> compute.
 
 typedef f32x16 acc_t;
-constexpr int MI = TM / 32, NI = TN / 32;
-constexpr int LDA = BK + 4, LDB = BN + 4;                     // floats; rows stay 16-byte aligned
-constexpr int A_STAGE = BM * LDA, B_STAGE = BK * LDB;
-constexpr int A_CHUNKS = BM * (BK / 4), B_CHUNKS = BK * (BN / 4);   // 16-byte pieces of a slab
+#ifndef BKP
+#define BKP BK
+#endif
+constexpr int MI = (TM + 31) / 32, NI = (TN + 31) / 32;
+#if OP == OP_CONV
+// rows of A / columns of B that the last atoms of the last waves may read past the tile
+constexpr int A_ROWS = (WM - 1) * TM + MI * 32, B_COLS = ((WN - 1) * TN + NI * 32 + 3) / 4 * 4;
+constexpr int LDA = BKP + 4;
+constexpr int A_STAGE = A_ROWS * LDA;
+constexpr int A_CHUNKS = BM * (BKP / 4);                      // (row, 4 taps)
+constexpr int LDB = B_COLS + 4;
+constexpr int B_STAGE = BKP * LDB;
+constexpr int BN4 = (BN + 3) / 4;
+constexpr int B_CHUNKS = BKP * BN4;                           // (tap, 4 columns)
+#else
+#if A_TRANS   // first operand stored [K][M]: staged [BK][BM + 4] and read like B, one value per MFMA
+constexpr int LDA = BM + 4;
+constexpr int A_STAGE = BK * LDA;
+constexpr int A_CHUNKS = BK * (BM / 4);
+#else
+constexpr int LDA = BK + 4;                                   // floats; rows stay 16-byte aligned
+constexpr int A_STAGE = BM * LDA;
+constexpr int A_CHUNKS = BM * (BK / 4);                       // 16-byte pieces of a slab
+#endif
+constexpr int LDB = BN + 4;
+constexpr int B_STAGE = BK * LDB;
+constexpr int B_CHUNKS = BK * (BN / 4);
+#endif
 constexpr int NA = (A_CHUNKS + NT - 1) / NT, NB = (B_CHUNKS + NT - 1) / NT;
 #ifndef NSTAGE
 #define NSTAGE 1
@@ -30,6 +60,49 @@ constexpr int NA = (A_CHUNKS + NT - 1) / NT, NB = (B_CHUNKS + NT - 1) / NT;
 
 struct Slab { f32x4 a[NA], b[NB]; };
 
+#if OP == OP_CONV
+// k0 = first position of the slab in the reduction walk (slab number * BK)
+__device__ __forceinline__ void load_slab(Slab &s, const float *__restrict__ Ab, const float *__restrict__ Bb,
+                                          int m0, const ColBlock &cb, int k0, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int q = tid + i * NT;
+        if (A_CHUNKS % NT == 0 || q < A_CHUNKS) {
+            const int row = q / (BKP / 4), kc = q % (BKP / 4);
+            f32x4 v;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = (kc * 4 + t < BK) ? Ab[(long)(m0 + row) * K + conv_tap(k0 + kc * 4 + t)] : 0.f;
+            s.a[i] = v;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int q = tid + i * NT;
+        if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
+            const int krow = q / BN4, c0 = (q % BN4) * 4;
+            f32x4 v;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = (krow < BK && c0 + t < BN) ? conv_b(Bb, cb, k0 + krow, c0 + t) : 0.f;
+            s.b[i] = v;
+        }
+    }
+}
+
+__device__ __forceinline__ void store_slab(const Slab &s, float *As, float *Bs, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int q = tid + i * NT;
+        if (A_CHUNKS % NT == 0 || q < A_CHUNKS) *(f32x4 *)(As + (q / (BKP / 4)) * LDA + (q % (BKP / 4)) * 4) = s.a[i];
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int q = tid + i * NT;
+        if (B_CHUNKS % NT == 0 || q < B_CHUNKS) *(f32x4 *)(Bs + (q / BN4) * LDB + (q % BN4) * 4) = s.b[i];
+    }
+}
+#else
 __device__ __forceinline__ void load_slab(Slab &s, const float *__restrict__ Ab, const float *__restrict__ Bb,
                                           int m0, int n0, int k0, int tid)
 {
@@ -37,7 +110,11 @@ __device__ __forceinline__ void load_slab(Slab &s, const float *__restrict__ Ab,
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS)
+#if A_TRANS
+            s.a[i] = *(const f32x4 *)(Ab + (long)(k0 + q / (BM / 4)) * M + m0 + (q % (BM / 4)) * 4);
+#else
             s.a[i] = *(const f32x4 *)(Ab + (long)(m0 + q / (BK / 4)) * K + k0 + (q % (BK / 4)) * 4);
+#endif
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -52,7 +129,11 @@ __device__ __forceinline__ void store_slab(const Slab &s, float *As, float *Bs, 
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int q = tid + i * NT;
+#if A_TRANS
+        if (A_CHUNKS % NT == 0 || q < A_CHUNKS) *(f32x4 *)(As + (q / (BM / 4)) * LDA + (q % (BM / 4)) * 4) = s.a[i];
+#else
         if (A_CHUNKS % NT == 0 || q < A_CHUNKS) *(f32x4 *)(As + (q / (BK / 4)) * LDA + (q % (BK / 4)) * 4) = s.a[i];
+#endif
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -60,6 +141,7 @@ __device__ __forceinline__ void store_slab(const Slab &s, float *As, float *Bs, 
         if (B_CHUNKS % NT == 0 || q < B_CHUNKS) *(f32x4 *)(Bs + (q / (BN / 4)) * LDB + (q % (BN / 4)) * 4) = s.b[i];
     }
 }
+#endif
 
 __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const float *As, const float *Bs, int wm, int wn, int lane)
 {
@@ -69,10 +151,17 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const float *
 #else
 #pragma unroll 1
 #endif
-    for (int g = 0; g < BK / 8; ++g) {
+    for (int g = 0; g < BKP / 8; ++g) {
         f32x4 af[MI];
+#if A_TRANS
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) af[i][j4] = As[(g * 8 + 4 * half + j4) * LDA + wm * TM + i * 32 + l32];
+#else
 #pragma unroll
         for (int i = 0; i < MI; ++i) af[i] = *(const f32x4 *)(As + (wm * TM + i * 32 + l32) * LDA + g * 8 + 4 * half);
+#endif
 #pragma unroll
         for (int j4 = 0; j4 < 4; ++j4) {
             float bf[NI];
@@ -96,10 +185,19 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const BlockId bid = block_id();
-    const int m0 = bid.m * BM, n0 = bid.n * BN;
+    const int m0 = bid.m * BM;
+#if OP == OP_CONV
+    const ColBlock cb = col_block(bid.n);
+#define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, cb, (kt) * BK, tid)
+#else
+    const int n0 = bid.n * BN;
+#define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, n0, (kt) * BK, tid)
+#endif
 
     for (int bi = 0; bi < BATCH_INNER; ++bi) {
-#if KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
+#if OP == OP_CONV
+        const float *Ab = A, *Bb = B;   // kernel tensor [M][K], image
+#elif KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
         const float *Ab = A + (long)bid.b * (KSTEPS * BK);
         const float *Bb = B + (long)bid.b * (KSTEPS * BK) * N;
         float *Cb = C;
@@ -121,20 +219,20 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
 #if NSTAGE == 2
         // every wave has left the previous batch's last slab before the stages are written again
         if (bi > 0) __syncthreads();
-        load_slab(slab, Ab, Bb, m0, n0, 0, tid);
+        LOAD_SLAB(slab, 0);
         store_slab(slab, As, Bs, tid);
         __syncthreads();
         for (int kt = 0; kt < KSTEPS; ++kt) {
             const int cur = kt & 1, nxt = cur ^ 1;
             // slab index clamped past the end: one redundant load instead of a branch around the accumulators
-            load_slab(slab, Ab, Bb, m0, n0, (kt + 1 < KSTEPS ? kt + 1 : KSTEPS - 1) * BK, tid);
+            LOAD_SLAB(slab, (kt + 1 < KSTEPS ? kt + 1 : KSTEPS - 1));
             compute_slab(acc, As + cur * A_STAGE, Bs + cur * B_STAGE, wm, wn, lane);
             store_slab(slab, As + nxt * A_STAGE, Bs + nxt * B_STAGE, tid);
             __syncthreads();
         }
 #else
         for (int kt = 0; kt < KSTEPS; ++kt) {
-            load_slab(slab, Ab, Bb, m0, n0, kt * BK, tid);
+            LOAD_SLAB(slab, kt);
             __syncthreads();
             store_slab(slab, As, Bs, tid);
             __syncthreads();
@@ -149,8 +247,14 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
             for (int j = 0; j < NI; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r / 4) + 4 * (lane >> 5) + r % 4;
-                    c_out(&Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)], acc[i][j][r]);
+                    const int row = i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + r % 4, col = j * 32 + (lane & 31);
+#if OP == OP_CONV
+                    // the overhang of a rounded-up wave tile is not stored
+                    if ((TM % 32 == 0 || row < TM) && (TN % 32 == 0 || col < TN))
+                        C[conv_c_index(cb, m0 + wm * TM + row, wn * TN + col)] = acc[i][j][r];
+#else
+                    c_out(&Cb[(long)(m0 + wm * TM + row) * N + n0 + wn * TN + col], acc[i][j][r]);
+#endif
                 }
     }
 }

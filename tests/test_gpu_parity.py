@@ -236,6 +236,39 @@ def test_matmul_and_bmm_fp32_inputs_on_the_fp32_mfma_template(torch_cuda):
     for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=1313, want_paths=(0, 4)):
         w.check(P.OPEVO_TILE4, cfg, "random")
     w.close()
+    w = Workload(torch_cuda, "bmm_ta", (6, 128, 64, 128), "f32", 80)             # first operand stored [B][K][M]
+    for label, cfg in [("fp32 transposed-A, 128x64 tile, two stages", [3, 2, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1]),
+                       ("fp32 transposed-A, single stage", [6, 1, 4, 1, 1, 32, 2, 1, 1, 32, 4, 32, 0])]:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == 4, label
+        w.check(P.OPEVO_TILE4, cfg, label)
+    for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=1414, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+
+
+def test_conv_fp32_inputs_on_the_fp32_mfma_template(torch_cuda):
+    """Conv2d with fp32 inputs (the paper's precision): implicit GEMM on fp32 atoms, padded slabs,
+    rounded-up wave tiles, boxed slabs of the separately split space, stride and padding variants."""
+    w = Workload(torch_cuda, "conv2d", (4, 16, 12, 12, 32, 5, 5, 1, 2), "f32", 81)
+    for label, cfg, path in [("fp32 conv, 32x32 tile, two stages", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 25, 16, 1], 4),
+                             ("fp32 conv, single stage", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 25, 16, 0], 4),
+                             ("fp32 conv, slab of 5 taps staged 8 wide", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 80, 5, 1], 4),
+                             ("fp32 conv, 24-column wave tile rounded up to 32", [2, 2, 1, 1, 1, 32, 2, 1, 1, 6, 6, 1, 1, 2, 16, 25, 1], 4),
+                             ("fp32 conv, scalar", [4, 1, 4, 2, 1, 4, 3, 1, 2, 2, 3, 2, 1, 2, 25, 16, 1], 0)]:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == path, label
+        w.check(P.OPEVO_TILE4, cfg, label)
+    w.check(P.OPEVO_TILE4P, [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 4, 4, 5, 1, 1, 5, 1, 0], "fp32 conv, box 4x1x5")
+    for cfg in w.random_valid(P.OPEVO_TILE4, 12, seed=1515, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (16, 3, 35, 35, 16, 11, 11, 4, 0), "f32", 82)     # C1-like: 11x11, stride 4, R = 363
+    for cfg in w.random_valid(P.OPEVO_TILE4, 10, seed=1616, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (2, 16, 9, 9, 32, 3, 3, 2, 1), "f32", 83)         # stride 2, padding 1
+    for cfg in w.random_valid(P.OPEVO_TILE4, 8, seed=1717, want_paths=(0, 4)):
+        w.check(P.OPEVO_TILE4, cfg, "random")
+    w.close()
 
 
 def test_matmul_multi_prime_axes(torch_cuda):

@@ -394,7 +394,19 @@ def test_fp32_inputs_use_the_fp32_mfma_template_where_the_tile_allows():
     kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
     assert "gemm_mfma_f32" in P.opevo_kernel_defines(op, P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1])
     P.opevo_kernel_destroy(kernel)
-    # 16-bit inputs never take it; convolutions and a transposed first operand neither
+    # 16-bit inputs never take it; a transposed first operand and convolutions do
     assert P.opevo_kernel_plan(_op(MM1, P.OPEVO_BF16), P.OPEVO_TILE4, [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1]).path in (1, 3)
+    conv = _op(C2_SMALL, P.OPEVO_F32)
+    for cfg, path, bkp in (([1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 25, 16, 1], 4, 16),
+                           ([1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 80, 5, 1], 4, 8),        # slab of 5 taps staged 8 wide
+                           ([2, 2, 1, 1, 1, 32, 2, 1, 1, 6, 6, 1, 1, 2, 16, 25, 1], 4, 32),      # 24-column wave tile rounded up to 32
+                           ([4, 1, 4, 2, 1, 4, 3, 1, 2, 2, 3, 2, 1, 2, 25, 16, 1], 0, 16)):      # 4 x 8 wave tile: scalar
+        plan = P.opevo_kernel_plan(conv, P.OPEVO_TILE4, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == path, (cfg, plan.path, plan.reason)
+        assert "-DBKP=%d" % bkp in P.opevo_kernel_defines(conv, P.OPEVO_TILE4, cfg)
     ta = P.opevo_op_create(P.OPEVO_BMM_TA, (960, 128, 64, 128), P.OPEVO_F32)
-    assert P.opevo_kernel_plan(ta, P.OPEVO_TILE4, [160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1]).path == 0
+    cfg = [160, 6, 1, 2, 2, 32, 1, 1, 2, 32, 8, 16, 1]
+    plan = P.opevo_kernel_plan(ta, P.OPEVO_TILE4, cfg)
+    assert plan.path == 4 and plan.lds_bytes == 2 * (16 * 132 + 16 * 68) * 4
+    kernel, _ = P.opevo_kernel_build(ta, P.OPEVO_TILE4, cfg)
+    P.opevo_kernel_destroy(kernel)
