@@ -212,7 +212,7 @@ def main() -> int:
                     "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}   # achieved TFLOP/s over the MFMA-only ceiling
 
     out = {
-        "metric": "best-found TFLOP/s after K OpEvo trials (and fraction of bf16 dense MFMA peak)",
+        "metric": "best-found TFLOP/s after K OpEvo trials (and fraction of %s dense MFMA peak)" % {"f16": "fp16", "f32": "fp32"}.get(dtype, dtype),
         "value": round(best, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / max(1, res["n_trials"]) * 1e3, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
