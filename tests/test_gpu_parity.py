@@ -532,13 +532,29 @@ PAPER_SHAPES = [
 ]
 
 
+PAPER_SHAPES_F32 = [
+    ("MM2 fp32", "matmul", (512, 4096, 1024), 1240, 16, (4,), [("fp32 mfma 128x128", [4, 2, 2, 32, 32, 2, 2, 32, 32, 32, 1])]),
+    ("BMM1 fp32", "bmm", (960, 128, 64, 128), 1242, 4, (4,), []),
+    ("BMM3 fp32", "bmm_ta", (960, 64, 64, 128), 1246, 4, (4,), []),
+    ("C2 fp32", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (4,), []),
+]
+
+
+def test_paper_operator_shapes_in_fp32_on_sampled_outputs(torch_cuda):
+    """The same at the paper's own precision (fp32 inputs, fp32 MFMA template), tolerance 1e-4."""
+    _paper_shapes(torch_cuda, PAPER_SHAPES_F32, "f32", TOL32, n_random=3)
+
+
 def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
     """MM2, MM3, BMM1-3, C1, C2 of App. B at full size (multi-prime axes: 960 = 2^6*3*5, 55 = 5*11,
     27 = 3^3, 192 = 2^6*3, 363 = 3*11^2, 1600 = 2^6*5^2).  The oracle computes a seeded sample of
     rows / batches / images; the whole output must be finite (NaN pre-fill)."""
-    torch = torch_cuda
-    for name, kind, dims, seed, n_sample, paths, picked in PAPER_SHAPES:
-        w = Workload(torch, kind, dims, "bf16", seed, oracle=False)
+    _paper_shapes(torch_cuda, PAPER_SHAPES, "bf16", TOL16, n_random=4)
+
+
+def _paper_shapes(torch, shapes, dtype, tol, n_random):
+    for name, kind, dims, seed, n_sample, paths, picked in shapes:
+        w = Workload(torch, kind, dims, dtype, seed, oracle=False)
         lead = dims[0]
         idx = np.sort(np.random.default_rng(seed).choice(lead, size=n_sample, replace=False))
         _say("  oracle sample for %s %s ..." % (name, dims))
@@ -552,7 +568,7 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
             ref = T.conv2d(w.b_host[idx], w.a_host, dims[7], dims[8])
         cases = [(label, cfg) for label, cfg in picked]
         if paths:
-            cases += [("random", list(c)) for c in w.random_valid(P.OPEVO_TILE4, 4, seed=seed + 1, want_paths=paths)]
+            cases += [("random", list(c)) for c in w.random_valid(P.OPEVO_TILE4, n_random, seed=seed + 1, want_paths=paths)]
         for label, cfg in cases:
             plan = P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg)
             assert plan.status == P.OPEVO_OK, (name, label, cfg, plan.reason)
@@ -564,7 +580,7 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
             out = out.reshape(lead, -1)
             assert np.all(np.isfinite(out)), (name, label)
             mx, fro = errors(out[idx].ravel(), np.asarray(ref).ravel())
-            assert mx <= TOL16[0] and fro <= TOL16[1], (name, label, cfg, mx, fro)
+            assert mx <= tol[0] and fro <= tol[1], (name, label, cfg, mx, fro)
         w.close()
 
 
