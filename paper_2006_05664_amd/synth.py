@@ -92,6 +92,7 @@ WORKLOADS: Dict[str, dict] = {
     "bmm3_f32": dict(kind="bmm_ta", dims=(960, 64, 64, 128), dtype="f32", seed=1246),
     "c1_f32": dict(kind="conv2d", dims=(512, 3, 227, 227, 64, 11, 11, 4, 0), dtype="f32", seed=1243),
     "c2_f32": dict(kind="conv2d", dims=(512, 64, 27, 27, 192, 5, 5, 1, 2), dtype="f32", seed=1244),
+    "mm8192_f16": dict(kind="matmul", dims=(8192, 8192, 8192), dtype="f16", seed=1238, dist="normal"),
     "mm8192_f32": dict(kind="matmul", dims=(8192, 8192, 8192), dtype="f32", seed=1238, dist="normal"),
 }
 
