@@ -699,6 +699,35 @@ def test_matmul_split_reduction(torch_cuda):
     w.close()
 
 
+def test_split_reduction_launch_can_be_captured_in_a_hip_graph(torch_cuda):
+    """The clear of C belongs to the launch and is a kernel (not a memset node), so a caller may record
+    the launch into a HIP graph: several replays, with eager work and synchronisations in between and
+    C dirtied before each, all reproduce the eager result."""
+    torch = torch_cuda
+    w = Workload(torch, "matmul", (256, 384, 1536), "bf16", 49)
+    kernel, _ = P.opevo_kernel_build(w.op, P.OPEVO_TILE4K, [2, 2, 2, 32, 3, 2, 2, 32, 6, 8, 32, 1])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        P.opevo_kernel_launch(kernel, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), side.cuda_stream)   # loads the module
+    side.synchronize()
+    mx, fro = errors(w.c.cpu().numpy(), w.ref)
+    assert mx <= TOL16[0] and fro <= TOL16[1]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        P.opevo_kernel_launch(kernel, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        w.c.fill_(float(rep) + 0.5)                    # dirty output: the graph's own clear must remove it
+        scratch = torch.randn(1 << 16, device="cuda:0").sum().item()     # unrelated eager work + a synchronisation
+        assert np.isfinite(scratch)
+        graph.replay()
+        torch.cuda.synchronize()
+        mx, fro = errors(w.c.cpu().numpy(), w.ref)
+        assert mx <= TOL16[0] and fro <= TOL16[1], (rep, mx, fro)
+    del graph
+    P.opevo_kernel_destroy(kernel)
+    w.close()
+
+
 # ------------------------------------------------------------------ harness pieces
 def test_compare_f32_matches_numpy(torch_cuda):
     torch = torch_cuda
