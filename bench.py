@@ -176,6 +176,14 @@ def main() -> int:
         kernel, _ = P.opevo_kernel_build(op, variant, roof_cfg)
         ms, _ = P.opevo_kernel_time(kernel, da.data_ptr(), db.data_ptr(), dc.data_ptr(), stream,
                                     warmup=3, launches_per_sample=20, samples=3)
+        # the same kernel on all-zero operands (no operand bits toggle, so the power-managed clock stays
+        # high): not the workload, only a measure of how much of the gap to the peak is the schedule's
+        ms_zero = None
+        if dtype != "f32" and P.opevo_op_bytes(op) < 4e9:
+            za, zb = torch.zeros_like(da), torch.zeros_like(db)
+            ms_zero, _ = P.opevo_kernel_time(kernel, za.data_ptr(), zb.data_ptr(), dc.data_ptr(), stream,
+                                             warmup=3, launches_per_sample=20, samples=3)
+            del za, zb
         P.opevo_kernel_destroy(kernel)
         achieved = flops / (ms * 1e-3) * 1e-12
         defines = P.opevo_kernel_defines(op, variant, roof_cfg)
@@ -209,7 +217,8 @@ def main() -> int:
                     "kernel_ms": round(ms, 5), "kernel": kname,
                     "mfma_only_ceiling": round(ceiling, 1) if ceiling else None,
                     "mfma_only_ceiling_zero_operands": round(ceiling0, 1) if ceiling0 else None,
-                    "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None}   # achieved TFLOP/s over the MFMA-only ceiling
+                    "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None,
+                    "same_kernel_on_zero_operands": round(flops / (ms_zero * 1e-3) * 1e-12, 2) if ms_zero else None}
 
     out = {
         "metric": "best-found TFLOP/s after K OpEvo trials (and fraction of %s dense MFMA peak)" % {"f16": "fp16", "f32": "fp32"}.get(dtype, dtype),
