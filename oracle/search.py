@@ -25,6 +25,13 @@ the design notes of the repository):
              starting from the rejected mutant; after 100 such re-mutations a uniformly
              random unsampled configuration is taken; none left => the space is exhausted
   R-budget   a trial is one evaluated configuration, the initial lambda included
+
+One thing here is NOT the paper's: `Space.mutate_uniform` and `OpEvo(..., mutation="uniform")`,
+the control experiment that replaces the topology-aware walk by the mutation of a plain
+evolutionary algorithm (per parameter, with probability p, a uniformly random vertex of its
+feasible set), so that what Sec. 4.3's walk buys can be measured.  Its definition is the one
+stated in the library's header; its law is p/|X_i| for every other vertex and 1 - p + p/|X_i| for
+the current one, which is what the tests pin it to.
 """
 from __future__ import annotations
 
@@ -331,6 +338,19 @@ class Space:
         return tuple(qwalk(p, v, q, rng) for p, v in zip(self.params, x))
 
 
+    def mutate_uniform(self, x: Config, p: float, rng: SplitMix64) -> Config:
+        """The control (not in the paper): the parameter graphs are ignored.  Parameter by parameter,
+        in order: u = next_double(); if u < p the parameter becomes vertex number
+        next_below(|X_i|) of its feasible set in enumeration order (which may be the vertex it
+        already had); otherwise it is kept and no second number is drawn."""
+        out = []
+        for vs, v in zip(self._verts, x):
+            if rng.next_double() < p:
+                v = vs[rng.next_below(len(vs))]
+            out.append(v)
+        return tuple(out)
+
+
 # ----------------------------------------------- selection + recombination (Sec. 4.2)
 def clamp_fitness(f: float) -> float:
     return f if f > 0.0 else 0.0  # also maps NaN to 0
@@ -386,9 +406,13 @@ class OpEvo:
     (the first generation is lambda random ones, later ones rho children);
     `tell` enqueues evaluated (configuration, fitness) pairs into Q."""
 
-    def __init__(self, space: Space, lam: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0):
-        assert lam >= 1 and rho >= 1 and 0.0 <= q < 1.0
+    def __init__(self, space: Space, lam: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0,
+                 mutation: str = "walk"):
+        assert lam >= 1 and rho >= 1 and 0.0 <= q < 1.0 and mutation in ("walk", "uniform")
         self.space, self.lam, self.rho, self.q = space, lam, rho, q
+        # "walk": Sec. 4.3's q-random walk on every parameter (Alg. 1 as published);
+        # "uniform": the plain-EA control, q then being the per-parameter resampling probability
+        self._mutate = space.mutate if mutation == "walk" else space.mutate_uniform
         self.rng = SplitMix64(seed)
         self.Q: List[Tuple[Config, float]] = []   # in trial order
         self.sampled = set()                      # evaluated or pending (R-dup)
@@ -434,8 +458,8 @@ class OpEvo:
         parents = [self.Q[t] for t in select_parents(self.Q, self.lam)]
         for _ in range(want):
             child = recombine(self.space, parents, self.rng)
-            child = self.space.mutate(child, self.q, self.rng)
-            child = self._fresh(child, lambda x: self.space.mutate(x, self.q, self.rng))
+            child = self._mutate(child, self.q, self.rng)
+            child = self._fresh(child, lambda x: self._mutate(x, self.q, self.rng))
             if child is None:
                 break
             self.sampled.add(child)
@@ -453,9 +477,9 @@ class OpEvo:
 
 
 def run_opevo(space: Space, f: Callable[[Config], float], budget: int, lam: int = 8, rho: int = 8,
-              q: float = 0.5, seed: int = 0) -> List[Tuple[Config, float]]:
+              q: float = 0.5, seed: int = 0, mutation: str = "walk") -> List[Tuple[Config, float]]:
     """Alg. 1 until `budget` configurations were evaluated (R-budget) or the space is exhausted."""
-    tuner = OpEvo(space, lam, rho, q, seed)
+    tuner = OpEvo(space, lam, rho, q, seed, mutation)
     while len(tuner.Q) < budget:
         xs = tuner.ask(budget - len(tuner.Q))
         if not xs:

@@ -347,3 +347,50 @@ def test_opevo_beats_uniform_random_search_on_average():
         rng = S.SplitMix64(1000 + seed)
         rnd.append(max(f(sp.random(rng)) for _ in range(300)))
     assert np.mean(evo) > 1.5 * np.mean(rnd)
+
+
+# ------------------------------------------ the plain-EA control (not the paper's; header-defined)
+def test_uniform_mutation_law_and_draw_count():
+    """Pin of the control: with probability p a parameter is redrawn uniformly, so every other vertex has
+    probability p/|X_i| and the current one 1 - p + p/|X_i|; parameters are independent; a kept parameter
+    costs one draw, a redrawn one two."""
+    sp = S.Space([S.Factor(8, 3), S.Categorical(4)])
+    x0 = ((8, 1, 1), (2,))
+    p, n = 0.4, 100000
+    rng = S.SplitMix64(123)
+    counts = [{}, {}]
+    joint_kept = 0
+    for _ in range(n):
+        y = sp.mutate_uniform(x0, p, rng)
+        assert sp.is_legal(y)
+        for i in range(2):
+            counts[i][y[i]] = counts[i].get(y[i], 0) + 1
+        joint_kept += (y == x0)
+    for i, size in enumerate((10, 4)):
+        assert len(counts[i]) == size
+        for v, c in counts[i].items():
+            want = p / size + ((1 - p) if v == x0[i] else 0.0)
+            assert abs(c / n - want) < 5 * math.sqrt(want * (1 - want) / n), (v, c / n, want)
+    want = (1 - p + p / 10) * (1 - p + p / 4)                    # independence of the parameters
+    assert abs(joint_kept / n - want) < 5 * math.sqrt(want * (1 - want) / n)
+    # p = 0 keeps everything and draws once per parameter; p close to 1 redraws everything (two draws each)
+    a, b = S.SplitMix64(5), S.SplitMix64(5)
+    assert sp.mutate_uniform(x0, 0.0, a) == x0
+    for _ in range(2):
+        b.next_u64()
+    assert a.state == b.state
+    a, b = S.SplitMix64(6), S.SplitMix64(6)
+    sp.mutate_uniform(x0, 1.0 - 1e-16, a)
+    for _ in range(4):
+        b.next_u64()
+    assert a.state == b.state
+
+
+def test_uniform_mutation_control_keeps_the_rules_of_alg1():
+    sp = _cfg1_space()
+    f = _peak_fitness(((8, 8), (4, 16), (2, 32)))
+    log = S.run_opevo(sp, f, budget=1000, seed=2, mutation="uniform")
+    assert len(log) == 343 and len({x for x, _ in log}) == 343          # no duplicates, exhausts, stops
+    a = S.run_opevo(sp, f, 100, seed=2, mutation="uniform")
+    b = S.run_opevo(sp, f, 100, seed=2, mutation="walk")
+    assert a[:8] == b[:8] and a != b                                    # same first generation, other children

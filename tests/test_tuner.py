@@ -120,6 +120,35 @@ def test_tuner_error_paths():
     P.opevo_tuner_destroy(t); P.opevo_space_destroy(sp)
 
 
+@pytest.mark.parametrize("descs,oparams,target,lam,rho,q,budget", CASES)
+@pytest.mark.parametrize("seed", [0, 7])
+def test_uniform_mutation_control_trajectory_equals_oracle(descs, oparams, target, lam, rho, q, budget, seed):
+    """The plain-EA control (opevo_tuner_set_mutation(..., 1)) against the oracle's, draw for draw."""
+    f = _fitness(target)
+    osp = S.Space(oparams)
+    want = S.run_opevo(osp, lambda x: f(osp.flat(x)), budget, lam, rho, q, seed, mutation="uniform")
+    sp = P.opevo_space_create(descs)
+    tuner = P.opevo_tuner_create(sp, lam, rho, q, seed)
+    P.opevo_tuner_set_mutation(tuner, 1)
+    got = []
+    while len(got) < budget:
+        xs = P.opevo_tuner_ask(tuner, budget - len(got))
+        if len(xs) == 0:
+            break
+        fit = [f(list(x)) for x in xs]
+        P.opevo_tuner_tell(tuner, xs, fit)
+        got += [(tuple(int(a) for a in x), fx) for x, fx in zip(xs, fit)]
+    assert got == [(tuple(osp.flat(x)), fx) for x, fx in want]
+    assert len({x for x, _ in got}) == len(got)
+    if osp.size() <= budget:
+        assert len(got) == osp.size()
+    # and it is a different search from the published one
+    walk = S.run_opevo(osp, lambda x: f(osp.flat(x)), budget, lam, rho, q, seed)
+    if osp.size() > budget:
+        assert [x for x, _ in walk] != [x for x, _ in want]
+    P.opevo_tuner_destroy(tuner); P.opevo_space_destroy(sp)
+
+
 def test_uniform_mutation_control_resamples_whole_parameters_and_keeps_the_rules():
     """The plain-EA control: per parameter, with probability q, a uniformly random vertex.  It obeys
     the same no-duplicate rule, is reproducible from the seed, and differs from the q-random walk."""
