@@ -342,6 +342,21 @@ int opevo_compare_rows_f32(const float *c, const float *ref_rows, const int32_t 
                            int64_t n_rows, int64_t row_len, void *stream,
                            double *max_scaled, double *rel_fro);
 
+/* opevo_compare_f32 for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same comparison with the same kernel, but the
+ * per-workgroup partial results live in a fixed array of 24 KiB of device memory that is part of the
+ * library's code object (one copy per GPU, held until the process ends), the final fold runs on
+ * the device in the same order as opevo_compare_f32's host fold, and nothing is copied back:
+ * result is a DEVICE pointer to two doubles that receive {max_scaled, rel_fro}, valid once the
+ * work enqueued on `stream` has finished.  The call allocates nothing, frees nothing and does
+ * not synchronise.  n may be at most OPEVO_COMPARE_STATIC_MAX_N; a larger n is refused with
+ * OPEVO_E_ARG.  All calls on one GPU share the one array: calls whose kernels may overlap there
+ * (different streams, or graphs replayed concurrently) race and must be serialised by the caller;
+ * no clearing is needed between calls (each call overwrites every partial it later reads). */
+#define OPEVO_COMPARE_STATIC_MAX_N ((int64_t)1 << 34)
+int opevo_compare_f32_static(const float *c, const float *ref, int64_t n, void *stream,
+                             double *result);
+
 /* -------------------------------------------------------- whole tuning run (Alg. 1) */
 typedef struct {
     const void *a, *b;         /* DEVICE inputs                                                  */

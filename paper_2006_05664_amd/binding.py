@@ -134,6 +134,7 @@ _SIGNATURES = {
     "opevo_mfma_ceiling": [C.c_int, C.c_int, _vp, _f64p],
     "opevo_compare_f32": [_vp, _vp, C.c_int64, _vp, _f64p, _f64p],
     "opevo_compare_rows_f32": [_vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _f64p, _f64p],
+    "opevo_compare_f32_static": [_vp, _vp, C.c_int64, _vp, _vp],
     "opevo_tune": [_vp, C.c_int, C.POINTER(opevo_tune_args), _i32p, C.POINTER(opevo_tune_result)],
 }
 for _name, _argtypes in _SIGNATURES.items():
@@ -536,6 +537,11 @@ def opevo_compare_f32(c: int, ref: int, n: int, stream: int = 0) -> Tuple[float,
     mx, fro = C.c_double(), C.c_double()
     _check(lib.opevo_compare_f32(c, ref, n, stream, C.byref(mx), C.byref(fro)))
     return mx.value, fro.value
+
+
+def opevo_compare_f32_static(c: int, ref: int, n: int, stream: int, result: int) -> None:
+    """`result` is a DEVICE pointer to two doubles; nothing is copied back and nothing synchronises."""
+    _check(lib.opevo_compare_f32_static(c, ref, n, stream, result))
 
 
 def opevo_compare_rows_f32(c: int, ref_rows: int, row_index: int, n_rows: int, row_len: int,

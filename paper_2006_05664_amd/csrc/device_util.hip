@@ -12,11 +12,18 @@
 
 #include "kernel.hpp"
 
+// Partials of opevo_compare_f32_static: device memory that exists from the moment the code object
+// is loaded, one copy per GPU, so that entry point never allocates.  In host code this name is
+// only a handle for hipGetSymbolAddress; the address it yields (static_scratch() below) is what
+// kernels and copies are given.
+static __device__ __align__(256) double scratch[3 * 1024];   // 3 doubles per workgroup of compare_partial (kBlocks)
+
 namespace {
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBlocks = 1024;
+static_assert(sizeof(scratch) == sizeof(double) * 3 * kBlocks, "scratch holds one triple per workgroup");
 constexpr int kThreads = 256;
 
 // rows == NULL: c and ref are both n elements.  rows != NULL: ref holds n = n_rows * row_len
@@ -52,6 +59,21 @@ void compare_partial(const float *__restrict__ c, const float *__restrict__ ref,
     }
 }
 
+// Finishes a comparison on the device: folds the per-workgroup partials in workgroup order (the
+// order the host-side fold of compare_f32 uses, so both give the same bits) and writes
+// result[0] = max_scaled, result[1] = rel_fro.
+__global__ void compare_finish(const double *__restrict__ part, int blocks, double *__restrict__ result)
+{
+    double mx = 0.0, se = 0.0, sr = 0.0;
+    for (int b = 0; b < blocks; ++b) {
+        mx = fmax(mx, part[b * 3 + 0]);
+        se += part[b * 3 + 1];
+        sr += part[b * 3 + 2];
+    }
+    result[0] = mx;
+    result[1] = sr > 0.0 ? sqrt(se / sr) : (se > 0.0 ? INFINITY : 0.0);
+}
+
 // Deadline control block of the scalar template: {start tick, allowed ticks, expired flag}.
 __global__ void stamp_deadline(unsigned long long *ctl, unsigned long long ticks)
 {
@@ -74,6 +96,7 @@ __global__ void zero_tail(float *p, int n)
 
 std::mutex g_ws_mutex;
 double *g_ws[64] = {nullptr};   // one workspace per device, kept until the process ends
+double *g_static_ws[64] = {nullptr};   // device address of `scratch` on each device
 unsigned long long *g_ctl[64] = {nullptr};
 double g_ticks_per_ms[64] = {0.0};
 
@@ -117,6 +140,41 @@ int compare_f32(const float *c, const float *ref, int64_t n, const int *rows, in
     if (max_scaled) *max_scaled = mx;
     if (rel_fro) *rel_fro = sr > 0.0 ? std::sqrt(se / sr) : (se > 0.0 ? INFINITY : 0.0);
     return OPEVO_OK;
+}
+
+// Device address of this device's copy of `scratch` (looked up once per device, with that device current).
+static int static_scratch(double **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return fail(OPEVO_E_HIP, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (!g_static_ws[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(compare scratch)");
+        g_static_ws[dev] = static_cast<double *>(p);
+    }
+    *out = g_static_ws[dev];
+    return OPEVO_OK;
+}
+
+int compare_f32_static(const float *c, const float *ref, int64_t n, hipStream_t stream, double *result_dev)
+{
+    double *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    int blocks = int(std::min<int64_t>(kBlocks, (n + kThreads - 1) / kThreads));
+    if (blocks < 1) blocks = 1;
+    // every workgroup overwrites its own three partials and the fold reads only those `blocks`
+    // triples, so nothing left in the array by an earlier call is ever read: no clearing needed
+    hipLaunchKernelGGL(compare_partial, dim3(blocks), dim3(kThreads), 0, stream, c, ref, (long)n,
+                       (const int *)nullptr, 1L, ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "compare_partial launch");
+    hipLaunchKernelGGL(compare_finish, dim3(1), dim3(1), 0, stream, (const double *)ws, blocks, result_dev);
+    e = hipGetLastError();
+    return e == hipSuccess ? OPEVO_OK : hip_fail(e, "compare_finish launch");
 }
 
 int deadline_ctl(unsigned long long **ctl)
@@ -190,4 +248,13 @@ extern "C" int opevo_compare_rows_f32(const float *c, const float *ref_rows, con
         return opevo::fail(OPEVO_E_ARG, "compare_rows_f32: bad arguments");
     return opevo::compare_f32(c, ref_rows, n_rows * row_len, row_index, row_len,
                               static_cast<hipStream_t>(stream), max_scaled, rel_fro);
+}
+
+extern "C" int opevo_compare_f32_static(const float *c, const float *ref, int64_t n, void *stream, double *result)
+{
+    if (!c || !ref || !result || n < 1) return opevo::fail(OPEVO_E_ARG, "compare_f32_static: bad arguments");
+    if (n > OPEVO_COMPARE_STATIC_MAX_N)
+        return opevo::fail(OPEVO_E_ARG, "compare_f32_static: n = %lld exceeds the limit of %lld elements",
+                           (long long)n, (long long)OPEVO_COMPARE_STATIC_MAX_N);
+    return opevo::compare_f32_static(c, ref, n, static_cast<hipStream_t>(stream), result);
 }
