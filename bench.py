@@ -64,6 +64,8 @@ def main() -> int:
                          "number of workgroups that share an output tile (partial sums added atomically)")
     ap.add_argument("--split-reduction", action="store_true",
                     help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
+    ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T"],
+                    help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4C for Conv2d, else TILE4)")
     ap.add_argument("--extended", action="store_true",
                     help="tune in the extended space (launch order as a permutation, group width as a discrete parameter)")
     ap.add_argument("--oracle-rows", type=int, default=32,
@@ -110,6 +112,12 @@ def main() -> int:
             print("bench.py: --split-reduction is a Conv2d space", file=sys.stderr)
             return 2
         variant = P.OPEVO_TILE4P
+    names = {"TILE2": P.OPEVO_TILE2, "TILE4": P.OPEVO_TILE4, "TILE4X": P.OPEVO_TILE4X, "TILE4P": P.OPEVO_TILE4P,
+             "TILE4K": P.OPEVO_TILE4K, "TILE4C": P.OPEVO_TILE4C, "TILE4T": P.OPEVO_TILE4T}
+    if args.space:
+        variant = names[args.space]
+    elif w["kind"] == "conv2d" and variant == P.OPEVO_TILE4:
+        variant = P.OPEVO_TILE4C    # the conv space with the reduction split and the channels-last choice
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
     flops = P.opevo_op_flops(op)
     a_host, b_host = synth.workload_inputs(args.workload)
@@ -257,7 +265,7 @@ def main() -> int:
                    "ms_per_trial": round(wall / max(1, res["n_trials"]) * 1e3, 2),
                    "compile_pool": {1: "8 worker executables (hipRTC of /opt/rocm)", 0: "8 forked workers (hipRTC of the process)",
                                     -1: "none: in-process hipRTC"}.get(pool_kind, str(pool_kind)),
-                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {P.OPEVO_TILE2: "TILE2", P.OPEVO_TILE4: "TILE4", P.OPEVO_TILE4X: "TILE4X", P.OPEVO_TILE4P: "TILE4P", P.OPEVO_TILE4K: "TILE4K"}[variant],
+                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {v: k for k, v in names.items()}[variant],
                    "best_cfg": [int(x) for x in res["best_cfg"]], "frac_of_peak": round(best / PEAK_TFLOPS[dtype], 4),
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),

@@ -212,8 +212,32 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         launch of such a member, and the time of that clear counts as part of the trial.  The sum is the
  *         same up to the rounding of an fp32 addition order that varies from run to run.  For
  *         operators whose output has fewer tiles than the chip has compute units (MM3 of App. B.1:
- *         512 x 1024 from K = 4096) this is what fills the machine. */
-typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4 } opevo_variant;
+ *         512 x 1024 from K = 4096) this is what fills the machine.
+ *  TILE4C: Conv2d only: TILE4 with the reduction axis in three factors (as TILE4K gives MatMul) and a
+ *         second binary choice, the layout the kernel reads its operands in:
+ *         Conv2d  B(2) Cout(4) H(4) W(4) R(3) unroll{0,1} layout{0,1},  R = (partitions, steps, LDS tile)
+ *         partitions = workgroups along grid z that share an output tile, each reducing its own
+ *         contiguous range of R and adding its partial sums into the output with fp32 atomic adds (the
+ *         output is cleared by a fill kernel before every launch of such a member, inside the timed
+ *         launch): the 256 x 6272 x 2304 GEMM view of the 14 x 14 convolution has too few output
+ *         tiles for 256 compute units otherwise.
+ *         layout = 0: operands as the caller stores them (NCHW image gathered value by value, OIHW
+ *         kernel tensor), R walked as (ci, r, s).  layout = 1: channels last.  Every launch is preceded,
+ *         on the same stream and inside the timed launch, by one pre-pass kernel that rewrites the
+ *         image as [B][H][W][Cin] and the kernel tensor as [Cout][Hk][Wk][Cin] into a workspace the
+ *         kernel object owns (allocated when its module is loaded, freed by opevo_kernel_destroy);
+ *         R is then walked as (r, s, ci), 8 consecutive reduction values of a pixel are 16
+ *         contiguous bytes, and both operands travel in 16-byte pieces like MatMul's first operand.
+ *         Same sum in another order.  Needs Cin and the LDS tile to be multiples of 8 and an MFMA
+ *         member; elsewhere layout = 1 runs the layout = 0 kernel.
+ *  TILE4T: MatMul only: TILE4 plus a binary choice of the second operand's layout,
+ *         MatMul  M(4) N(4) K(2) unroll{0,1} bpack{0,1}
+ *         bpack = 1: every launch is preceded, on the same stream and inside the timed launch, by a
+ *         pre-pass kernel that transposes B to [N][K] into a workspace the kernel object owns; both
+ *         operands are then K-contiguous and read from LDS with plain 16-byte fragment reads.  Only
+ *         members of the direct-to-LDS template have such a kernel; elsewhere bpack = 1 runs the
+ *         bpack = 0 kernel. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4, OPEVO_TILE4C = 5, OPEVO_TILE4T = 6 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]

@@ -94,6 +94,116 @@ __global__ void zero_tail(float *p, int n)
     if ((int)threadIdx.x < n) p[threadIdx.x] = 0.f;
 }
 
+// Batched transposition of 16-bit matrices, out[b][c][r] = in[b][r][c], for two problems in one
+// launch (workgroups below blocks0 serve the first): the rewrite of an NCHW image and an OIHW kernel
+// tensor to channels-last, or of a MatMul's second operand to [N][K].  A workgroup moves one tile of
+// tr rows x tc columns through LDS; every thread issues all its loads before it uses the first, and
+// no index needs a division by a run-time number.  Two tile shapes, chosen by the host:
+//   narrow (tc == cols <= 64, e.g. the 9 columns of a 3 x 3 kernel; tr * tc <= 4096): the tile is one
+//     contiguous run of the input and is copied to LDS as it is.
+//   wide (tc = 64 columns of a longer row, tr = 64): reads walk c with the lane, writes walk r.
+// Where rows and cols are multiples of 4 (vec4) both directions move four elements (8 bytes) per
+// lane: a wave instruction costs the same for 2 bytes per lane as for 8.
+struct TransposeJob { const unsigned short *in; unsigned short *out; int batches, rows, cols, tr, tc, tiles_r, tiles_c, narrow, vec4; };
+typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
+constexpr int kTilePitch = 68;     // wide tiles: 64 columns + 4, rows stay 8-byte aligned
+__global__ __launch_bounds__(256) void transpose_tiles_16(TransposeJob j0, TransposeJob j1, int blocks0)
+{
+    __shared__ __attribute__((aligned(8))) unsigned short tile[64 * kTilePitch];   // >= 4096 for the narrow tiles
+    int blk = blockIdx.x;
+    const bool first = blk < blocks0;
+    if (!first) blk -= blocks0;
+    const unsigned short *jin = first ? j0.in : j1.in;
+    unsigned short *jout = first ? j0.out : j1.out;
+    const int rows = first ? j0.rows : j1.rows, cols = first ? j0.cols : j1.cols, tr = first ? j0.tr : j1.tr,
+              tc = first ? j0.tc : j1.tc, tiles_r = first ? j0.tiles_r : j1.tiles_r, tiles_c = first ? j0.tiles_c : j1.tiles_c,
+              narrow = first ? j0.narrow : j1.narrow, vec4 = first ? j0.vec4 : j1.vec4;
+    const int tcb = blk % tiles_c, trb = (blk / tiles_c) % tiles_r, b = blk / (tiles_c * tiles_r);
+    const int r0 = trb * tr, c0 = tcb * tc;
+    const int nr = min(tr, rows - r0), nc = min(tc, cols - c0);
+    const unsigned short *in = jin + ((long)b * rows + r0) * cols + c0;
+    unsigned short *out = jout + ((long)b * cols + c0) * rows + r0;
+    const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
+    if (narrow) {
+        // contiguous tile of nr * nc <= 4096 elements, kept in LDS with pitch nc
+        if (vec4) {
+            u16x4_t v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = (tid + k * 256) * 4;
+                v[k] = i < nr * nc ? *(const u16x4_t *)(in + i) : (u16x4_t){0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = (tid + k * 256) * 4;
+                if (i < nr * nc) *(u16x4_t *)(tile + i) = v[k];
+            }
+            __syncthreads();
+            for (int c = ty; c < nc; c += 4)
+                for (int r = tx * 4; r < nr; r += 256) {
+                    u16x4_t o;
+                    o.x = tile[r * nc + c]; o.y = tile[(r + 1) * nc + c]; o.z = tile[(r + 2) * nc + c]; o.w = tile[(r + 3) * nc + c];
+                    *(u16x4_t *)(out + (long)c * rows + r) = o;
+                }
+        } else {
+            unsigned short v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int i = tid + k * 256;
+                v[k] = i < nr * nc ? in[i] : (unsigned short)0;
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int i = tid + k * 256;
+                if (i < nr * nc) tile[i] = v[k];
+            }
+            __syncthreads();
+            for (int c = ty; c < nc; c += 4)
+                for (int r = tx; r < nr; r += 64) out[(long)c * rows + r] = tile[r * nc + c];
+        }
+    } else if (vec4) {
+        // 64 x 64 tile in 4 x 4 blocks: 16 column quads x 16 row groups per pass
+        const int cq = tid & 15, rq = tid >> 4;
+        u16x4_t v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int rr = rq + 16 * k;
+            v[k] = (rr < nr && cq * 4 < nc) ? *(const u16x4_t *)(in + (long)rr * cols + cq * 4) : (u16x4_t){0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) *(u16x4_t *)(tile + (rq + 16 * k) * kTilePitch + cq * 4) = v[k];
+        __syncthreads();
+        // write: 16 row quads x 16 columns per pass; a thread gathers 4 rows of one column
+        const int rqw = tid & 15, cg = tid >> 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int cc = cg + 16 * k;
+            if (cc < nc && rqw * 4 < nr) {
+                u16x4_t o;
+                o.x = tile[(rqw * 4 + 0) * kTilePitch + cc]; o.y = tile[(rqw * 4 + 1) * kTilePitch + cc];
+                o.z = tile[(rqw * 4 + 2) * kTilePitch + cc]; o.w = tile[(rqw * 4 + 3) * kTilePitch + cc];
+                *(u16x4_t *)(out + (long)cc * rows + rqw * 4) = o;
+            }
+        }
+    } else {
+        // 64 x 64 tile, element by element
+        unsigned short v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int rr = ty + 4 * k;
+            v[k] = (rr < nr && tx < nc) ? in[(long)rr * cols + tx] : (unsigned short)0;
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) tile[(ty + 4 * k) * kTilePitch + tx] = v[k];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int cc = ty + 4 * k;
+            if (cc < nc && tx < nr) out[(long)cc * rows + tx] = tile[tx * kTilePitch + cc];
+        }
+    }
+}
+
 std::mutex g_ws_mutex;
 double *g_ws[64] = {nullptr};   // one workspace per device, kept until the process ends
 double *g_static_ws[64] = {nullptr};   // device address of `scratch` on each device
@@ -209,6 +319,42 @@ int zero_f32(float *p, int64_t n, hipStream_t stream)
     if (n % 4) hipLaunchKernelGGL(zero_tail, dim3(1), dim3(64), 0, stream, p + n4 * 4, int(n % 4));
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? OPEVO_OK : hip_fail(e, "zero_f32 launch");
+}
+
+int transpose_16(const void *in0, void *out0, int64_t batches0, int64_t rows0, int64_t cols0,
+                 const void *in1, void *out1, int64_t batches1, int64_t rows1, int64_t cols1, hipStream_t stream)
+{
+    auto job = [](const void *in, void *out, int64_t batches, int64_t rows, int64_t cols) {
+        TransposeJob j;
+        j.in = static_cast<const unsigned short *>(in); j.out = static_cast<unsigned short *>(out);
+        j.batches = int(batches); j.rows = int(rows); j.cols = int(cols);
+        // narrow tile: whole rows where they are short, as many as fit 4096 elements (a multiple of 4
+        // of them for the 8-byte form); wide tile: 64 x 64
+        const bool aligned = reinterpret_cast<uintptr_t>(in) % 8 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
+        j.narrow = cols <= 64;
+        j.vec4 = aligned && rows % 4 == 0 && cols % 4 == 0;
+        if (j.narrow) {
+            j.tc = int(std::max<int64_t>(cols, 1));
+            // rows * cols of a batch is a multiple of 4 whenever rows is: the contiguous copy may then go 8 bytes at a time
+            j.vec4 = aligned && rows % 4 == 0;
+            int64_t tr = std::max<int64_t>(1, std::min<int64_t>(rows, 4096 / j.tc));
+            if (j.vec4 && tr >= 4) tr = tr / 4 * 4;
+            j.tr = int(tr);
+            if (j.vec4 && (j.tr % 4 != 0)) j.vec4 = 0;
+        } else { j.tc = 64; j.tr = 64; }
+        j.tiles_r = int((rows + j.tr - 1) / j.tr); j.tiles_c = int((cols + j.tc - 1) / j.tc);
+        return j;
+    };
+    if (!in1) batches1 = 0;
+    const TransposeJob j0 = job(in0, out0, batches0, rows0, cols0), j1 = job(in1, out1, batches1, rows1, cols1);
+    const int64_t blocks0 = int64_t(j0.batches) * j0.tiles_r * j0.tiles_c, blocks1 = int64_t(j1.batches) * j1.tiles_r * j1.tiles_c;
+    if (blocks0 + blocks1 > INT32_MAX || batches0 * rows0 * cols0 >= (int64_t(1) << 40) || rows0 >= (int64_t(1) << 31) ||
+        cols0 >= (int64_t(1) << 31) || rows1 >= (int64_t(1) << 31) || cols1 >= (int64_t(1) << 31))
+        return fail(OPEVO_E_ARG, "operand re-layout pre-pass: tensors too large");
+    if (blocks0 + blocks1 == 0) return OPEVO_OK;
+    hipLaunchKernelGGL(transpose_tiles_16, dim3(unsigned(blocks0 + blocks1)), dim3(256), 0, stream, j0, j1, int(blocks0));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? OPEVO_OK : hip_fail(e, "operand re-layout pre-pass launch");
 }
 
 int deadline_arm(unsigned long long *ctl, double timeout_ms, hipStream_t stream)

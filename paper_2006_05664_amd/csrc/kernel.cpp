@@ -54,6 +54,13 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     k->defines = d.defines;
     k->name = d.kernel_name;
     k->zero_bytes = size_t(d.zero_bytes);
+    k->prepass = d.prepass;
+    if (d.prepass == 1) {          // image [B][Cin][H*W] -> [B][H*W][Cin]; kernel tensor [Cout][Cin][Hk*Wk] -> [Cout][Hk*Wk][Cin]
+        k->pp_batches0 = op.nimg; k->pp_rows0 = op.cin; k->pp_cols0 = op.hin * op.win;
+        k->pp_batches1 = op.M; k->pp_rows1 = op.cin; k->pp_cols1 = op.hk * op.wk;
+    } else if (d.prepass == 2) {   // B [K][N] -> [N][K]
+        k->pp_batches0 = op.batch; k->pp_rows0 = op.K; k->pp_cols0 = op.N;
+    }
     if (compile_ms)
         *compile_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = k;
@@ -81,6 +88,13 @@ int load_kernel(opevo_kernel *k, bool refuse_spills)
             (void)hipGetLastError();
         }
     }
+    if (k->prepass && !k->workspace) {
+        const size_t bytes1 = (size_t(k->pp_batches1 * k->pp_rows1 * k->pp_cols1) * 2 + 255) / 256 * 256;
+        const size_t bytes0 = size_t(k->pp_batches0 * k->pp_rows0 * k->pp_cols0) * 2;
+        HIP_TRY(hipMalloc(&k->workspace, bytes1 + 256 + bytes0));
+        hipError_t e = hipMemset(static_cast<char *>(k->workspace) + bytes1, 0, 256);   // the block of zeros padded taps are read from
+        if (e != hipSuccess) return hip_fail(e, "hipMemset(workspace zeros)");
+    }
     // A member whose kernel needs private scratch memory (register spills) is not run, on any
     // template.  The direct-to-LDS template counts its own outstanding loads (s_waitcnt vmcnt(n)):
     // spill stores would sit on the same counter and may complete out of order with loads, so a
@@ -101,6 +115,16 @@ int launch_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStr
     // members whose workgroups add partial sums into the output start from a cleared output
     if (k->zero_bytes)
         if (int rc = zero_f32(static_cast<float *>(c), int64_t(k->zero_bytes / 4), stream)) return rc;
+    if (k->prepass) {
+        const size_t bytes1 = (size_t(k->pp_batches1 * k->pp_rows1 * k->pp_cols1) * 2 + 255) / 256 * 256;
+        char *ws = static_cast<char *>(k->workspace);
+        void *first = ws, *zeros = ws + bytes1, *second = ws + bytes1 + 256;
+        if (int rc = transpose_16(b, second, k->pp_batches0, k->pp_rows0, k->pp_cols0,
+                                  k->prepass == 1 ? a : nullptr, first, k->pp_batches1, k->pp_rows1, k->pp_cols1, stream))
+            return rc;
+        if (k->prepass == 1) { a = first; b = zeros; }   // Conv2d: a = kernel tensor, b = zeros followed by the image
+        else b = second;
+    }
     void *args[] = {(void *)&a, (void *)&b, (void *)&c, (void *)&ctl};
     // the direct-to-LDS template declares its stages statically; the others take dynamic LDS
     const unsigned dyn_lds = k->plan.path == 3 ? 0u : unsigned(k->plan.lds_bytes);
@@ -215,6 +239,7 @@ int opevo_kernel_destroy(opevo_kernel *k)
 {
     if (!k) return OPEVO_OK;
     if (k->module) (void)hipModuleUnload(k->module);
+    if (k->workspace) (void)hipFree(k->workspace);
     delete k;
     return OPEVO_OK;
 }

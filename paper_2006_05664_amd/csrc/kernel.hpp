@@ -18,6 +18,15 @@ struct opevo_kernel {
     hipModule_t module = nullptr;  // loaded on first launch
     hipFunction_t fn = nullptr;
     int scratch_bytes = 0;         // private scratch per lane the compiler used (known once loaded)
+    // Members whose kernel reads re-laid-out operands.  Every launch first runs one pre-pass kernel on
+    // the same stream that writes them into `workspace` (allocated when the module is loaded).
+    //   prepass 1 (Conv2d, channels last): [kernel tensor as [Cout][Hk*Wk][Cin]] [256 bytes of zeros]
+    //             [image as [B][H*W][Cin]]; the kernel's second pointer is the block of zeros.
+    //   prepass 2 (MatMul): the second operand transposed to [N][K].
+    int prepass = 0;
+    int64_t pp_batches0 = 0, pp_rows0 = 0, pp_cols0 = 0;   // second operand: out[b][c][r] = in[b][r][c]
+    int64_t pp_batches1 = 0, pp_rows1 = 0, pp_cols1 = 0;   // first operand (Conv2d only)
+    void *workspace = nullptr;
 };
 
 namespace opevo {
@@ -42,6 +51,10 @@ int deadline_arm(unsigned long long *ctl, double timeout_ms, hipStream_t stream)
 int deadline_expired(unsigned long long *ctl, hipStream_t stream, bool *expired);
 // Clears n floats at p (16-byte aligned) with a small kernel on `stream`.
 int zero_f32(float *p, int64_t n, hipStream_t stream);
+// out[b][c][r] = in[b][r][c] for up to two batched matrices of 16-bit elements in one launch on
+// `stream` (the second is skipped if in1 is NULL).
+int transpose_16(const void *in0, void *out0, int64_t batches0, int64_t rows0, int64_t cols0,
+                 const void *in1, void *out1, int64_t batches1, int64_t rows1, int64_t cols1, hipStream_t stream);
 int hip_fail(hipError_t e, const char *what);
 
 }  // namespace opevo

@@ -2,7 +2,9 @@
 #include "op.hpp"
 
 #include <cstring>
+#include <algorithm>
 #include <new>
+#include <numeric>
 #include <sstream>
 
 using namespace opevo;
@@ -87,6 +89,21 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
         descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 3), flag("unroll")};
         return OPEVO_OK;
     }
+    if (variant == OPEVO_TILE4T) {
+        // MatMul with the layout of the second operand as a second binary choice: as stored ([K][N]) or
+        // transposed to [N][K] by a pre-pass before every launch
+        if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the space with a packed second operand exists for MatMul only");
+        descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 2), flag("unroll"), flag("bpack")};
+        return OPEVO_OK;
+    }
+    if (variant == OPEVO_TILE4C) {
+        // Conv2d with the fused reduction axis in three factors (partitions along grid z, steps, LDS
+        // tile) and the operand layout as a second binary choice
+        if (op.kind != OPEVO_CONV2D) return fail(OPEVO_E_ARG, "the split-reduction / channels-last space exists for Conv2d only");
+        descs = {factor("B", op.nimg, 2), factor("Cout", op.M, 4), factor("H", op.hout, 4), factor("W", op.wout, 4),
+                 factor("R", op.K, 3), flag("unroll"), flag("layout")};
+        return OPEVO_OK;
+    }
     if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
     switch (op.kind) {
     case OPEVO_MATMUL:
@@ -163,7 +180,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t BM = 1, BN = 1, BK = 1, ksteps = 1, WM = 1, WN = 1, TM = 1, TN = 1, FM = 1, FN = 1;
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
-    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P || variant == OPEVO_TILE4K);
+    bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P || variant == OPEVO_TILE4K ||
+                       variant == OPEVO_TILE4C || variant == OPEVO_TILE4T);
+    int bpack = 0;                         // MatMul, TILE4T: 1 = second operand transposed to [N][K] by a pre-pass
+    int layout = 0;                        // Conv2d, TILE4C: 1 = channels-last operands (pre-pass)
     int64_t ksplit = 1;
     int64_t box[6] = {1, 1, 1, 1, 1, 1};   // C_in, H_k, W_k as (boxes, box extent) pairs
     bool tap_box = false;
@@ -180,8 +200,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         n1 = c[4]; WN = c[5]; TN = int64_t(c[6]) * c[7]; FN = c[7];
         if (variant == OPEVO_TILE4K) { ksplit = c[8]; b1 = ksplit; ksteps = c[9]; BK = c[10]; flagv = c[11]; }
         else { ksteps = c[8]; BK = c[9]; flagv = c[10]; }
+        if (variant == OPEVO_TILE4T) bpack = c[11];
         BM = WM * TM; BN = WN * TN;
-        tile4_width = int(c - cfg) + (variant == OPEVO_TILE4K ? 12 : 11);
+        tile4_width = int(c - cfg) + (variant == OPEVO_TILE4K || variant == OPEVO_TILE4T ? 12 : 11);
     } else {   // conv: B(2) Cout(4) H(4) W(4) R(2) flag
         const int32_t *c = cfg;
         const int64_t nb1 = c[0]; nb2 = c[1];
@@ -204,6 +225,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             const bool contiguous = (box[5] == op.wk || (box[3] == 1 && box[1] == 1)) && (box[3] == op.hk || box[1] == 1);
             tap_box = !contiguous;
             tile4_width = 22;
+        } else if (variant == OPEVO_TILE4C) {
+            ksplit = c[14]; b1 = ksplit; ksteps = c[15]; BK = c[16]; flagv = c[17]; layout = c[18];
+            tile4_width = 19;
         } else {
             ksteps = c[14]; BK = c[15]; flagv = c[16];
             tile4_width = 17;
@@ -225,6 +249,38 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t BKP = BK;   // width of a K slab as the MFMA template stages and multiplies it
     int64_t TMacc = TM, TNacc = TN;   // wave tile in whole atoms (accumulator registers)
     bool ragged = false;
+    // Channels-last operands (TILE4C, layout = 1) need 8-value pieces that never straddle a tap (Cin and
+    // the LDS tile multiples of 8) and byte offsets into the image that fit 32 bits; they exist on the
+    // MFMA templates only.  Elsewhere the choice is inert and the member runs as with layout = 0.
+    const bool nhwc_ok = layout == 1 && op.kind == OPEVO_CONV2D && op.dtype != OPEVO_F32 && op.cin % 8 == 0 &&
+                         BK % 8 == 0 && op.b_elems() * 2 + 256 < (int64_t(1) << 32) &&
+                         op.hin + 2 * op.pad + op.hk < 32768 && op.win + 2 * op.pad + op.wk < 32768;   // coordinates in 15 bits
+    int nstage_dlds = 0;
+    int64_t bnr = BN;   // rows of the second operand's stage part on the direct-to-LDS template when it is K-contiguous
+    int64_t anr = BM;   // rows of the first operand's stage part there
+    // Direct global->LDS streaming (path 3) of a pipelined member whose slabs split into whole 1 KiB wave
+    // loads: `rows_b` rows of BK K-contiguous elements for the second operand (0: it is stored [K][N]).
+    auto dlds_stages = [&](int64_t rows_a, int64_t rows_b, bool a_km_rows) -> int {
+        const int64_t nw = WM * WN;
+        if (64 * nw > kMaxThreads || !(BK == 32 || BK == 64 || BK == 128)) return 0;
+        const int64_t a_bytes = rows_a * BK * 2, b_bytes = (rows_b ? rows_b : BN) * BK * 2;
+        if (a_bytes % (1024 * nw) != 0 || b_bytes % (1024 * nw) != 0) return 0;
+        if (!rows_b && !(BN % 128 == 0 || BN == 64 || BN == 32)) return 0;
+        if (a_km_rows && !(BM % 128 == 0 || BM == 64 || BM == 32)) return 0;   // A rows are M-contiguous then
+        const int64_t per = (a_bytes + b_bytes) / (1024 * nw);
+        int st_found = 0;
+        for (int st = 4; st >= 2; --st)
+            if (st * (a_bytes + b_bytes) <= kMaxLds && (st - 2) * per <= 63) { st_found = st; break; }
+        if (!st_found) return 0;
+        // The template keeps accumulators and fragments in register arrays and relies on its K
+        // loop body (one pass over the ring) unrolling completely.  Instructions in that body:
+        // per stage and MFMA step the MFMAs and fragment reads, per stage the loads.  Bodies
+        // past this size were seen not to unroll (code objects of 0.5-1.5 MB instead of 20 KB);
+        // such members use the register-staged template instead.
+        const int64_t mi = TM / 32, ni = (TN + 31) / 32, kk = BK / 16;
+        const int64_t body = st_found * (kk * (mi * ni + (op.trans_a ? 2 : 1) * mi + (rows_b ? 1 : 2) * ni) + per);
+        return body > kMaxDldsBody ? 0 : st_found;
+    };
     if (four_level && op.dtype != OPEVO_F32) {
         if (op.kind == OPEVO_CONV2D) {
             // The convolution's reduction axis Cin*Hk*Wk rarely has a factor 16 (3*11*11 = 363): a slab
@@ -235,6 +291,23 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             const int64_t TMp = (TM + 15) / 16 * 16, TNp = (TN + 15) / 16 * 16;
             if (TM % 32 == 0 && TN % 32 == 0) { path = 1; BKP = (BK + 15) / 16 * 16; }
             else if (TMp * TNp <= 2 * TM * TN) { path = 2; BKP = (BK + 31) / 32 * 32; ragged = (TMp != TM || TNp != TN); TMacc = TMp; TNacc = TNp; }
+            // channels-last, pipelined, wave tiles of whole 32-row atoms whose pixel side rounds up to 32
+            // without doubling the work: the direct-to-LDS template with a K-contiguous second operand
+            const int64_t TN32 = (TN + 31) / 32 * 32;
+            if (nhwc_ok && flagv == 1 && TM % 32 == 0 && TN32 <= 2 * TN && TM * TN32 / 64 <= kMaxAcc) {
+                const int64_t nw = WM * WN;
+                // rows staged: every pixel of the box and every row a wave's last atom reads, rounded up
+                // until the part splits into whole 1 KiB loads per wave
+                int64_t rows = std::max(BN, (WN - 1) * TN + TN32), rows_a = BM;
+                if (BK == 32 || BK == 64 || BK == 128) {
+                    const int64_t unit = 1024 * nw / std::gcd(int64_t(1024) * nw, BK * 2);
+                    rows = (rows + unit - 1) / unit * unit;
+                    rows_a = (rows_a + unit - 1) / unit * unit;
+                    if (rows * BK * 2 / (1024 * nw) <= 8 && rows_a * BK * 2 / (1024 * nw) <= 8)
+                        nstage_dlds = dlds_stages(rows_a, rows, false);
+                }
+                if (nstage_dlds) { path = 3; bnr = rows; anr = rows_a; BKP = BK; ragged = false; TMacc = TM; TNacc = TN32; }
+            }
         } else {
             const bool align_ok = (op.K % 8 == 0) && (op.N % 8 == 0);
             if (align_ok && TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0) path = 1;
@@ -256,29 +329,15 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     }
     const bool stage_lds = path == 4 || !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
     // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
-    // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.
-    int nstage_dlds = 0;
-    if (path == 1 && flagv == 1 && stage_lds && op.kind != OPEVO_CONV2D && 64 * WM * WN <= kMaxThreads) {
-        const int64_t nw = WM * WN;
-        const bool bk_ok = (BK == 32 || BK == 64 || BK == 128);
-        const bool bn_ok = (BN % 128 == 0 || BN == 64 || BN == 32) &&
-                           (!op.trans_a || BM % 128 == 0 || BM == 64 || BM == 32);   // A rows are M-contiguous then
-        const bool split_ok = (BM * BK * 2) % (1024 * nw) == 0 && (BK * BN * 2) % (1024 * nw) == 0;
-        if (bk_ok && bn_ok && split_ok) {
-            const int64_t per = (BM * BK * 2 + BK * BN * 2) / (1024 * nw);
-            for (int st = 4; st >= 2; --st)
-                if (st * (BM + BN) * BK * 2 <= kMaxLds && (st - 2) * per <= 63) { nstage_dlds = st; break; }
-            // The template keeps accumulators and fragments in register arrays and relies on its K
-            // loop body (one pass over the ring) unrolling completely.  Instructions in that body:
-            // per stage and MFMA step the MFMAs and fragment reads, per stage the loads.  Bodies
-            // past this size were seen not to unroll (code objects of 0.5-1.5 MB instead of 20 KB);
-            // such members use the register-staged template instead.
-            const int64_t mi = TM / 32, ni = TN / 32, kk = BK / 16;
-            const int64_t body = nstage_dlds * (kk * (mi * ni + (op.trans_a ? 2 : 1) * mi + 2 * ni) + per);
-            if (body > kMaxDldsBody) nstage_dlds = 0;
-        }
+    // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.  With
+    // bpack = 1 (TILE4T) the second operand is read from the [N][K] copy a pre-pass makes.
+    const bool b_packed = bpack == 1 && op.kind == OPEVO_MATMUL && !op.trans_a;
+    if (path == 1 && flagv == 1 && stage_lds && op.kind != OPEVO_CONV2D) {
+        nstage_dlds = dlds_stages(BM, b_packed ? BN : 0, op.trans_a);
         if (nstage_dlds) path = 3;
     }
+    const bool b_kmajor = path == 3 && (b_packed || op.kind == OPEVO_CONV2D);
+    const bool nhwc = nhwc_ok && (path == 1 || path == 2 || path == 3);
     // a transposed first operand is staged by the MFMA templates like B (rows of 8 along M), so it
     // needs M % 8 == 0 and LDS staging; other members run on the scalar template
     if (op.trans_a && (path == 1 || path == 2) && (op.M % 8 != 0 || !stage_lds)) path = 0;
@@ -298,7 +357,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         lds = nstage * (a_rows * (BKP + 4) + BKP * (b_cols + 4)) * 4;
     }
     else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
-    else if (path == 3) lds = nstage * (BM + BN) * BK * 2;
+    else if (path == 3) lds = nstage * (anr + (b_kmajor ? bnr : BN)) * BK * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
     p.path = path;
@@ -337,7 +396,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     {
         std::ostringstream nm;
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
-           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : four_level ? "4" : "2");
+           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : variant == OPEVO_TILE4C ? "c" : variant == OPEVO_TILE4T ? "t" : four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
@@ -361,15 +420,19 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         // fields are wide enough (byte offsets into the image tensor in 32 bits, padded image
         // coordinates in 15) and the table stays small (8 bytes per position of the reduction walk)
         const bool table = path != 0 && op.b_elems() < (int64_t(1) << 31) && op.hin + 2 * op.pad < 32768 &&
-                           op.win + 2 * op.pad < 32768 && op.hk < 32768 && op.wk < 32768 && ksteps * BKP <= 8192;
+                           op.win + 2 * op.pad < 32768 && op.hk < 32768 && op.wk < 32768 && ksplit * ksteps * BKP <= 8192 && !nhwc;
         if (path != 0) D << " -DCONV_TABLE=" << (table ? 1 : 0);
+        if (nhwc) D << " -DCONV_NHWC=1";
     }
     if (tap_box)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
           << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
+    if (b_kmajor) D << " -DB_KMAJOR=1 -DBNR=" << bnr;
+    if (path == 3 && anr != BM) D << " -DANR=" << anr;
     if (kunroll) D << " -DKUNROLL=" << kunroll;
     if (ksplit > 1) D << " -DKSPLIT=" << ksplit;
     out.zero_bytes = ksplit > 1 ? op.c_elems() * 4 : 0;
+    out.prepass = nhwc ? 1 : (b_kmajor && op.kind == OPEVO_MATMUL) ? 2 : 0;
     if (linear)
         D << " -DGRID_LINEAR=1 -DGRID_N1=" << n1 << " -DGRID_M1=" << m1 << " -DGRID_B1=" << b1 << " -DORDER0=" << order[0]
           << " -DORDER1=" << order[1] << " -DORDER2=" << order[2] << " -DGROUP=" << group;

@@ -33,6 +33,9 @@ struct Decoded {
     std::string defines;   // space separated -D options
     std::string kernel_name;   // symbol of the instantiated kernel
     int64_t zero_bytes = 0;    // bytes of the output the host clears before every launch (split reduction), else 0
+    // pre-pass before every launch: 0 none; 1 Conv2d: the kernel reads channels-last copies of both operands;
+    // 2 MatMul: the kernel reads a copy of the second operand transposed to [N][K]
+    int prepass = 0;
 };
 
 // OPEVO_OK (plan.status says valid/invalid) or OPEVO_E_ILLEGAL / OPEVO_E_ARG.

@@ -2,8 +2,8 @@
 //
 // Every name in capitals is a compile-time constant supplied per configuration as a -D
 // option by the host (see the plan/define renderer): the kernels contain no run-time
-// shape arguments, so each configuration is its own specialised program (Sec. 1: "compile
-// a device code with a specific configuration and run it on real hardware").
+// shape arguments, so each configuration is its own specialised program, compiled and run
+// on the hardware to be scored (Sec. 1).
 //
 // All three operators are run as one batched GEMM view  C[b][m][n] = sum_k A[b][m][k] B[b][k][n]:
 //   OP 0  MatMul       (App. B.1)  batch = 1
@@ -22,7 +22,7 @@
 #define A_TRANS 0
 #endif
 #ifndef KSPLIT
-#define KSPLIT 1   // MatMul: workgroups along grid z that share one output tile, each reducing its own K range
+#define KSPLIT 1   // MatMul, Conv2d: workgroups along grid z that share one output tile, each reducing its own K range
 #endif
 #define OP_MATMUL 0
 #define OP_BMM 1
@@ -87,6 +87,13 @@ __device__ __forceinline__ void c_out(float *p, float v)
 }
 
 #if OP == OP_CONV
+// Conv2d with the reduction split over grid z: first position of this workgroup's range of the
+// reduction walk (its KSTEPS slabs follow from there)
+#if KSPLIT > 1
+#define CONV_KBASE(bid) ((bid).b * (KSTEPS * BK))
+#else
+#define CONV_KBASE(bid) 0
+#endif
 struct ColBlock { int nb0, y0, x0; };
 __device__ __forceinline__ ColBlock col_block(int bx)
 {

@@ -29,6 +29,12 @@
 //           BKP != BK the kernel tensor is read element by element (its rows are not 16-byte
 //           aligned then) with the same bounds as the image gather, and so it is when the slabs
 //           are boxes of separately split C_in, H_k and W_k (TAP_BOX: not contiguous in memory).
+//           CONV_NHWC: the operands were rewritten channels-last by a pre-pass (image [B][H][W][Cin],
+//           kernel tensor [Cout][Hk][Wk][Cin]) and the reduction is walked as (r, s, ci).  Cin and BK
+//           are multiples of 8, so 8 consecutive positions are 8 consecutive channels of one tap:
+//           16 contiguous bytes of a pixel (or zeros where the tap falls outside the image), and a
+//           row of the kernel tensor is contiguous along the whole walk.  Both operands then travel
+//           in 16-byte pieces, consecutive lanes taking consecutive pieces of one row.
 
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
@@ -90,9 +96,31 @@ constexpr int B_CHUNKS = (BK / KB) * (BN / 8);
 #endif
 constexpr int NB = (B_CHUNKS + NT - 1) / NT;
 
+#ifndef CONV_NHWC
+#define CONV_NHWC 0
+#endif
 #if OP == OP_CONV
 #ifndef CONV_TABLE
 #define CONV_TABLE 0
+#endif
+#if CONV_NHWC
+// A column of the implicit GEMM (an output pixel) as the channels-last gather needs it: the input
+// pixel under tap (0, 0), which lies outside the image for padded borders (y0, x0 may be negative;
+// base2, the byte offset of its channel 0 from the kernel's second pointer, is kept modulo 2^32).
+// That pointer is a block of 256 zero bytes, which the [B][H][W][Cin] image follows.
+struct NhwcCol { u32 base2; int y0, x0; };
+__device__ __forceinline__ NhwcCol nhwc_col(const ColBlock &cb, int c)
+{
+    NhwcCol col;
+    const int nb = cb.nb0 + c / (BH * BW);
+    col.y0 = (cb.y0 + (c / BW) % BH) * STRIDE - PAD_CONV;
+    col.x0 = (cb.x0 + c % BW) * STRIDE - PAD_CONV;
+    col.base2 = 256u + 2u * (u32)(((nb * HIN + col.y0) * WIN + col.x0) * CIN);
+    return col;
+}
+constexpr int NB_NHWC = (BN * (BKP / 8) + NT - 1) / NT;
+constexpr bool NHWC_COLS_IN_REGS = NB_NHWC <= 8;
+struct NhwcCols { NhwcCol c[NHWC_COLS_IN_REGS ? NB_NHWC : 1]; };
 #endif
 #if CONV_TABLE
 // Image gather through a table.  Taken element by element, the gather spends some thirty integer
@@ -109,12 +137,12 @@ constexpr int NB = (B_CHUNKS + NT - 1) / NT;
 // a compare (a coordinate below zero wraps to a large field), one add for the address, the load
 // and two selects.  The host only selects this path if the fields are wide enough.
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-constexpr int NTAB = KSTEPS * BKP;
+constexpr int NTAB = KSPLIT * KSTEPS * BKP;
 struct ConvTable { u32 e[2 * NTAB]; };   // 8 positions = {off2[0..8), rs[0..8)}: 64 bytes
 constexpr ConvTable make_conv_table()
 {
     ConvTable t{};
-    for (int kt = 0; kt < KSTEPS; ++kt)
+    for (int kt = 0; kt < KSPLIT * KSTEPS; ++kt)
         for (int j = 0; j < BKP; ++j) {
             u32 off2 = 0, rs = 0;
             if (j < BK) {
@@ -228,6 +256,8 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
                                           , const ColBlock &cb
 #if CONV_TABLE
                                           , const ConvCols &cols
+#elif CONV_NHWC
+                                          , const NhwcCols &ncols
 #endif
 #else
                                           , int n0
@@ -244,6 +274,11 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
             const int row = q / (BKP / 8), kc = q % (BKP / 8);
             if (BKP == BK && !GATHER_A) {
                 s.a[i] = *(const u32x4 *)(Ab + (long)(m0 + row) * K + k0 + kc * 8);
+            } else if (CONV_NHWC) {   // BK is a multiple of 8: a piece is whole or past the slab's end
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                const bool in = kc * 8 < BK;
+                const u32x4 v = *(const u32x4 *)(Ab + (long)(m0 + row) * K + (in ? k0 + kc * 8 : 0));
+                s.a[i] = in ? v : zero;
             } else {   // padded slab: taps past BK are zeros, rows start at any 2-byte offset;
                        // boxed reduction walk: the taps of a slab are not contiguous
                 u32 h[8];
@@ -260,6 +295,24 @@ __device__ __forceinline__ void load_slab(Slab &s, const u16 *__restrict__ Ab, c
 #endif
 #if OP != OP_CONV
     load_kmajor<KB, B_CHUNKS, NB>(s.b, Bb + (long)k0 * N + n0, N, tid);
+#elif CONV_NHWC
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int q = tid + i * NT;
+        if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
+            const int c = q / (BKP / 8), kc = q % (BKP / 8);
+            const NhwcCol col = NHWC_COLS_IN_REGS ? ncols.c[i] : nhwc_col(cb, c);
+            const int kp = k0 + kc * 8;                        // position in the (r, s, ci) walk
+            const int tap = kp / CIN, ci0 = kp % CIN, r = tap / WK, sx = tap % WK;
+            const bool ok = (BKP == BK || kc * 8 < BK) && (unsigned)(col.y0 + r) < (unsigned)HIN &&
+                            (unsigned)(col.x0 + sx) < (unsigned)WIN;
+            // unconditional load (from the block of zeros where the tap is outside) and a select
+            const u32 o = ok ? col.base2 + 2u * (u32)((r * WIN + sx) * CIN + ci0) : 0u;
+            const u32x4 v = *(const u32x4 *)((const char *)Bb + (size_t)o);
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            s.b[i] = ok ? v : zero;
+        }
+    }
 #else
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -317,7 +370,11 @@ __device__ __forceinline__ void store_slab(const Slab &s, u16 *As, u16 *Bs, int 
     for (int i = 0; i < NB; ++i) {
         const int q = tid + i * NT;
         if (B_CHUNKS % NT == 0 || q < B_CHUNKS) {
+#if CONV_NHWC
+            const int c = q / (BKP / 8), kc = q % (BKP / 8);
+#else
             const int c = q % BN, kc = q / BN;
+#endif
             *(u32x4 *)(Bs + lds_off(c, kc * 8)) = s.b[i];
         }
     }
@@ -431,9 +488,16 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
             for (int i = 0; i < NCOL; ++i) cols.c[i] = conv_col(cb, (tid + i * NT) % BN);
         }
-#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, cb, cols)
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, CONV_KBASE(bid) + (kt) * BK, tid, cb, cols)
+#elif CONV_NHWC
+        NhwcCols ncols;
+        if (NHWC_COLS_IN_REGS) {
+#pragma unroll
+            for (int i = 0; i < NB_NHWC; ++i) ncols.c[i] = nhwc_col(cb, ((tid + i * NT) / (BKP / 8)) % BN);
+        }
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, CONV_KBASE(bid) + (kt) * BK, tid, cb, ncols)
 #else
-#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, cb)
+#define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, CONV_KBASE(bid) + (kt) * BK, tid, cb)
 #endif
 #else
 #define LOAD_INTO(S, kt) load_slab(S, Ab, Bb, m0, (kt) * BK, tid, n0)
@@ -510,7 +574,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                     const int gm = m0 + wm * TM + i * ATOM + row;
                     const int cn = wn * TN + j * ATOM + lrow;   // column inside the workgroup tile
 #if OP == OP_CONV
-                    C[conv_c_index(cb, gm, cn)] = acc[i][j][r];
+                    c_out(&C[conv_c_index(cb, gm, cn)], acc[i][j][r]);
 #else
                     c_out(&Cb[(long)gm * N + n0 + cn], acc[i][j][r]);
 #endif

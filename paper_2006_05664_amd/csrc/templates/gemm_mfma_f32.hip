@@ -188,7 +188,7 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
     const int m0 = bid.m * BM;
 #if OP == OP_CONV
     const ColBlock cb = col_block(bid.n);
-#define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, cb, (kt) * BK, tid)
+#define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, cb, CONV_KBASE(bid) + (kt) * BK, tid)
 #else
     const int n0 = bid.n * BN;
 #define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, n0, (kt) * BK, tid)
@@ -251,7 +251,7 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
 #if OP == OP_CONV
                     // the overhang of a rounded-up wave tile is not stored
                     if ((TM % 32 == 0 || row < TM) && (TN % 32 == 0 || col < TN))
-                        C[conv_c_index(cb, m0 + wm * TM + row, wn * TN + col)] = acc[i][j][r];
+                        c_out(&C[conv_c_index(cb, m0 + wm * TM + row, wn * TN + col)], acc[i][j][r]);
 #else
                     c_out(&Cb[(long)(m0 + wm * TM + row) * N + n0 + wn * TN + col], acc[i][j][r]);
 #endif

@@ -60,7 +60,11 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
         for (int e = 0; e < E; ++e) acc[e] = 0.f;
 
         for (int kt = 0; kt < KSTEPS; ++kt) {
+#if OP == OP_CONV
+            const int k0 = CONV_KBASE(bid) + kt * BK;
+#else
             const int k0 = kt * BK;
+#endif
             if (tid == 0 && ctl && ctl[1] != 0 && wall_clock64() - ctl[0] > ctl[1]) {
                 expired = 1;
                 ctl[2] = 1;
@@ -102,7 +106,7 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
             const int idx = tid + e * NT;
             if (idx < BM * BN) {
 #if OP == OP_CONV
-                C[conv_c_index(cb, m0 + idx / BN, idx % BN)] = acc[e];
+                c_out(&C[conv_c_index(cb, m0 + idx / BN, idx % BN)], acc[e]);
 #else
                 c_out(&Cb[(long)(m0 + idx / BN) * N + n0 + idx % BN], acc[e]);
 #endif

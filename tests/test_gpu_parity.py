@@ -51,6 +51,14 @@ def errors(c: np.ndarray, ref: np.ndarray):
 
 
 REFUSED_HANDPICKED = []     # hand-picked members the library refused to run because their kernels spill
+REFUSED_RANDOM = []         # seeded random members refused for the same reason
+# The only hand-picked members that may be refused for spills (they fill the register file on purpose: the
+# regression cases of a spill that once lost part of a value).  Any other hand-picked member that is
+# refused fails its test: it was chosen to cover a code path and no longer does.
+MAY_SPILL = ("may spill: 128 x 16 tile, one wave, slab 128, two partitions", "may spill: the same with one partition",
+             # derived from a TILE4 case by splitting its reduction: the split costs the registers that were left
+             "mfma32 8 rows x 56, 3 partition(s), layout 0")
+N_RANDOM = [0]              # seeded random members checked
 
 
 class Workload:
@@ -109,10 +117,15 @@ class Workload:
     def check(self, variant, cfg, label=""):
         _say("  case %s %s %s cfg=%s" % (self.kind, self.dims, label, list(map(int, cfg))))
         out = self.run(variant, cfg)
-        if out is None:     # refused after compilation (register spills): an invalid member, not a failure
-            if label != "random":
+        if out is None:     # refused after compilation (register spills): an invalid member
+            if label == "random":
+                REFUSED_RANDOM.append((self.kind, self.dims, list(map(int, cfg))))
+                N_RANDOM[0] += 1
+            else:   # judged at the end of the module, against the explicit list MAY_SPILL
                 REFUSED_HANDPICKED.append((self.kind, self.dims, label))
             return None
+        if label == "random":
+            N_RANDOM[0] += 1
         mx, fro = errors(out, self.ref)
         assert mx <= self.tol[0] and fro <= self.tol[1], (label, list(cfg), mx, fro, P.opevo_kernel_defines(self.op, variant, cfg))
         return mx, fro
@@ -172,29 +185,30 @@ def test_matmul64_f32_every_two_level_config_matches_oracle(torch_cuda):
 
 # ------------------------------------------------------------------ config 2: MatMul 512x1024x1024 bf16
 MM1_CASES = [
-    ("mfma32 double-buffered", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1]),
-    ("mfma32 single stage", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 0]),
-    ("mfma32 one atom per basic tile", [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1]),
-    ("mfma32 basic tile smaller than atom", [4, 2, 16, 4, 8, 2, 32, 2, 64, 16, 1]),
-    ("mfma32 deep slab", [8, 1, 1, 64, 16, 1, 2, 32, 4, 256, 0]),
-    ("mfma16", [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 1]),
-    ("mfma16 single stage", [32, 1, 1, 16, 64, 1, 1, 16, 8, 128, 0]),
-    ("mfma 1 wave, ragged slab share", [16, 1, 1, 32, 8, 1, 4, 32, 64, 16, 1]),
-    ("mfma 16 waves of 128x64, double-buffered, slab 16", [1, 4, 4, 32, 4, 4, 1, 64, 64, 16, 1]),
-    ("direct-to-LDS, 16 waves of 64x64", [2, 4, 2, 32, 4, 4, 2, 32, 32, 32, 1]),
-    ("direct-to-LDS, 4 stages of 32", [2, 2, 1, 128, 8, 4, 1, 32, 32, 32, 1]),
-    ("direct-to-LDS, slab 128, 2 stages", [4, 2, 2, 32, 8, 2, 2, 32, 8, 128, 1]),
-    ("direct-to-LDS, 64-wide tile, 1 wave", [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1]),
-    ("direct-to-LDS, 2 stages of 128", [4, 2, 1, 64, 8, 2, 1, 64, 8, 128, 1]),
-    ("scalar fallback", [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1]),
-    ("scalar fallback thin", [512, 1, 1, 1, 1, 1, 1, 1024, 128, 8, 0]),
-    ("scalar odd K slab", [16, 2, 4, 4, 32, 2, 4, 4, 1024, 1, 1]),
+    ("mfma32 double-buffered", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 1], 3),
+    ("mfma32 single stage", [2, 2, 2, 64, 8, 2, 2, 32, 16, 64, 0], 1),
+    ("mfma32 one atom per basic tile", [4, 2, 2, 32, 8, 2, 2, 32, 32, 32, 1], 3),
+    ("mfma32 basic tile smaller than atom", [4, 2, 16, 4, 8, 2, 32, 2, 64, 16, 1], 1),
+    ("mfma32 deep slab", [8, 1, 1, 64, 16, 1, 2, 32, 4, 256, 0], 1),
+    ("mfma16", [16, 2, 1, 16, 16, 2, 1, 32, 16, 64, 1], 2),
+    ("mfma16 single stage", [32, 1, 1, 16, 64, 1, 1, 16, 8, 128, 0], 2),
+    ("mfma 1 wave, ragged slab share", [16, 1, 1, 32, 8, 1, 4, 32, 64, 16, 1], 1),
+    ("mfma 16 waves of 64x64, double-buffered, slab 16", [2, 4, 2, 32, 4, 4, 1, 64, 64, 16, 1], 1),
+    ("direct-to-LDS, 16 waves of 64x64", [2, 4, 2, 32, 4, 4, 2, 32, 32, 32, 1], 3),
+    ("direct-to-LDS, 4 stages of 32", [2, 2, 1, 128, 8, 4, 1, 32, 32, 32, 1], 3),
+    ("direct-to-LDS, slab 128, 2 stages", [4, 2, 2, 32, 8, 2, 2, 32, 8, 128, 1], 3),
+    ("direct-to-LDS, 64-wide tile, 1 wave", [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1], 3),
+    ("direct-to-LDS, 2 stages of 128", [4, 2, 1, 64, 8, 2, 1, 64, 8, 128, 1], 3),
+    ("scalar fallback", [32, 2, 2, 4, 16, 2, 8, 4, 64, 16, 1], 0),
+    ("scalar fallback thin", [512, 1, 1, 1, 1, 1, 1, 1024, 128, 8, 0], 0),
+    ("scalar odd K slab", [16, 2, 4, 4, 32, 2, 4, 4, 1024, 1, 1], 0),
 ]
 
 
 def test_matmul_mm1_bf16_handpicked_and_random_configs(torch_cuda):
     w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
-    for label, cfg in MM1_CASES:
+    for label, cfg, path in MM1_CASES:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == path, label
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 24, seed=101):
         w.check(P.OPEVO_TILE4, cfg, "random")
@@ -295,21 +309,22 @@ def test_degenerate_sizes(torch_cuda):
 
 # ------------------------------------------------------------------ config 3: BMM 128 x (128x64 . 64x128)
 BMM_CASES = [
-    ("lds (direct), 2 batches per workgroup", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1]),
-    ("lds (direct), 4 batches, 2 slabs of 32", [32, 4, 1, 2, 2, 32, 1, 1, 4, 32, 2, 32, 1]),
-    ("lds register-staged, 2 batches", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 4, 16, 1]),
-    ("direct from global", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0]),
-    ("lds, two slabs", [128, 1, 1, 2, 2, 32, 1, 2, 1, 64, 2, 32, 1]),
-    ("mfma16 direct", [32, 4, 4, 2, 1, 16, 2, 2, 2, 16, 1, 64, 0]),
-    ("mfma16 lds", [128, 1, 4, 2, 1, 16, 2, 2, 2, 16, 2, 32, 1]),
-    ("scalar", [16, 8, 8, 2, 2, 4, 4, 2, 4, 4, 4, 16, 1]),
-    ("whole batch in one grid row", [1, 128, 1, 2, 2, 32, 1, 2, 2, 32, 1, 64, 1]),
+    ("lds (direct), 2 batches per workgroup", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 1], 3),
+    ("lds (direct), 4 batches, 2 slabs of 32", [32, 4, 1, 2, 2, 32, 1, 1, 4, 32, 2, 32, 1], 3),
+    ("lds register-staged, 2 batches", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 4, 16, 1], 1),
+    ("direct from global", [64, 2, 2, 1, 2, 32, 2, 1, 2, 32, 1, 64, 0], 1),
+    ("lds, two slabs", [128, 1, 1, 2, 2, 32, 1, 2, 1, 64, 2, 32, 1], 3),
+    ("mfma16 direct", [32, 4, 4, 2, 1, 16, 2, 2, 2, 16, 1, 64, 0], 2),
+    ("mfma16 lds", [128, 1, 4, 2, 1, 16, 2, 2, 2, 16, 2, 32, 1], 2),
+    ("scalar", [16, 8, 8, 2, 2, 4, 4, 2, 4, 4, 4, 16, 1], 0),
+    ("whole batch in one grid row", [1, 128, 1, 2, 2, 32, 1, 2, 2, 32, 1, 64, 1], 3),
 ]
 
 
 def test_bmm_attention_shape_bf16(torch_cuda):
     w = Workload(torch_cuda, "bmm", (128, 128, 128, 64), "bf16", 1236)
-    for label, cfg in BMM_CASES:
+    for label, cfg, path in BMM_CASES:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == path, label
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 18, seed=202):
         w.check(P.OPEVO_TILE4, cfg, "random")
@@ -327,20 +342,21 @@ def test_bmm_odd_batch(torch_cuda):
 
 # ------------------------------------------------------------------ config 4: Conv2d 1x64x56x56, 3x3
 CONV56_CASES = [
-    ("mfma32 8 rows x 56", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 1, 1, 1, 56, 9, 64, 1]),
-    ("mfma32 single stage", [1, 1, 2, 1, 1, 32, 7, 1, 1, 8, 2, 1, 1, 28, 18, 32, 0]),
-    ("mfma16 7-pixel pieces", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1]),
-    ("mfma16 slab 96", [1, 1, 4, 1, 1, 16, 14, 1, 1, 4, 1, 1, 7, 8, 6, 96, 1]),
-    ("mfma16, slab 24 zero-padded to 32", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
-    ("mfma16, 8 x 112 wave tile rounded up to 16 x 112", [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
-    ("scalar", [1, 1, 8, 2, 1, 4, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0]),
-    ("scalar one pixel tiles", [1, 1, 8, 1, 1, 8, 56, 1, 1, 1, 8, 1, 1, 7, 64, 9, 1]),
+    ("mfma32 8 rows x 56", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 1, 1, 1, 56, 9, 64, 1], 1),
+    ("mfma32 single stage", [1, 1, 2, 1, 1, 32, 7, 1, 1, 8, 2, 1, 1, 28, 18, 32, 0], 1),
+    ("mfma16 7-pixel pieces", [1, 1, 1, 2, 1, 32, 7, 2, 1, 4, 2, 1, 7, 4, 18, 32, 1], 2),
+    ("mfma16 slab 96, 4 waves of 16 x 56", [1, 1, 4, 1, 1, 16, 14, 2, 1, 2, 1, 2, 7, 4, 6, 96, 1], 2),
+    ("mfma16, slab 24 zero-padded to 32", [1, 1, 1, 2, 4, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 2),
+    ("mfma16, 8 x 112 wave tile rounded up to 16 x 112", [1, 1, 4, 2, 1, 8, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 2),
+    ("scalar", [1, 1, 8, 2, 1, 4, 7, 2, 2, 2, 2, 1, 7, 4, 24, 24, 0], 0),
+    ("scalar one pixel tiles", [1, 1, 8, 1, 1, 8, 56, 1, 1, 1, 8, 1, 1, 7, 64, 9, 1], 0),
 ]
 
 
 def test_conv56_bf16(torch_cuda):
     w = Workload(torch_cuda, "conv2d", (1, 64, 56, 56, 64, 3, 3, 1, 1), "bf16", 1237)
-    for label, cfg in CONV56_CASES:
+    for label, cfg, path in CONV56_CASES:
+        assert P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path == path, label
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 18, seed=303):
         w.check(P.OPEVO_TILE4, cfg, "random")
@@ -374,13 +390,13 @@ def test_conv_stride_padding_kernel_shapes(torch_cuda):
                        ("mfma16, 7 waves, slab 11 padded to 32", [1, 16, 1, 1, 1, 16, 1, 7, 1, 1, 7, 1, 1, 1, 33, 11, 1]),
                        ("mfma16, 28-pixel wave tile rounded up to 32", [4, 4, 1, 1, 1, 16, 7, 1, 1, 1, 1, 1, 1, 7, 11, 33, 1]),
                        ("mfma16, 7 waves of 16 x 8 rounded up to 16 x 16", [2, 8, 1, 1, 2, 8, 1, 7, 1, 1, 7, 1, 1, 1, 3, 121, 0]),
-                       ("mfma16, one wave, 784 pixels", [1, 16, 1, 1, 1, 16, 1, 1, 1, 7, 1, 1, 7, 1, 33, 11, 1])]:
+                       ("mfma16, one wave, 196 pixels of 4 images", [4, 4, 1, 1, 1, 16, 1, 1, 1, 7, 1, 1, 7, 1, 33, 11, 1])]:
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(0, 2)):
         w.check(P.OPEVO_TILE4, cfg, "random")
     w.close()
     w = Workload(torch_cuda, "conv2d", (32, 3, 19, 19, 32, 11, 11, 4, 0), "bf16", 45)   # out 3x3, 32 images per tile
-    for label, cfg in [("mfma32, slab 121 padded to 128", [1, 32, 1, 1, 1, 32, 3, 1, 1, 1, 3, 1, 1, 1, 3, 121, 1]),
+    for label, cfg in [("mfma32, 9 waves of 32 x 32, slab 121 padded to 128, single stage", [1, 32, 1, 1, 1, 32, 1, 3, 1, 1, 1, 3, 1, 1, 3, 121, 0]),
                        ("mfma32, 3 waves, slab 33 padded to 48", [1, 32, 1, 1, 1, 32, 1, 3, 1, 1, 1, 1, 3, 1, 11, 33, 1])]:
         w.check(P.OPEVO_TILE4, cfg, label)
     for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=707, want_paths=(0, 1, 2)):
@@ -423,19 +439,32 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
     _say("  oracle rows/entries for 8192^3 ...")
     ref_rows = T.matmul_rows(w.a_host, w.b_host, rows)
     ref_ent = T.matmul_entries(w.a_host, w.b_host, ei, ej)
-    cases = [("256x256 tile, 4 waves, double-buffered", [32, 2, 1, 128, 32, 2, 1, 128, 128, 64, 1]),
-             ("256x128 tile, 8 waves", [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1]),
-             ("direct-to-LDS 256x256, 4 waves of 128x128, 4 stages of 32", [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1]),
-             ("direct-to-LDS 256x256, 8 waves of 128x64, 4 stages of 32", [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1]),
-             ("direct-to-LDS 256x256, 8 waves of 128x64, 2 stages of 64", [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1]),
-             ("direct-to-LDS 256x256, 16 waves of 64x64", [32, 4, 16, 4, 32, 4, 2, 32, 256, 32, 1]),
-             ("128x128 single stage", [64, 2, 2, 32, 64, 2, 1, 64, 128, 64, 0]),
-             ("mfma16 32x64 tile", [256, 2, 1, 16, 128, 2, 1, 32, 128, 64, 1])]
-    for cfg in w.random_valid(P.OPEVO_TILE4, 6, seed=606, want_paths=(1, 2, 3)):
-        cases.append(("random", list(cfg)))
-    for label, cfg in cases:
+    V4, VT = P.OPEVO_TILE4, P.OPEVO_TILE4T
+    # (label, space, configuration, template path the decoder must choose)
+    cases = [("direct-to-LDS 256x256, 4 waves of 128x128, 2 stages of 64", V4, [32, 2, 1, 128, 32, 2, 1, 128, 128, 64, 1], 3),
+             ("direct-to-LDS 256x128, 8 waves, 4 stages of 32", V4, [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1], 3),
+             ("direct-to-LDS 256x256, 4 waves of 128x128, 4 stages of 32", V4, [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1], 3),
+             ("direct-to-LDS 256x256, 8 waves of 128x64, 4 stages of 32", V4, [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1], 3),
+             ("direct-to-LDS 256x256, 8 waves of 128x64, 2 stages of 64", V4, [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1], 3),
+             ("direct-to-LDS 256x256, 16 waves of 64x64", V4, [32, 4, 16, 4, 32, 4, 2, 32, 256, 32, 1], 3),
+             ("register-staged, double-buffered (flag 1), 256x256, 4 waves, slabs of 16", V4, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1], 1),
+             ("register-staged, double-buffered (flag 1), 128x256, 8 waves, slabs of 16", V4, [64, 2, 2, 32, 32, 4, 2, 32, 512, 16, 1], 1),
+             ("register-staged 128x128 single stage", V4, [64, 2, 2, 32, 64, 2, 1, 64, 128, 64, 0], 1),
+             ("16x16x32 atoms, 32x64 tile, double-buffered", V4, [256, 2, 1, 16, 128, 2, 1, 32, 128, 64, 1], 2),
+             ("16x16x32 atoms, 64x64 tile, 4 waves of 16x64, slabs of 32", V4, [128, 4, 1, 16, 128, 1, 2, 32, 256, 32, 1], 2),
+             ("second operand transposed by the pre-pass, 256x256, 4 waves, 4 stages of 32", VT, [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1, 1], 3),
+             ("second operand transposed by the pre-pass, 256x256, 8 waves, 2 stages of 64", VT, [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1, 1], 3),
+             ("second operand transposed by the pre-pass, 128x128, 2 stages of 128", VT, [64, 2, 2, 32, 64, 2, 2, 32, 64, 128, 1, 1], 3),
+             ("bpack = 1 on a register-staged member: inert", VT, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1], 1)]
+    for cfg in w.random_valid(V4, 6, seed=606, want_paths=(1, 2, 3)):
+        cases.append(("random", V4, list(cfg), None))
+    for label, variant, cfg, path in cases:
         _say("  case 8192^3 %s cfg=%s" % (label, list(map(int, cfg))))
-        out = w.run(P.OPEVO_TILE4, cfg)
+        if path is not None:
+            assert P.opevo_kernel_plan(w.op, variant, cfg).path == path, label
+        if variant == VT:
+            assert ("-DB_KMAJOR=1" in P.opevo_kernel_defines(w.op, variant, cfg)) == (path == 3), label
+        out = w.run(variant, cfg)
         if out is None:
             assert label == "random", label
             continue
@@ -448,6 +477,37 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
         # property that holds at any size: column sums of C equal (1^T A) B
         colsum = w.a_host.astype(np.float64).sum(axis=0) @ w.b_host.astype(np.float64)
         assert np.max(np.abs(out.astype(np.float64).sum(axis=0) - colsum)) <= 2e-2 * (np.max(np.abs(colsum)) + 1)
+    w.close()
+
+
+# ------------------------------------------------------------------ MatMul with the second operand transposed by a pre-pass
+def test_matmul_second_operand_packed_by_a_prepass(torch_cuda):
+    """TILE4T: M(4) N(4) K(2) unroll bpack.  bpack = 1 on a direct-to-LDS member: a pre-pass writes B as
+    [N][K] into the kernel's workspace before every launch and both operands are read K-contiguous."""
+    V = P.OPEVO_TILE4T
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
+    for label, cfg, _ in MM1_CASES:
+        c = list(cfg) + [1]
+        plan = P.opevo_kernel_plan(w.op, V, c)
+        assert plan.path == P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path, label
+        assert ("-DB_KMAJOR=1" in P.opevo_kernel_defines(w.op, V, c)) == (plan.path == 3), label
+        w.check(V, c, label + ", bpack 1")
+    for cfg in w.random_valid(V, 16, seed=1212, want_paths=(3,)):
+        w.check(V, cfg, "random")
+    # one kernel object, launched again after B changed: the pre-pass belongs to every launch
+    c = [2, 2, 1, 128, 8, 4, 1, 32, 32, 32, 1, 1]
+    kernel, _ = P.opevo_kernel_build(w.op, V, c)
+    mx, fro = errors(w.run(V, c, kernel), w.ref)
+    assert mx <= TOL16[0] and fro <= TOL16[1]
+    w.b.mul_(-2.0)
+    mx, fro = errors(w.run(V, c, kernel), -2.0 * w.ref)
+    assert mx <= TOL16[0] and fro <= TOL16[1], (mx, fro)
+    P.opevo_kernel_destroy(kernel)
+    w.close()
+    # a shape whose axes are no powers of two (multi-prime factor graphs), ragged transposition tiles
+    w = Workload(torch_cuda, "matmul", (192, 320, 448), "bf16", 77)
+    for cfg in w.random_valid(V, 8, seed=1313, want_paths=(3,)):
+        w.check(V, cfg, "random")
     w.close()
 
 
@@ -525,9 +585,12 @@ PAPER_SHAPES = [
       ("mfma16, 480 batches per workgroup", [2, 480, 4, 2, 1, 16, 2, 2, 1, 16, 4, 32, 0])]),
     ("BMM2", "bmm_ta", (960, 128, 64, 128), 1245, 6, (0, 1, 2, 3), []),
     ("BMM3", "bmm_ta", (960, 64, 64, 128), 1246, 6, (0, 1, 2, 3), []),
-    ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (1, 2), []),
+    ("C2", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (0, 1, 2), []),
+    # the same operator in the space with the split reduction and channels-last operands: direct-to-LDS members
+    ("C2 channels last", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (3,),
+     [("6 waves of 32 x 243 -> 256, slabs of 32", [512, 1, 3, 2, 1, 32, 1, 3, 9, 1, 1, 1, 27, 1, 1, 50, 32, 1, 1])], "TILE4C"),
     # C1's reduction axis 3*11*11 = 363 has no factor 16: MFMA members stage zero-padded K slabs
-    ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (1, 2),
+    ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (0, 1, 2),
      [("scalar, 16 x 484 tile", [128, 4, 4, 1, 4, 4, 5, 11, 1, 1, 5, 1, 11, 1, 11, 33, 1])]),
 ]
 
@@ -553,7 +616,8 @@ def test_paper_operator_shapes_on_sampled_outputs(torch_cuda):
 
 
 def _paper_shapes(torch, shapes, dtype, tol, n_random):
-    for name, kind, dims, seed, n_sample, paths, picked in shapes:
+    for name, kind, dims, seed, n_sample, paths, picked, *space in shapes:
+        V = getattr(P, "OPEVO_" + space[0]) if space else P.OPEVO_TILE4
         w = Workload(torch, kind, dims, dtype, seed, oracle=False)
         lead = dims[0]
         idx = np.sort(np.random.default_rng(seed).choice(lead, size=n_sample, replace=False))
@@ -568,14 +632,15 @@ def _paper_shapes(torch, shapes, dtype, tol, n_random):
             ref = T.conv2d(w.b_host[idx], w.a_host, dims[7], dims[8])
         cases = [(label, cfg) for label, cfg in picked]
         if paths:
-            cases += [("random", list(c)) for c in w.random_valid(P.OPEVO_TILE4, n_random, seed=seed + 1, want_paths=paths)]
+            cases += [("random", list(c)) for c in w.random_valid(V, n_random, seed=seed + 1, want_paths=paths)]
         for label, cfg in cases:
-            plan = P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg)
+            plan = P.opevo_kernel_plan(w.op, V, cfg)
             assert plan.status == P.OPEVO_OK, (name, label, cfg, plan.reason)
             _say("  case %s %s path %d cfg=%s" % (name, label, plan.path, list(map(int, cfg))))
-            out = w.run(P.OPEVO_TILE4, cfg)
+            out = w.run(V, cfg)
             if out is None:
                 assert label == "random", (name, label)
+                REFUSED_RANDOM.append((kind, dims, list(map(int, cfg))))
                 continue
             out = out.reshape(lead, -1)
             assert np.all(np.isfinite(out)), (name, label)
@@ -636,6 +701,130 @@ def test_conv_with_separately_split_reduction_axes(torch_cuda):
         w.check(V, cfg, label)
     for cfg in w.random_valid(V, 6, seed=909, want_paths=(0, 2)):
         w.check(V, cfg, "random")
+    w.close()
+
+
+# ------------------------------------------------------------------ Conv2d: reduction split over workgroups, channels-last operands
+def _c4(cfg17, parts, layout):
+    """A TILE4 convolution member as a TILE4C member: R = (steps, slab) -> (parts, steps / parts, slab)."""
+    assert cfg17[14] % parts == 0
+    return list(cfg17[:14]) + [parts, cfg17[14] // parts, cfg17[15], cfg17[16], layout]
+
+
+def test_conv_split_reduction_and_channels_last_operands(torch_cuda):
+    """TILE4C: B(2) Cout(4) H(4) W(4) R(3) unroll layout.  Partitions along grid z add partial sums into
+    a cleared output; layout = 1 reads channels-last copies of both operands that a pre-pass writes
+    before every launch.  Every template path, padded slabs, ragged wave tiles, stride and padding,
+    slabs that span several taps, repeated launches with changed inputs, random members, Alg. 1."""
+    V = P.OPEVO_TILE4C
+    w = Workload(torch_cuda, "conv2d", (1, 64, 56, 56, 64, 3, 3, 1, 1), "bf16", 1237)
+    for label, cfg, path in CONV56_CASES:
+        for parts, layout in ((1, 0), (1, 1), (3, 1), (3, 0)):
+            if cfg[14] % parts:
+                continue
+            c = _c4(cfg, parts, layout)
+            plan = P.opevo_kernel_plan(w.op, V, c)
+            # a pipelined channels-last member may move from the register-staged to the direct-to-LDS template
+            assert plan.status == P.OPEVO_OK and plan.grid[2] == parts, (label, plan.reason)
+            assert plan.path == path or (layout == 1 and c[17] == 1 and path in (1, 2) and plan.path == 3), (label, plan.path)
+            defs = P.opevo_kernel_defines(w.op, V, c)
+            # channels-last needs an MFMA member and a slab that is a multiple of 8; elsewhere the choice is inert
+            assert ("-DCONV_NHWC=1" in defs) == (layout == 1 and path in (1, 2) and cfg[15] % 8 == 0), (label, defs)
+            assert ("-DKSPLIT=%d" % parts in defs) == (parts > 1)
+            w.check(V, c, "%s, %d partition(s), layout %d" % (label, parts, layout))
+    for cfg in w.random_valid(V, 32, seed=808, want_paths=(0, 1, 2, 3)):
+        w.check(V, cfg, "random")
+    # one kernel object, launched again after the inputs changed: the pre-pass and the clear belong to every launch
+    cfg = _c4(CONV56_CASES[0][1], 3, 1)
+    kernel, _ = P.opevo_kernel_build(w.op, V, cfg)
+    out = w.run(V, cfg, kernel)
+    mx, fro = errors(out, w.ref)
+    assert mx <= TOL16[0] and fro <= TOL16[1]
+    w.b.mul_(2.0)                                  # image doubled (exact in bf16): the output must double
+    out2 = w.run(V, cfg, kernel)
+    mx, fro = errors(out2, 2.0 * w.ref)
+    assert mx <= TOL16[0] and fro <= TOL16[1], (mx, fro)
+    w.a.mul_(0.5)                                  # kernel tensor halved: back to the reference
+    ms, _ = P.opevo_kernel_time(kernel, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, warmup=2, samples=3)
+    torch_cuda.cuda.synchronize()
+    mx, fro = errors(w.c.cpu().numpy(), w.ref)
+    assert ms > 0 and mx <= TOL16[0] and fro <= TOL16[1], (ms, mx, fro)
+    P.opevo_kernel_destroy(kernel)
+    w.close()
+    # stride 2 with padding (taps outside the image on every border), 16 channels
+    w = Workload(torch_cuda, "conv2d", (2, 16, 9, 9, 32, 3, 3, 2, 1), "bf16", 43)      # out 5x5, R = 144
+    for label, cfg in [("mfma16 rounded up, slab 48 padded to 64, 3 partitions", [1, 2, 1, 1, 1, 32, 1, 1, 1, 5, 5, 1, 1, 1, 3, 1, 48, 1, 1]),
+                       ("mfma32, slab 16 = one tap, single stage", [1, 2, 1, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 1, 9, 16, 0, 1]),
+                       ("mfma32, slab 8 padded to 16, 2 partitions", [1, 2, 1, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 2, 9, 8, 1, 1]),
+                       ("mfma32, one slab of 144 (all 9 taps)", [1, 2, 1, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 1, 1, 144, 0, 1])]:
+        assert "-DCONV_NHWC=1" in P.opevo_kernel_defines(w.op, V, cfg), label
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 12, seed=909, want_paths=(0, 1, 2)):
+        w.check(V, cfg, "random")
+    w.close()
+    # 5x5 with padding 2, slabs of 40 = two and a half taps of 16 channels
+    w = Workload(torch_cuda, "conv2d", (4, 16, 12, 12, 32, 5, 5, 1, 2), "bf16", 42)    # out 12x12, R = 400
+    for label, cfg in [("mfma32, batch inside the tile, slab 40 padded to 48, 2 partitions", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 2, 5, 40, 1, 1]),
+                       ("mfma32, slab 80, 5 partitions of one slab", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 5, 1, 80, 0, 1]),
+                       ("the same tiles on the NCHW gather", [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 5, 1, 80, 0, 0])]:
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 12, seed=910, want_paths=(1, 2)):
+        w.check(V, cfg, "random")
+    w.close()
+    # direct-to-LDS members (slabs of 32 / 64 / 128 reduction values): 4x4 kernel over 16 channels, so a slab
+    # holds 2, 4 or 8 taps (up to two kernel rows); padding 1; 3 images of 10x10 outputs (ragged pixel tiles)
+    w = Workload(torch_cuda, "conv2d", (3, 16, 11, 11, 32, 4, 4, 1, 1), "bf16", 46)     # R = 256
+    for label, cfg in [("one wave 32 x 25 -> 32, slab 32 = 2 taps, 4 stages", [3, 1, 1, 1, 1, 32, 2, 1, 1, 5, 2, 1, 1, 5, 1, 8, 32, 1, 1]),
+                       ("4 waves of 32 x 25, slab 64 = one kernel row", [3, 1, 1, 1, 1, 32, 1, 2, 1, 5, 1, 2, 1, 5, 1, 4, 64, 1, 1]),
+                       ("4 waves of 32 x 25 -> 32, slab 128 = two kernel rows, 2 partitions of one slab", [3, 1, 1, 1, 1, 32, 1, 2, 1, 5, 1, 2, 1, 5, 2, 1, 128, 1, 1]),
+                       ("5 waves of 32 x 20 -> 32 (A and B parts rounded up to whole loads), 2 partitions", [3, 1, 1, 1, 1, 32, 1, 5, 1, 2, 1, 1, 1, 10, 2, 2, 64, 1, 1])]:
+        assert P.opevo_kernel_plan(w.op, V, cfg).path == 3, label
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 12, seed=911, want_paths=(3,)):
+        w.check(V, cfg, "random")
+    w.close()
+    # stride 2, padding 1, 3x3 over 32 channels: a slab of 32 is exactly one tap
+    w = Workload(torch_cuda, "conv2d", (4, 32, 10, 10, 64, 3, 3, 2, 1), "bf16", 47)     # out 5x5, R = 288
+    for label, cfg in [("2 waves of 32 x 100 -> 128 (4 images), slab 32, 3 partitions", [1, 4, 1, 2, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 3, 3, 32, 1, 1]),
+                       ("one image per tile, 1 wave 64 x 25 -> 32", [4, 1, 1, 1, 2, 32, 1, 1, 1, 5, 1, 1, 1, 5, 1, 9, 32, 1, 1])]:
+        assert P.opevo_kernel_plan(w.op, V, cfg).path == 3, label
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 8, seed=912, want_paths=(3,)):
+        w.check(V, cfg, "random")
+    w.close()
+    # 3 input channels: no channels-last member exists, layout = 1 runs the gather
+    w = Workload(torch_cuda, "conv2d", (16, 3, 35, 35, 16, 11, 11, 4, 0), "bf16", 44)
+    cfg = [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 11, 33, 1, 1]
+    assert "CONV_NHWC" not in P.opevo_kernel_defines(w.op, V, cfg)
+    w.check(V, cfg, "Cin = 3: inert layout flag")
+    w.close()
+
+
+def test_conv14_split_reduction_channels_last_full_size_and_alg1(torch_cuda):
+    V = P.OPEVO_TILE4C
+    w = Workload(torch_cuda, "conv2d", (32, 256, 14, 14, 256, 3, 3, 1, 1), "bf16", 1239)
+    for label, cfg in [("8 images per tile, channels last", [4, 8, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 1, 36, 64, 1, 1]),
+                       ("the same with 4 partitions", [4, 8, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 4, 9, 64, 1, 1]),
+                       ("the same on the register-staged template (single stage)", [4, 8, 2, 2, 2, 32, 7, 1, 1, 2, 7, 1, 1, 2, 4, 9, 64, 0, 1]),
+                       ("mfma16, 4 images per tile, 9 partitions = one per tap", [8, 4, 4, 2, 1, 32, 7, 1, 1, 2, 7, 1, 1, 2, 9, 8, 32, 1, 1]),
+                       ("64 x 196 tiles (one image), slab 128, 2 partitions", [32, 1, 4, 2, 1, 32, 1, 1, 2, 7, 1, 2, 1, 7, 2, 9, 128, 1, 1]),
+                       ("direct-to-LDS: 128 x 196, 14 waves of 64 x 28 -> 32", [32, 1, 2, 2, 2, 32, 1, 7, 2, 1, 1, 1, 14, 1, 1, 36, 64, 1, 1]),
+                       ("direct-to-LDS: 256 x 196, 16 waves of 64 x 49 -> 64, 8 partitions, 4 stages", [32, 1, 1, 4, 2, 32, 1, 2, 7, 1, 1, 2, 7, 1, 8, 9, 32, 1, 1]),
+                       ("direct-to-LDS: 2 images per tile, 3 stages", [16, 2, 2, 2, 2, 32, 1, 7, 2, 1, 1, 1, 14, 1, 8, 9, 32, 1, 1]),
+                       ("direct-to-LDS: 64 x 196, 7 waves", [32, 1, 4, 1, 2, 32, 1, 7, 2, 1, 1, 1, 14, 1, 2, 18, 64, 1, 1])]:
+        assert "-DCONV_NHWC=1" in P.opevo_kernel_defines(w.op, V, cfg), label
+        if "direct-to-LDS" in label:
+            assert P.opevo_kernel_plan(w.op, V, cfg).path == 3, label
+        w.check(V, cfg, label)
+    for cfg in w.random_valid(V, 12, seed=511, want_paths=(1, 2, 3)):
+        w.check(V, cfg, "random")
+    ref = torch_cuda.from_numpy(w.ref.astype(np.float32).ravel()).cuda()
+    res = P.opevo_tune(w.op, V, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), ref.data_ptr(), w.stream,
+                       trials=64, lambda_=8, rho=8, q=0.5, seed=3, compile_threads=8, warmup=2, samples=3,
+                       trial_timeout_ms=50.0)
+    assert res["n_trials"] == 64 and res["n_parity_fail"] == 0 and res["n_compile_fail"] == 0 and res["best_tflops"] > 0
+    w.check(V, res["best_cfg"], "tuned best")
+    _say("  conv14 best after 64 trials %.1f TFLOP/s: %s" % (res["best_tflops"], list(res["best_cfg"])))
     w.close()
 
 
@@ -824,5 +1013,13 @@ def test_zz_few_handpicked_members_were_refused_for_spills(torch_cuda):
     """Hand-picked members are chosen to exercise code paths; a few fill the register file and are
     refused after compilation.  If many were, the cases above would no longer cover those paths."""
     for item in REFUSED_HANDPICKED:
-        _say("  refused: %s %s %s" % item)
-    assert len(REFUSED_HANDPICKED) <= 8, REFUSED_HANDPICKED
+        _say("  refused (hand-picked, on the explicit list): %s %s %s" % item)
+    for item in REFUSED_RANDOM:
+        _say("  refused (random): %s %s %s" % item)
+    _say("  refused for spills: %d hand-picked (of %d allowed), %d of at least %d random members"
+         % (len(REFUSED_HANDPICKED), len(MAY_SPILL), len(REFUSED_RANDOM), N_RANDOM[0]))
+    unexpected = [item for item in REFUSED_HANDPICKED if item[2] not in MAY_SPILL]
+    assert not unexpected, "hand-picked members refused for spills that are not on the explicit list: %s" % unexpected
+    # random members that the decoder calls valid but that fill the register file: invalid trials (fitness 0),
+    # not failures, as long as they stay a small share of what is sampled
+    assert len(REFUSED_RANDOM) <= max(8, N_RANDOM[0] // 6), REFUSED_RANDOM

@@ -410,3 +410,125 @@ def test_fp32_inputs_use_the_fp32_mfma_template_where_the_tile_allows():
     assert plan.path == 4 and plan.lds_bytes == 2 * (16 * 132 + 16 * 68) * 4
     kernel, _ = P.opevo_kernel_build(ta, P.OPEVO_TILE4, cfg)
     P.opevo_kernel_destroy(kernel)
+
+
+# ---------------------------------------------------------------- Conv2d: split reduction + channels-last operands (TILE4C)
+def test_conv_split_channels_last_space_and_its_decoding():
+    op = _op(CONV14, P.OPEVO_BF16)
+    sp = P.opevo_op_space(op, P.OPEVO_TILE4C)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["B", "Cout", "H", "W", "R", "unroll", "layout"] and P.opevo_space_width(sp) == 19
+    # 2304 = 2^8 * 3^2 in three ordered factors: C(10, 2) * C(4, 2) = 45 * 6
+    assert P.opevo_space_param_size(sp, 4) == 270
+    P.opevo_space_destroy(sp)
+    for kd in (MM1, BMM):
+        with pytest.raises(P.OpevoError):
+            P.opevo_op_space(_op(kd, P.OPEVO_BF16), P.OPEVO_TILE4C)
+    V = P.OPEVO_TILE4C
+    # 4 partitions on grid z; channels last; 14 waves of 64 x 28 (rounded up to 32): the direct-to-LDS
+    # template with both stage parts rounded up to whole 1 KiB loads per wave (224 rows each)
+    cfg = [32, 1, 2, 2, 2, 32, 1, 7, 2, 1, 1, 1, 14, 1, 4, 9, 64, 1, 1]
+    plan = P.opevo_kernel_plan(op, V, cfg)
+    d = P.opevo_kernel_defines(op, V, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == 3 and list(plan.grid) == [32, 2, 4] and plan.block == 896
+    assert list(plan.tile) == [128, 196, 64] and list(plan.wave_tile) == [64, 28] and plan.acc_per_lane == 32
+    for want in ("-DKSPLIT=4", "-DKSTEPS=9", "-DCONV_NHWC=1", "-DB_KMAJOR=1", "-DBNR=224", "-DANR=224", "-DNSTG=2"):
+        assert want in d.split(), (want, d)
+    assert plan.lds_bytes == 2 * (224 + 224) * 64 * 2
+    # layout = 0: the same tiles on the NCHW gather (register-staged, 16x16 atoms), same grid
+    plan0 = P.opevo_kernel_plan(op, V, cfg[:18] + [0])
+    d0 = P.opevo_kernel_defines(op, V, cfg[:18] + [0])
+    assert plan0.path == 2 and list(plan0.grid) == [32, 2, 4] and "CONV_NHWC" not in d0 and "-DKSPLIT=4" in d0.split()
+    # not pipelined (unroll = 0): channels last on the register-staged template
+    d1 = P.opevo_kernel_defines(op, V, cfg[:17] + [0, 1])
+    assert P.opevo_kernel_plan(op, V, cfg[:17] + [0, 1]).path == 2 and "-DCONV_NHWC=1" in d1.split() and "B_KMAJOR" not in d1
+    # a slab that is no multiple of 8 (2304 = 36 * 4 * 16 ... here 9 * 4 * 4 * 4 * 4: slab 4): the choice is inert
+    d2 = P.opevo_kernel_defines(op, V, cfg[:14] + [4, 144, 4, 1, 1])
+    assert "CONV_NHWC" not in d2
+    with pytest.raises(P.OpevoError):                          # 4 * 9 * 32 != 2304
+        P.opevo_kernel_plan(op, V, cfg[:14] + [4, 9, 32, 1, 1])
+    # three input channels (the paper's C1): no channels-last member exists
+    c1 = _op((P.OPEVO_CONV2D, (16, 3, 35, 35, 16, 11, 11, 4, 0)), P.OPEVO_BF16)
+    assert "CONV_NHWC" not in P.opevo_kernel_defines(c1, V, [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 11, 33, 1, 1])
+
+
+def test_conv_split_channels_last_space_is_not_mostly_invalid_and_reaches_every_template():
+    op = _op(CONV14, P.OPEVO_BF16)
+    V = P.OPEVO_TILE4C
+    sp = P.opevo_op_space(op, V)
+    rng = P.opevo_rng_create(5)
+    paths, valid, total = {}, 0, 3000
+    for _ in range(total):
+        cfg = P.opevo_space_random(sp, rng)
+        plan = P.opevo_kernel_plan(op, V, cfg)
+        if plan.status == P.OPEVO_OK:
+            valid += 1
+            paths[plan.path] = paths.get(plan.path, 0) + 1
+            assert plan.lds_bytes <= 160 * 1024 and plan.block <= 1024 and plan.acc_per_lane <= 256
+            assert plan.grid[2] == cfg[14]                     # partitions on grid z
+    assert valid > 0.3 * total and set(paths) == {0, 1, 2, 3}, (valid, paths)
+    P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+
+
+TILE4C_COMPILE_CASES = [
+    ("direct-to-LDS, channels last, 14 waves, padded stage parts, 4 partitions", CONV14, [32, 1, 2, 2, 2, 32, 1, 7, 2, 1, 1, 1, 14, 1, 4, 9, 64, 1, 1], 3),
+    ("direct-to-LDS, channels last, one wave of 32 x 28, slabs of 128 in groups of 4 steps", CONV14, [32, 1, 8, 1, 1, 32, 1, 7, 2, 1, 1, 1, 14, 1, 1, 18, 128, 1, 1], 3),
+    ("direct-to-LDS, multi-tap slabs (16 channels, slab 64 = 4 taps)", (P.OPEVO_CONV2D, (3, 16, 11, 11, 32, 4, 4, 1, 1)), [3, 1, 1, 1, 1, 32, 1, 2, 1, 5, 1, 2, 1, 5, 1, 4, 64, 1, 1], 3),
+    ("register-staged, channels last, slab 40 padded to 48", (P.OPEVO_CONV2D, (4, 16, 12, 12, 32, 5, 5, 1, 2)), [1, 4, 1, 1, 1, 32, 3, 1, 1, 4, 6, 1, 1, 2, 2, 5, 40, 1, 1], 1),
+    ("register-staged 16x16 atoms, NCHW gather, 9 partitions", CONV14, [8, 4, 4, 2, 1, 32, 7, 1, 1, 2, 7, 1, 1, 2, 9, 8, 32, 1, 0], 2),
+    ("scalar, 2 partitions", CONV56, [1, 1, 8, 2, 1, 4, 7, 2, 2, 2, 2, 1, 7, 4, 2, 12, 24, 0, 1], 0),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg,path", TILE4C_COMPILE_CASES, ids=[c[0] for c in TILE4C_COMPILE_CASES])
+def test_conv_split_channels_last_templates_compile(label, kd, cfg, path):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4C, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4C, cfg)
+    assert 1000 < P.opevo_kernel_code_size(kernel) < (128 << 10)
+    P.opevo_kernel_destroy(kernel)
+
+
+# ---------------------------------------------------------------- MatMul: second operand transposed by a pre-pass (TILE4T)
+def test_packed_second_operand_space_and_its_decoding():
+    op = _op((P.OPEVO_MATMUL, (8192, 8192, 8192)), P.OPEVO_BF16)
+    V = P.OPEVO_TILE4T
+    sp = P.opevo_op_space(op, V)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["M", "N", "K", "unroll", "bpack"] and P.opevo_space_width(sp) == 12
+    assert P.opevo_space_size(sp) == 2 * P.opevo_space_size(P.opevo_op_space(op, P.OPEVO_TILE4))
+    P.opevo_space_destroy(sp)
+    with pytest.raises(P.OpevoError):
+        P.opevo_op_space(_op(CONV56, P.OPEVO_BF16), V)
+    cfg = [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1]
+    for bpack in (0, 1):
+        plan = P.opevo_kernel_plan(op, V, cfg + [bpack])
+        d = P.opevo_kernel_defines(op, V, cfg + [bpack])
+        assert plan.status == P.OPEVO_OK and plan.path == 3 and plan.lds_bytes == 4 * 512 * 32 * 2
+        assert ("-DB_KMAJOR=1" in d.split()) == (bpack == 1) and ("-DBNR=256" in d.split()) == (bpack == 1)
+    # on a member of the register-staged template the choice is inert
+    d = P.opevo_kernel_defines(op, V, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1])
+    assert "B_KMAJOR" not in d
+    # with the second operand K-contiguous, tile widths that the [K][N] chunk permutation cannot serve become eligible
+    mm = _op((P.OPEVO_MATMUL, (512, 768, 1024)), P.OPEVO_BF16)
+    c96 = [4, 2, 2, 32, 8, 1, 3, 32, 32, 32, 1]                # BN = 96
+    assert P.opevo_kernel_plan(mm, V, c96 + [0]).path == 1 and P.opevo_kernel_plan(mm, V, c96 + [1]).path == 3
+
+
+TILE4T_COMPILE_CASES = [
+    ("256x256, 4 waves, 4 stages of 32", (P.OPEVO_MATMUL, (8192, 8192, 8192)), [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1, 1]),
+    ("one wave of 32 x 64, slabs of 64 in groups of 2 steps", MM1, [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1, 1]),
+    ("96-wide tile", (P.OPEVO_MATMUL, (512, 768, 1024)), [4, 2, 2, 32, 8, 1, 3, 32, 32, 32, 1, 1]),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg", TILE4T_COMPILE_CASES, ids=[c[0] for c in TILE4T_COMPILE_CASES])
+def test_packed_second_operand_templates_compile(label, kd, cfg):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4T, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == 3, (plan.reason, plan.path)
+    assert "-DB_KMAJOR=1" in P.opevo_kernel_defines(op, P.OPEVO_TILE4T, cfg).split()
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4T, cfg)
+    assert 1000 < P.opevo_kernel_code_size(kernel) < (128 << 10)
+    P.opevo_kernel_destroy(kernel)
