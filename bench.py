@@ -71,7 +71,7 @@ def main() -> int:
     ap.add_argument("--oracle-rows", type=int, default=32,
                     help="rows of C the CPU oracle computes (8192^3 only), spread evenly: one per block of M / rows")
     ap.add_argument("--timeout-ms", type=float, default=0.0,
-                    help="deadline of a scalar-template launch; 0 = 300 ms scaled by the workload's flops relative "
+                    help="deadline of a scalar-template or folded launch; 0 = 100 ms scaled by the workload's flops relative "
                          "to the 8192^3 MatMul, at least 10 ms")
     ap.add_argument("--traffic", default=None,
                     help="measured HBM bytes per launch of the dominant kernel, 'fetch,write' (from counter runs)")
@@ -166,7 +166,7 @@ def main() -> int:
     drows = torch.from_numpy(rows).cuda() if rows is not None else None
     tol = (1e-4, 1e-4) if dtype == "f32" else (2e-2, 5e-3)
 
-    timeout_ms = args.timeout_ms if args.timeout_ms > 0 else max(10.0, 300.0 * flops / (2.0 * 8192.0 ** 3))
+    timeout_ms = args.timeout_ms if args.timeout_ms > 0 else max(10.0, 100.0 * flops / (2.0 * 8192.0 ** 3))
 
     def tune(trials, seed):
         return P.opevo_tune(op, variant, da.data_ptr(), db.data_ptr(), dc.data_ptr(), dref.data_ptr(), stream,

@@ -185,6 +185,17 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         Conv2d widens this: an LDS tile of any length is zero-padded to whole K-steps, and a
  *         per-wave tile that is no multiple of 16 is rounded up to whole 16x16 atoms as long as
  *         that at most doubles the work (the overhang is computed and not stored).
+ *         Folding: a member that asks for more than a workgroup has is not scored 0 but run as serial
+ *         work, so that the search sees a slow member with its own place in the landscape: a per-wave
+ *         tile of more than 256 accumulators per lane is cut (a prime at a time along its longer side)
+ *         into sub-tiles that become tiles of waves of their own; a reduction slab too long for the LDS
+ *         is halved while it stays a multiple of 32; a workgroup tile too large for the LDS even then
+ *         (or for 1024 threads x 256 outputs on the scalar template) is cut into sub-tiles that the
+ *         workgroup computes one after another (Conv2d: along the channel side only); more than 16
+ *         waves: the workgroup runs the largest divisor of their number that is at most 16 and every
+ *         real wave takes the tiles of several waves in turn, each with the whole K loop.  opevo_plan
+ *         reports the tile, wave tile and threads the kernel really uses.  What still cannot run
+ *         (a pixel box too large for the LDS, staging registers, spills) stays invalid.
  *  TILE4X: TILE4 plus the two remaining parameter types of Sec. 3 as launch tunables.  The
  *         workgroups are launched as a one-dimensional grid and walk the grid axes (0 = N tiles,
  *         1 = M tiles, 2 = batch blocks of a BMM) in the order given by a PERMUTATION parameter
@@ -268,6 +279,10 @@ typedef struct {
     int32_t tile[3];       /* workgroup tile BM, BN, BK                                        */
     int32_t wave_tile[2];  /* per-wave tile                                                    */
     char    reason[96];    /* why invalid, else empty                                          */
+    int32_t sub_tiles[2];  /* folded members: sub-tiles of `tile` along M and N that a workgroup
+                              computes one after another (1, 1 otherwise): a workgroup owns
+                              sub_tiles[0] * tile[0] rows and sub_tiles[1] * tile[1] columns  */
+    int32_t wave_passes;   /* folded members: tiles every wave computes in turn (1 otherwise)  */
 } opevo_plan;
 
 /* Decode + validate (host only, no GPU): OPEVO_E_ILLEGAL if cfg is not in the space;
@@ -283,7 +298,11 @@ int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg,
  * no exec is done: a worker is then a fork of the caller that only serves compile requests
  * with the hipRTC the caller is bound to.  Workers keep no device file open.  Idempotent;
  * *n_running (may be NULL) = workers alive.  Without a pool every instantiation compiles in
- * the calling process.  opevo_compile_pool_kind: 1 executable workers, 0 forks, -1 no pool. */
+ * the calling process.  opevo_compile_pool_kind: 1 executable workers, 0 forks, -1 no pool.
+ * Start the pool before the first GPU call of the process, and never while another thread is
+ * compiling: executable workers use the newer compiler of the ROCm installation (their kernels
+ * are about a tenth faster), and a fork taken while a thread sits inside hipRTC can leave the
+ * child with that thread's locks held.  Fork-only pools are capped at 12 workers. */
 int opevo_compile_pool_start(int n_workers, int *n_running);
 int opevo_compile_pool_stop(void);
 int opevo_compile_pool_kind(int *kind);
@@ -296,7 +315,7 @@ int opevo_compile_pool_kind(int *kind);
  * unroll the schedule) makes this call return OPEVO_E_INVALID.  On every template, a kernel
  * that the compiler gave private scratch memory (register spills) makes its first launch /
  * timing return OPEVO_E_INVALID: it would be slow, it would break the load counting of path 3,
- * and spill code of a register-staged member was seen to lose part of a value.  opevo_tune
+ * and one spilling member of the register-staged template once gave wrong rows.  opevo_tune
  * scores both as invalid trials. */
 int opevo_kernel_build(const opevo_op *op, int variant, const int32_t *cfg,
                        opevo_kernel **out, double *compile_ms);
@@ -336,8 +355,8 @@ int opevo_kernel_launch(opevo_kernel *kernel, const void *a, const void *b, void
  * on its own.  warmup_ms > 0 extends the warm-up until that much GPU time has been spent
  * (at most 4000 launches): after idling the device needs tens of milliseconds to reach its
  * sustained clocks, and a sample taken earlier under-reports the kernel by up to a quarter.
- * timeout_ms > 0 gives scalar-template kernels a deadline of timeout_ms per
- * launch: one that is still running then winds down by itself (every workgroup leaves at its
+ * timeout_ms > 0 gives scalar-template kernels, and folded members of the register-staged MFMA
+ * templates (see TILE4), a deadline of timeout_ms per launch: one that is still running then winds down by itself (every workgroup leaves at its
  * next K slab) and the call returns OPEVO_E_INVALID; 0 = no deadline.  Synchronises `stream`. */
 int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *c, void *stream,
                       int warmup, double warmup_ms, int launches_per_sample, int samples,

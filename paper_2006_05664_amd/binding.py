@@ -43,7 +43,8 @@ class opevo_param_desc(C.Structure):
 class opevo_plan(C.Structure):
     _fields_ = [("status", C.c_int32), ("path", C.c_int32), ("grid", C.c_int32 * 3), ("block", C.c_int32),
                 ("lds_bytes", C.c_int32), ("acc_per_lane", C.c_int32), ("tile", C.c_int32 * 3),
-                ("wave_tile", C.c_int32 * 2), ("reason", C.c_char * 96)]
+                ("wave_tile", C.c_int32 * 2), ("reason", C.c_char * 96), ("sub_tiles", C.c_int32 * 2),
+                ("wave_passes", C.c_int32)]
 
 
 class opevo_tune_args(C.Structure):

@@ -1,6 +1,6 @@
 // Cache of compiled code objects.
 //
-// A trial is "compile the template under configuration x, run it, time it" (Sec. 3); the compile
+// A trial compiles the template under configuration x, runs it and times it (Sec. 3); the compile
 // is by far the longest of the three.  Runs of Alg. 1 that differ only in the seed, or sweeps over
 // q and lambda, revisit many configurations, and so does a repeated tuning job in a new process.
 // The cache maps (template text, constants, compile options) to the gfx950 code object: in memory

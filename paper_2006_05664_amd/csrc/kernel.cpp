@@ -98,11 +98,12 @@ int load_kernel(opevo_kernel *k, bool refuse_spills)
     // A member whose kernel needs private scratch memory (register spills) is not run, on any
     // template.  The direct-to-LDS template counts its own outstanding loads (s_waitcnt vmcnt(n)):
     // spill stores would sit on the same counter and may complete out of order with loads, so a
-    // count could be reached while a slab is still in flight.  And on the register-staged template
-    // a member that filled all 512 registers was compiled into code that spills three dwords of a
-    // 16-byte staging value to scratch, parks the fourth in an accumulation register and never
-    // moves it back before the value is stored to LDS: wrong rows in the result, found by the
-    // parity gate.  Such members are slow anyway; they score as invalid (fitness 0).
+    // count could be reached while a slab is still in flight.  On the register-staged template one
+    // spilling member (all 512 registers in use, 20 bytes of scratch) once failed the parity gate
+    // with 4 wrong rows in every 128 while its sibling with other spill choices was right; why is
+    // not established (the template is not cleared by that, nor is the compiler blamed).  Spilling
+    // members are slow in any case; they score as invalid (fitness 0) and stay a regression case
+    // of the GPU tests (either refused or right).
     if (refuse_spills && k->scratch_bytes > 0)
         return fail(OPEVO_E_INVALID, "member spills %d bytes of registers per lane", k->scratch_bytes);
     return OPEVO_OK;
@@ -140,7 +141,8 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
     if (samples < 1) return fail(OPEVO_E_ARG, "kernel_time: samples must be >= 1");
     if (int rc = load_kernel(k)) return rc;
     unsigned long long *ctl = nullptr;
-    if (timeout_ms > 0.0 && k->plan.path == 0)
+    // the scalar template and folded members of the register-staged templates honour a deadline
+    if (timeout_ms > 0.0 && k->plan.path != 3)
         if (int rc = deadline_ctl(&ctl)) return rc;
     // samples + 1 events: the samples run back to back, without a host round trip (and an idle
     // GPU) between them; only the first, estimating launch is followed by a synchronisation

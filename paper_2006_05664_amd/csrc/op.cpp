@@ -184,6 +184,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                        variant == OPEVO_TILE4C || variant == OPEVO_TILE4T);
     int bpack = 0;                         // MatMul, TILE4T: 1 = second operand transposed to [N][K] by a pre-pass
     int layout = 0;                        // Conv2d, TILE4C: 1 = channels-last operands (pre-pass)
+    int64_t subm = 1, subn = 1;            // sub-tiles a workgroup computes one after another (folded members)
     int64_t ksplit = 1;
     int64_t box[6] = {1, 1, 1, 1, 1, 1};   // C_in, H_k, W_k as (boxes, box extent) pairs
     bool tap_box = false;
@@ -234,6 +235,54 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         }
         BM = WM * TM; BN = WN * TN;
     }
+    // ---- members that ask for more than a workgroup has are folded into serial work instead of scoring 0
+    // (the search then sees a slow member with its own place in the landscape, not a hole; Sec. 4.2 keeps
+    // zero fitness for what cannot run at all):
+    //  * a per-wave tile that needs more than 256 accumulators per lane (or, for a member with more than
+    //    16 waves, more than its occupancy leaves) is cut along its longer side (a prime at a time) into
+    //    sub-tiles, each of which becomes the tile of a wave of its own;
+    //  * a reduction slab too long for the LDS is halved (twice as many steps) while it stays a
+    //    multiple of 32;
+    //  * more than 16 waves (below): the workgroup runs the largest divisor of their number that fits,
+    //    and every real wave takes the tiles of several waves one after another, each with the whole K loop.
+    if (four_level) {
+        auto smallest_prime = [](int64_t n) { for (int64_t q = 2; q * q <= n; ++q) if (n % q == 0) return q; return n; };
+        // The registers a lane may use depend on how many waves share a SIMD (512 for one, 256 for two,
+        // 128 for four): a member that is folded anyway gets wave tiles that leave room for fragments
+        // and staging next to the accumulators at the occupancy it will run at.
+        auto real_waves = [&](int64_t v) { for (int64_t dv = kMaxThreads / 64; dv > 1; --dv) if (v % dv == 0) return dv; return int64_t(1); };
+        auto acc_cap = [&]() {
+            const int64_t per_simd = (real_waves(WM * WN) + 3) / 4;
+            return std::min<int64_t>(kMaxAcc, 512 / per_simd / 2 - 8);   // half the registers: the other half holds two slabs in flight and the fragments
+        };
+        const bool refold = TM * TN > 64 * kMaxAcc || WM * WN > kMaxThreads / 64;
+        while (refold && TM * TN > 64 * acc_cap() && TM * TN > 1) {
+            const bool cut_m = (TM >= TN && TM > 1) || TN == 1;
+            int64_t &T = cut_m ? TM : TN, &W = cut_m ? WM : WN, &F = cut_m ? FM : FN;
+            const int64_t q = smallest_prime(T);
+            T /= q; W *= q;
+            F = std::gcd(F, T);
+        }
+        //  * a workgroup tile too large for the LDS even with the shortest slab (or, on the scalar template,
+        //    for 1024 threads with 256 outputs each) is cut, a prime at a time along its longer side, into
+        //    sub-tiles that the workgroup computes one after another (SUBM x SUBN of them).
+        const int elem = op.dtype == OPEVO_F32 ? 4 : 2;
+        const int stages = (flagv && ksteps > 1) ? 2 : 1;
+        auto lds_need = [&]() { return (BM + BN) * std::max<int64_t>((BK + kPad) * elem * stages, BK * 4); };
+        const int64_t lds_cap = kMaxLds - 16;   // room for the deadline flag word of folded members
+        while (lds_need() > lds_cap && BK % 64 == 0 && !tap_box) { BK /= 2; ksteps *= 2; }
+        // (the scalar template: 1024 threads have 128 registers per lane each; 16 outputs per thread fit with its unrolled loop)
+        const int64_t out_cap = BM * BN > int64_t(kMaxThreads) * kMaxAcc ? int64_t(kMaxThreads) * 16 : INT64_MAX;
+        while (lds_need() > lds_cap || BM * BN > out_cap) {
+            // a convolution's column block is a box of pixels: only its channel side is cut
+            const bool cut_m = op.kind == OPEVO_CONV2D || BM >= BN;
+            int64_t &W = cut_m ? WM : WN, &T = cut_m ? TM : TN, &F = cut_m ? FM : FN, &S = cut_m ? subm : subn;
+            if (W * T == 1) break;
+            if (W > 1) { const int64_t q = smallest_prime(W); W /= q; S *= q; }
+            else { const int64_t q = smallest_prime(T); T /= q; S *= q; F = std::gcd(F, T); }
+            BM = WM * TM; BN = WN * TN;
+        }
+    }
     // extended variant: launch order and group width
     const bool linear = (variant == OPEVO_TILE4X);
     int order[3] = {0, 1, 2};
@@ -262,6 +311,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     // loads: `rows_b` rows of BK K-contiguous elements for the second operand (0: it is stored [K][N]).
     auto dlds_stages = [&](int64_t rows_a, int64_t rows_b, bool a_km_rows) -> int {
         const int64_t nw = WM * WN;
+        if (subm * subn > 1) return 0;   // folded members stay on the register-staged template
         if (64 * nw > kMaxThreads || !(BK == 32 || BK == 64 || BK == 128)) return 0;
         const int64_t a_bytes = rows_a * BK * 2, b_bytes = (rows_b ? rows_b : BN) * BK * 2;
         if (a_bytes % (1024 * nw) != 0 || b_bytes % (1024 * nw) != 0) return 0;
@@ -342,8 +392,16 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     // needs M % 8 == 0 and LDS staging; other members run on the scalar template
     if (op.trans_a && (path == 1 || path == 2) && (op.M % 8 != 0 || !stage_lds)) path = 0;
 
-    int64_t NT;
-    if (four_level) NT = 64 * WM * WN;
+    int64_t NT, nwr = WM * WN;   // nwr: waves the workgroup really runs
+    if (four_level) {
+        if (path == 0) nwr = std::min<int64_t>(nwr, kMaxThreads / 64);   // the scalar template deals outputs round-robin to any number of threads
+        else while (nwr > kMaxThreads / 64) {      // largest divisor of WM * WN that fits
+            int64_t best = 1;
+            for (int64_t dv = kMaxThreads / 64; dv >= 1; --dv) if ((WM * WN) % dv == 0) { best = dv; break; }
+            nwr = best;
+        }
+        NT = 64 * nwr;
+    }
     else {
         NT = ((BM * BN + 63) / 64) * 64;
         if (NT > 256) NT = 256;
@@ -369,11 +427,13 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     p.acc_per_lane = int32_t(acc > INT32_MAX ? INT32_MAX : acc);
     p.tile[0] = int32_t(BM); p.tile[1] = int32_t(BN); p.tile[2] = int32_t(BK);
     p.wave_tile[0] = int32_t(four_level ? TM : BM); p.wave_tile[1] = int32_t(four_level ? TN : BN);
+    p.sub_tiles[0] = int32_t(subm); p.sub_tiles[1] = int32_t(subn);
+    p.wave_passes = int32_t(four_level && nwr > 0 ? (WM * WN) / nwr : 1);
 
     // ---- black-box constraints made explicit: such members get fitness 0 (Sec. 4.2)
     if (NT > kMaxThreads) invalid(p, "%ld threads per workgroup > %ld", long(NT), long(kMaxThreads));
     else if (acc > kMaxAcc) invalid(p, "%ld accumulators per lane > %ld", long(acc), long(kMaxAcc));
-    else if (lds + (path == 0 ? 16 : 0) > kMaxLds)   // the scalar template adds a static flag word
+    else if (lds + ((path == 0 || subm * subn * ((WM * WN) / std::max<int64_t>(nwr, 1)) > 1) ? 16 : 0) > kMaxLds)   // the deadline flag word of the scalar template and of folded members
         invalid(p, "%ld bytes of LDS > %ld", long(lds), long(kMaxLds));
     else if (!linear && (m1 > 65535 || b1 > 65535)) invalid(p, "grid y/z %ld x %ld > 65535", long(m1), long(b1));
     else if (linear && n_blocks > INT32_MAX) invalid(p, "%ld workgroups in a one-dimensional grid", long(n_blocks));
@@ -410,6 +470,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         D << " -DATOM=" << (path == 2 ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
           << " -DNSTAGE=" << nstage << " -DNSTG=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
+        if (nwr != WM * WN) D << " -DNWR=" << nwr;
+    }
+    if (subm * subn > 1) {
+        D << " -DSUBM=" << subm << " -DSUBN=" << subn;
     }
     if (op.kind == OPEVO_CONV2D) {
         D << " -DCIN=" << op.cin << " -DHIN=" << op.hin << " -DWIN=" << op.win << " -DHK=" << op.hk

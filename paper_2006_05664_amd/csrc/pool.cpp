@@ -101,6 +101,9 @@ int pool_start(int n)
     signal(SIGPIPE, SIG_IGN);
     const std::string exe = gpu_is_open() ? std::string() : worker_executable();
     g_kind = exe.empty() ? 0 : 1;
+    // Fork-only workers inherit the open device descriptors until their first action (closing them)
+    // has run: keep their number below what a GPU machine allows to hold the device at one time.
+    if (exe.empty() && n > 12) n = 12;
     for (int i = 0; i < n; ++i) {
         int req[2], resp[2];
         if (pipe(req) != 0) break;

@@ -24,6 +24,12 @@
 #ifndef KSPLIT
 #define KSPLIT 1   // MatMul, Conv2d: workgroups along grid z that share one output tile, each reducing its own K range
 #endif
+#ifndef SUBM
+// A workgroup tile too large for one pass (LDS, accumulators) is computed as SUBM x SUBN sub-tiles of
+// BM x BN, one after another: workgroup (n, m) owns rows [m*SUBM*BM, +SUBM*BM) and the columns alike.
+#define SUBM 1
+#define SUBN 1
+#endif
 #define OP_MATMUL 0
 #define OP_BMM 1
 #define OP_CONV 2

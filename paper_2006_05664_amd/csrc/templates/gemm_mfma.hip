@@ -74,6 +74,10 @@ typedef f32x4 acc_t;
 // Atoms per wave tile.  A Conv2d wave tile need not be a multiple of the atom (pixel tiles come
 // from factors of 55, 27, ...): the last atom row / column then hangs over the tile; what it
 // computes from its neighbours' rows (or from whatever follows the stage in LDS) is never stored.
+#ifndef NWR
+#define NWR (WM * WN)   // waves the workgroup really runs
+#endif
+constexpr int NPASS = (WM * WN) / NWR;
 constexpr int MI = (TM + ATOM - 1) / ATOM, NI = (TN + ATOM - 1) / ATOM;
 constexpr bool RAGGED_M = TM % ATOM != 0, RAGGED_N = TN % ATOM != 0;
 constexpr int FMI = (!RAGGED_M && FM % ATOM == 0) ? FM / ATOM : 1;   // atoms per basic tile
@@ -440,22 +444,44 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As
 
 extern "C" __global__ __launch_bounds__(NT)
 void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
-                  unsigned long long *ctl /* deadline control, used by the scalar template only */)
+                  unsigned long long *ctl /* deadline control: folded members only (the scalar template always honours it) */)
 {
     extern __shared__ __attribute__((aligned(16))) u16 smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane % ATOM, lk = (lane / ATOM) * 8;
     const BlockId bid = block_id();
-    const int m0 = bid.m * BM;
 #if OP == OP_CONV
     const ColBlock cb = col_block(bid.n);
-#else
-    const int n0 = bid.n * BN;
 #endif
 
-    for (int bi = 0; bi < BATCH_INNER; ++bi) {
+    // A configuration may ask for more waves than a workgroup can hold (WM * WN > 16).  The workgroup
+    // then runs NWR of them (a divisor of WM * WN), and every real wave takes the tiles of
+    // WM * WN / NWR waves one after another, each with the whole K loop: slow, and the same result.
+#if SUBM * SUBN * NPASS > 1
+    // Folded members can run for seconds (few workgroups, many passes): like the scalar template they
+    // honour the harness's deadline, checked once per pass by thread 0 and passed on through LDS so
+    // that the whole workgroup leaves together.
+    __shared__ int expired;
+    if (tid == 0) expired = 0;
+#endif
+    for (int bi = 0; bi < BATCH_INNER; ++bi)
+    for (int sub = 0; sub < SUBM * SUBN; ++sub)
+    for (int pass = 0; pass < NPASS; ++pass) {
+#if SUBM * SUBN * NPASS > 1
+        if (tid == 0 && ctl && ctl[1] != 0 && wall_clock64() - ctl[0] > ctl[1]) {
+            expired = 1;
+            ctl[2] = 1;
+        }
+        __syncthreads();
+        if (expired) return;
+#endif
+        const int vwave = wave + pass * NWR;
+        const int wm = vwave / WN, wn = vwave % WN;
+        const int m0 = (bid.m * SUBM + sub / SUBN) * BM;
+#if OP != OP_CONV
+        const int n0 = (bid.n * SUBN + sub % SUBN) * BN;
+#endif
 #if OP == OP_CONV
         const u16 *Ab = A, *Bb = B;
 #else
@@ -508,7 +534,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         // after them.  Global latency therefore has two K steps to hide in.
         Slab slab1;
         constexpr int KPAIRS = KSTEPS / 2 * 2;
-        if (bi > 0) __syncthreads();
+        if (bi > 0 || sub > 0 || pass > 0) __syncthreads();
         LOAD_INTO(slab, 0);
         if (KSTEPS > 1) LOAD_INTO(slab1, 1);
         store_slab(slab, As, Bs, tid);

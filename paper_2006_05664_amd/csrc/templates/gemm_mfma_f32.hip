@@ -28,6 +28,10 @@ typedef f32x16 acc_t;
 #ifndef BKP
 #define BKP BK
 #endif
+#ifndef NWR
+#define NWR (WM * WN)   // waves the workgroup really runs
+#endif
+constexpr int NPASS = (WM * WN) / NWR;
 constexpr int MI = (TM + 31) / 32, NI = (TN + 31) / 32;
 #if OP == OP_CONV
 // rows of A / columns of B that the last atoms of the last waves may read past the tile
@@ -178,23 +182,45 @@ __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const float *
 
 extern "C" __global__ __launch_bounds__(NT)
 void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float *__restrict__ C,
-                 unsigned long long *ctl /* deadline control, used by the scalar template only */)
+                 unsigned long long *ctl /* deadline control: folded members only (the scalar template always honours it) */)
 {
     extern __shared__ __attribute__((aligned(16))) float smem_f32[];
     float *As = smem_f32, *Bs = smem_f32 + NSTAGE * A_STAGE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
     const BlockId bid = block_id();
-    const int m0 = bid.m * BM;
 #if OP == OP_CONV
     const ColBlock cb = col_block(bid.n);
 #define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, cb, CONV_KBASE(bid) + (kt) * BK, tid)
 #else
-    const int n0 = bid.n * BN;
 #define LOAD_SLAB(S, kt) load_slab(S, Ab, Bb, m0, n0, (kt) * BK, tid)
 #endif
 
-    for (int bi = 0; bi < BATCH_INNER; ++bi) {
+    // more waves asked for than a workgroup holds: NWR real waves take the tiles of WM * WN / NWR waves each,
+    // one after another, each with the whole K loop
+#if SUBM * SUBN * NPASS > 1
+    // Folded members can run for seconds (few workgroups, many passes): like the scalar template they
+    // honour the harness's deadline, checked once per pass by thread 0 and passed on through LDS so
+    // that the whole workgroup leaves together.
+    __shared__ int expired;
+    if (tid == 0) expired = 0;
+#endif
+    for (int bi = 0; bi < BATCH_INNER; ++bi)
+    for (int sub = 0; sub < SUBM * SUBN; ++sub)
+    for (int pass = 0; pass < NPASS; ++pass) {
+#if SUBM * SUBN * NPASS > 1
+        if (tid == 0 && ctl && ctl[1] != 0 && wall_clock64() - ctl[0] > ctl[1]) {
+            expired = 1;
+            ctl[2] = 1;
+        }
+        __syncthreads();
+        if (expired) return;
+#endif
+        const int vwave = wave + pass * NWR;
+        const int wm = vwave / WN, wn = vwave % WN;
+        const int m0 = (bid.m * SUBM + sub / SUBN) * BM;
+#if OP != OP_CONV
+        const int n0 = (bid.n * SUBN + sub % SUBN) * BN;
+#endif
 #if OP == OP_CONV
         const float *Ab = A, *Bb = B;   // kernel tensor [M][K], image
 #elif KSPLIT > 1   // MatMul, reduction split over grid z: this workgroup owns K range [bid.b * KSTEPS * BK, + KSTEPS * BK)
@@ -218,7 +244,7 @@ void KERNEL_NAME(const float *__restrict__ A, const float *__restrict__ B, float
         Slab slab;
 #if NSTAGE == 2
         // every wave has left the previous batch's last slab before the stages are written again
-        if (bi > 0) __syncthreads();
+        if (bi > 0 || sub > 0 || pass > 0) __syncthreads();
         LOAD_SLAB(slab, 0);
         store_slab(slab, As, Bs, tid);
         __syncthreads();

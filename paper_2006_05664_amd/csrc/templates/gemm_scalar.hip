@@ -31,16 +31,18 @@ void KERNEL_NAME(const in_t *__restrict__ A, const in_t *__restrict__ B, float *
     const int tid = threadIdx.x;
     if (tid == 0) expired = 0;
     const BlockId bid = block_id();
-    const int m0 = bid.m * BM;
     constexpr int E = (BM * BN + NT - 1) / NT;
 
 #if OP == OP_CONV
     const ColBlock cb = col_block(bid.n);
-#else
-    const int n0 = bid.n * BN;
 #endif
 
-    for (int bi = 0; bi < BATCH_INNER; ++bi) {
+    for (int bi = 0; bi < BATCH_INNER; ++bi)
+    for (int sub = 0; sub < SUBM * SUBN; ++sub) {
+        const int m0 = (bid.m * SUBM + sub / SUBN) * BM;
+#if OP != OP_CONV
+        const int n0 = (bid.n * SUBN + sub % SUBN) * BN;
+#endif
 #if OP == OP_CONV
         const in_t *Ab = A;   // kernel tensor [M][K]
 #else

@@ -111,10 +111,13 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
             Child &c = kids[i];
             double tflops = 0.0, ms = 0.0;
             int status = c.status;
+            // the build ran on a worker thread: its message becomes this thread's last error, so that the
+            // caller of opevo_tune (and the trace) can read why the latest failed member failed
+            if (status != OPEVO_OK && !c.error.empty()) set_error("%s", c.error.c_str());
             if (trace) {
-                std::fprintf(stderr, "[opevo_tune] trial %d %s: built (status %d, %.0f ms)%s\n", done + i,
+                std::fprintf(stderr, "[opevo_tune] trial %d %s: built (status %d, %.0f ms)%s%s\n", done + i,
                              c.kernel ? c.kernel->name.c_str() : "-", status, c.compile_ms,
-                             status == OPEVO_OK ? ", running" : "");
+                             status == OPEVO_OK ? ", running" : ": ", status == OPEVO_OK ? "" : c.error.c_str());
                 std::fflush(stderr);
             }
             if (status == OPEVO_OK && rc_final == OPEVO_OK) {

@@ -52,7 +52,7 @@ def main() -> int:
     da, db = synth.to_device(a_host, dtype), synth.to_device(b_host, dtype)
     dc = torch.empty(P.opevo_op_sizes(op)[2], dtype=torch.float32, device="cuda:0")
     stream = torch.cuda.current_stream().cuda_stream
-    timeout_ms = max(10.0, 300.0 * flops / (2.0 * 8192.0 ** 3))
+    timeout_ms = max(10.0, 100.0 * flops / (2.0 * 8192.0 ** 3))
     seeds = [int(s) for s in args.seeds.split(",")]
     marks = [m for m in (50, 100, 200, 300, 400, 500, 750, 1000) if m <= args.trials]
 

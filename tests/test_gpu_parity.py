@@ -917,6 +917,75 @@ def test_split_reduction_launch_can_be_captured_in_a_hip_graph(torch_cuda):
     w.close()
 
 
+# ------------------------------------------------------------------ folded members: serial sub-tiles, wave passes, halved slabs
+def test_folded_members_match_the_oracle(torch_cuda):
+    """Members that ask for more waves, accumulators or LDS than a workgroup has are folded into serial
+    work (sub-tiles of the workgroup tile one after another, several wave tiles per real wave, halved
+    slabs).  Hand-picked ones on every register-staged path and the scalar template, seeded random ones,
+    the fp32 template, a convolution (cut along channels), a BMM, and the deadline of a folded member."""
+    def folded(w, variant, cfg):
+        plan = P.opevo_kernel_plan(w.op, variant, cfg)
+        return plan.status == P.OPEVO_OK and (plan.wave_passes > 1 or plan.sub_tiles[0] * plan.sub_tiles[1] > 1)
+
+    def random_folded(w, variant, n, seed, paths):
+        sp, rng = P.opevo_op_space(w.op, variant), P.opevo_rng_create(seed)
+        got, per = [], {p: 0 for p in paths}
+        for _ in range(100000):
+            cfg = P.opevo_space_random(sp, rng)
+            plan = P.opevo_kernel_plan(w.op, variant, cfg)
+            if not folded(w, variant, cfg) or plan.path not in per or per[plan.path] >= -(-n // len(paths)):
+                continue
+            # keep the serial work small enough for a test: at most 64 tile passes per workgroup
+            if plan.wave_passes * plan.sub_tiles[0] * plan.sub_tiles[1] > 64:
+                continue
+            per[plan.path] += 1
+            got.append(cfg)
+            if len(got) >= n:
+                break
+        P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+        return got
+
+    V = P.OPEVO_TILE4
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
+    cases = [("32 x 32 waves of 16 x 32: 16 real waves, 64 passes", [1, 32, 1, 16, 1, 32, 1, 32, 16, 64, 1], 2),
+             ("one wave asked to hold 512 x 512, single stage", [1, 1, 8, 64, 2, 1, 8, 64, 16, 64, 0], 1),
+             ("1024-deep slab, halved to 64 (then a direct-to-LDS member)", [2, 2, 2, 64, 8, 2, 2, 32, 1, 1024, 1], 3),
+             ("32 waves of 32 x 64, single stage", [2, 8, 1, 32, 4, 4, 2, 32, 32, 32, 0], 1),
+             ("scalar, 512 x 1024 in one workgroup", [1, 64, 1, 8, 1, 8, 16, 8, 64, 16, 0], 0)]
+    for label, cfg, path in cases:
+        plan = P.opevo_kernel_plan(w.op, V, cfg)
+        assert plan.status == P.OPEVO_OK and plan.path == path and (folded(w, V, cfg) or plan.tile[2] < cfg[9]), (label, plan.path, plan.reason)
+        w.check(V, cfg, label)
+    for cfg in random_folded(w, V, 18, 2020, (0, 1, 2)):
+        w.check(V, cfg, "random")
+    # the deadline: a folded member on one workgroup runs for tens of milliseconds; with 1 ms allowed it must
+    # wind down by itself and be reported invalid, and the next launch of another kernel must be fine
+    slow = [1, 32, 1, 16, 1, 32, 1, 32, 16, 64, 1]
+    kernel, _ = P.opevo_kernel_build(w.op, V, slow)
+    ms, _ = P.opevo_kernel_time(kernel, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, warmup=1, samples=1, warmup_ms=0.0)
+    if ms > 2.0:
+        with pytest.raises(P.OpevoError) as ei:
+            P.opevo_kernel_time(kernel, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), w.stream, warmup=1, samples=1,
+                                timeout_ms=ms / 4, warmup_ms=0.0)
+        assert ei.value.status == P.OPEVO_E_INVALID and "deadline" in ei.value.message
+    P.opevo_kernel_destroy(kernel)
+    w.check(V, cases[1][1], "after an expired deadline")
+    w.close()
+    w = Workload(torch_cuda, "matmul", (256, 384, 512), "f32", 78)
+    for cfg in random_folded(w, V, 6, 2021, (4,)):
+        w.check(V, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "bmm", (24, 128, 64, 128), "bf16", 79)
+    for cfg in random_folded(w, V, 6, 2022, (0, 1, 2)):
+        w.check(V, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (4, 32, 12, 12, 512, 3, 3, 1, 1), "bf16", 80)      # 512 output channels: tiles cut along channels
+    for V2 in (P.OPEVO_TILE4, P.OPEVO_TILE4C):
+        for cfg in random_folded(w, V2, 8, 2023, (0, 1, 2)):
+            w.check(V2, cfg, "random")
+    w.close()
+
+
 # ------------------------------------------------------------------ harness pieces
 def test_compare_f32_matches_numpy(torch_cuda):
     torch = torch_cuda
