@@ -79,6 +79,8 @@ def main() -> int:
                     help="comma-separated configuration to measure the roofline object on instead of this run's "
                          "best (for hardware-counter runs, whose per-dispatch overhead perturbs the timings "
                          "that steer the search)")
+    ap.add_argument("--no-build-ahead", action="store_true",
+                    help="do not build a guess of the next generation on spare compile workers while the current one is timed")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
                          "known-size reference that scales the HBM counters of a profiler run")
@@ -91,7 +93,9 @@ def main() -> int:
     import numpy as np
     import paper_2006_05664_amd as P
     from paper_2006_05664_amd import synth
-    P.opevo_compile_pool_start(8)          # 8 compile workers (Sec. 6), forked before the GPU is touched
+    # 8 compile workers for the generation being evaluated (Sec. 6) and 8 that build a guess of the next one
+    # ahead of time; all forked before the GPU is touched
+    P.opevo_compile_pool_start(8 if args.no_build_ahead else 16)
     pool_kind = P.opevo_compile_pool_kind()
     import torch
     from oracle import tensor as oracle_tensor   # cpu_baseline leg and reference rows only
@@ -174,7 +178,7 @@ def main() -> int:
                             n_ref_rows=int(rows.size) if rows is not None else 0, ref_row_len=row_len,
                             trials=trials, lambda_=8, rho=8, q=0.5, seed=seed, compile_threads=8,
                             warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=timeout_ms, progress_every=100,
-                            tol_max_scaled=tol[0], tol_rel_fro=tol[1])
+                            tol_max_scaled=tol[0], tol_rel_fro=tol[1], speculate_threads=0 if args.no_build_ahead else 8)
 
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
@@ -263,12 +267,13 @@ def main() -> int:
                    "step": "one launch of the best-found kernel: %d untimed launches + 25 ms clock warm-up, then the median of 3 "
                            "groups of %d back-to-back launches between HIP events" % (max(1, args.warmup), max(1, args.steps)),
                    "ms_per_trial": round(wall / max(1, res["n_trials"]) * 1e3, 2),
-                   "compile_pool": {1: "8 worker executables (hipRTC of /opt/rocm)", 0: "8 forked workers (hipRTC of the process)",
-                                    -1: "none: in-process hipRTC"}.get(pool_kind, str(pool_kind)),
+                   "compile_pool": {1: "%d worker executables (hipRTC of /opt/rocm)", 0: "%d forked workers (hipRTC of the process)",
+                                    -1: "none (%d asked for): in-process hipRTC"}.get(pool_kind, "%d") % (8 if args.no_build_ahead else 16),
                    "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {v: k for k, v in names.items()}[variant],
                    "best_cfg": [int(x) for x in res["best_cfg"]], "frac_of_peak": round(best / PEAK_TFLOPS[dtype], 4),
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),
+                   "n_built_ahead": int(res["n_built_ahead"]),
                    "n_invalid": int(res["n_invalid"]), "n_compile_fail": int(res["n_compile_fail"]),
                    "n_parity_fail": int(res["n_parity_fail"]), "parity_failures": parity_failures, "parity_gate": sample,
                    "timing": "per trial: 25 ms warm-up, then median of 5 back-to-back samples of >= 200 us; inputs cache-warm"},

@@ -433,6 +433,12 @@ typedef struct {
                                    (kernel name = configuration), so that the log of a run that
                                    died names what was on the GPU                                   */
     int32_t     mutation;       /* as opevo_tuner_set_mutation: 0 the paper's q-random walk, 1 control */
+    int32_t     speculate_threads; /* > 0: while a generation is compiled and timed, that many further host
+                                   threads build the generation Alg. 1 would ask for next if none of the
+                                   current children made the top-lambda (a copy of the tuner is asked; the
+                                   run's own tuner and its trajectory are untouched).  A guessed kernel is
+                                   used when the run really asks for that configuration, else discarded.
+                                   Needs as many idle compile workers; 0: off                            */
 } opevo_tune_args;
 
 typedef struct {
@@ -442,6 +448,7 @@ typedef struct {
     double  best_ms;
     int32_t n_invalid, n_compile_fail, n_parity_fail;
     double  wall_s, compile_s, run_s;   /* total, hipRTC (wall, overlapped), GPU measurement     */
+    int32_t n_built_ahead;     /* trials whose kernel had been built ahead of time (speculate_threads)  */
 } opevo_tune_result;
 
 /* Runs Alg. 1 on the GPU: ask -> instantiate the generation's children concurrently ->

@@ -57,14 +57,14 @@ class opevo_tune_args(C.Structure):
                 ("cfg_log", C.POINTER(C.c_int32)), ("fitness_log", C.POINTER(C.c_double)),
                 ("status_log", C.POINTER(C.c_int32)), ("compile_ms_log", C.POINTER(C.c_double)),
                 ("run_ms_log", C.POINTER(C.c_double)), ("wall_s_log", C.POINTER(C.c_double)),
-                ("progress_every", C.c_int32), ("mutation", C.c_int32)]
+                ("progress_every", C.c_int32), ("mutation", C.c_int32), ("speculate_threads", C.c_int32)]
 
 
 class opevo_tune_result(C.Structure):
     _fields_ = [("n_trials", C.c_int32), ("best_trial", C.c_int32), ("best_tflops", C.c_double),
                 ("best_ms", C.c_double), ("n_invalid", C.c_int32), ("n_compile_fail", C.c_int32),
                 ("n_parity_fail", C.c_int32), ("wall_s", C.c_double), ("compile_s", C.c_double),
-                ("run_s", C.c_double)]
+                ("run_s", C.c_double), ("n_built_ahead", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -557,7 +557,7 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                trials: int = 500, lambda_: int = 8, rho: int = 8, q: float = 0.5, seed: int = 0,
                compile_threads: int = 8, warmup: int = 3, launches_per_sample: int = 0, samples: int = 5,
                warmup_ms: float = 25.0, trial_timeout_ms: float = 0.0, tol_max_scaled: float = 2e-2, tol_rel_fro: float = 5e-3,
-               progress_every: int = 0, mutation: int = 0) -> dict:
+               progress_every: int = 0, mutation: int = 0, speculate_threads: int = 0) -> dict:
     """Runs Alg. 1 on the GPU; returns the result struct fields, the best configuration and the
     per-trial logs as numpy arrays."""
     space = opevo_op_space(op, variant)
@@ -575,7 +575,8 @@ def opevo_tune(op, variant: int, a: int, b: int, c: int, ref: Optional[int] = No
                            warmup_ms=warmup_ms, trial_timeout_ms=trial_timeout_ms, tol_max_scaled=tol_max_scaled, tol_rel_fro=tol_rel_fro,
                            cfg_log=_ip(logs["cfg"]), fitness_log=_dp(logs["fitness"]),
                            status_log=_ip(logs["status"]), compile_ms_log=_dp(logs["compile_ms"]),
-                           run_ms_log=_dp(logs["run_ms"]), wall_s_log=_dp(logs["wall_s"]), progress_every=progress_every, mutation=mutation)
+                           run_ms_log=_dp(logs["run_ms"]), wall_s_log=_dp(logs["wall_s"]), progress_every=progress_every, mutation=mutation,
+                           speculate_threads=speculate_threads)
     best = np.zeros(w, dtype=np.int32)
     res = opevo_tune_result()
     _check(lib.opevo_tune(op, variant, C.byref(args), _ip(best), C.byref(res)))

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <mutex>
 #include <thread>
 #include <vector>
@@ -30,6 +31,46 @@ double seconds_since(std::chrono::steady_clock::time_point t0)
 {
     return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
 }
+
+// Kernels of the NEXT generation, built ahead of time while this generation is compiled and timed.
+// Alg. 1 chooses the next children from the top-lambda of everything evaluated so far; late in a run
+// most generations leave that set as it is, and then the next children follow from the tuner's state
+// alone.  So the run asks a COPY of the tuner -- told this generation's children with fitness 0, i.e.
+// "none of them makes the top-lambda" -- for its next children and builds those on spare compile
+// workers.  When the real tuner later asks for a configuration that was built ahead, the kernel is
+// taken from here; every other guess is thrown away.  The real tuner never sees any of this: the
+// trajectory is the one Alg. 1 takes without it.
+struct Ahead {
+    std::mutex mu;
+    std::condition_variable cv;
+    int width = 0;
+    std::vector<int32_t> cfgs;          // n * width
+    std::vector<Child> kids;
+    std::vector<char> taken;
+    std::atomic<int> next{0};
+    std::vector<std::thread> threads;
+
+    int find(const int32_t *cfg) const
+    {
+        for (size_t i = 0; i < kids.size(); ++i)
+            if (!taken[i] && std::memcmp(cfgs.data() + i * width, cfg, sizeof(int32_t) * width) == 0) return int(i);
+        return -1;
+    }
+    bool all_built()
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        for (const Child &c : kids) if (!c.done) return false;
+        return true;
+    }
+    // joins the builders and frees what nobody took
+    void finish()
+    {
+        for (auto &t : threads) t.join();
+        threads.clear();
+        for (size_t i = 0; i < kids.size(); ++i)
+            if (!taken[i] && kids[i].kernel) { opevo_kernel_destroy(kids[i].kernel); kids[i].kernel = nullptr; }
+    }
+};
 
 }  // namespace
 
@@ -70,6 +111,8 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
     std::vector<double> fit(gen_cap);
     int done = 0, rc_final = OPEVO_OK;
     double best = 0.0;
+    std::shared_ptr<Ahead> ahead;                 // the guess for the generation that comes next
+    std::vector<std::shared_ptr<Ahead>> stale;    // older guesses, joined and freed at the end
     // OPEVO_TUNE_TRACE=1 in the environment: one line on stderr per trial, before its kernel runs,
     // so that the log of a run that died names the configuration that was on the GPU
     const char *trace_env = std::getenv("OPEVO_TUNE_TRACE");
@@ -85,10 +128,52 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
         std::condition_variable cv;
         std::atomic<int> next(0);
         const auto t_compile = std::chrono::steady_clock::now();
+        // children that were built ahead during the previous generation (possibly still being built)
+        std::vector<int> from_ahead(n, -1);
+        std::shared_ptr<Ahead> prev = ahead;
+        if (prev)
+            for (int i = 0; i < n; ++i) {
+                const int j = prev->find(cfgs.data() + size_t(i) * w);
+                if (j >= 0) { from_ahead[i] = j; prev->taken[j] = 1; }
+            }
+        // guess the next generation and start building it on the spare compile workers
+        ahead.reset();
+        if (args->speculate_threads > 0 && done + n < args->trials) {
+            opevo_tuner guess(*tuner);
+            std::vector<double> zeros(n, 0.0);
+            guess.tell(cfgs.data(), zeros.data(), n);
+            auto a = std::make_shared<Ahead>();
+            a->width = w;
+            a->cfgs.resize(size_t(gen_cap) * w);
+            const int m = guess.ask(a->cfgs.data(), args->trials - done - n);
+            if (m > 0) {
+                a->kids.resize(m);
+                a->taken.assign(m, 0);
+                Ahead *ap = a.get();
+                auto builder = [ap, op, variant, m, w]() {
+                    for (;;) {
+                        const int i = ap->next.fetch_add(1);
+                        if (i >= m) return;
+                        Child c;
+                        c.status = build_kernel(*op, variant, ap->cfgs.data() + size_t(i) * w, &c.kernel, &c.compile_ms);
+                        if (c.status != OPEVO_OK) c.error = last_error();
+                        c.done = true;
+                        {
+                            std::lock_guard<std::mutex> lock(ap->mu);
+                            ap->kids[i] = std::move(c);
+                        }
+                        ap->cv.notify_all();
+                    }
+                };
+                for (int t = 0; t < std::min(args->speculate_threads, m); ++t) a->threads.emplace_back(builder);
+                ahead = a;
+            }
+        }
         auto worker = [&]() {
             for (;;) {
                 const int i = next.fetch_add(1);
                 if (i >= n) return;
+                if (from_ahead[i] >= 0) continue;       // comes from the previous generation's guess
                 Child c;
                 c.status = build_kernel(*op, variant, cfgs.data() + size_t(i) * w, &c.kernel, &c.compile_ms);
                 if (c.status != OPEVO_OK) c.error = last_error();
@@ -104,7 +189,13 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
         for (int t = 0; t < std::min(n_threads, n); ++t) pool.emplace_back(worker);
 
         for (int i = 0; i < n; ++i) {
-            {
+            if (from_ahead[i] >= 0) {
+                std::unique_lock<std::mutex> lock(prev->mu);
+                prev->cv.wait(lock, [&] { return prev->kids[from_ahead[i]].done; });
+                kids[i] = std::move(prev->kids[from_ahead[i]]);
+                prev->kids[from_ahead[i]].kernel = nullptr;
+                result->n_built_ahead++;
+            } else {
                 std::unique_lock<std::mutex> lock(mu);
                 cv.wait(lock, [&] { return kids[i].done; });
             }
@@ -177,6 +268,11 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
             c.kernel = nullptr;
         }
         for (auto &th : pool) th.join();
+        if (prev) stale.push_back(prev);    // its builders may still be busy with guesses nobody asked for
+        for (size_t k = 0; k < stale.size();) {   // retire the guesses whose builders have finished
+            if (stale[k]->all_built()) { stale[k]->finish(); stale.erase(stale.begin() + k); }
+            else ++k;
+        }
         result->compile_s += seconds_since(t_compile);
         if (rc_final != OPEVO_OK) break;
         tuner->tell(cfgs.data(), fit.data(), n);
@@ -187,6 +283,8 @@ extern "C" int opevo_tune(const opevo_op *op, int variant, const opevo_tune_args
         }
         done += n;
     }
+    if (ahead) stale.push_back(ahead);
+    for (auto &a : stale) a->finish();
     // compile_s was measured around the whole generation; what is left after the GPU share
     result->compile_s = std::max(0.0, result->compile_s - result->run_s);
     result->n_trials = done;

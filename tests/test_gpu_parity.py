@@ -1045,17 +1045,24 @@ def test_mfma_ceiling_is_plausible(torch_cuda):
     assert 500.0 < t1 <= t0 * 1.02 and t0 < 2600.0          # nominal dense bf16 peak is 2500
 
 
-def test_tune_runs_alg1_on_the_gpu_with_parity_gate(torch_cuda):
+@pytest.mark.parametrize("ahead", [0, 4], ids=["plain", "next generation built ahead"])
+def test_tune_runs_alg1_on_the_gpu_with_parity_gate(torch_cuda, ahead):
+    """With `ahead` the run builds a guess of the next generation on spare compile workers while the current one
+    is compiled and timed; the trajectory must still be Alg. 1's, configuration for configuration."""
     torch = torch_cuda
     w = Workload(torch, "matmul", (512, 1024, 1024), "bf16", 1235)
     ref = torch.from_numpy(w.ref.astype(np.float32)).cuda()
     res = P.opevo_tune(w.op, P.OPEVO_TILE4, w.a.data_ptr(), w.b.data_ptr(), w.c.data_ptr(), ref.data_ptr(), w.stream,
-                       trials=60, lambda_=8, rho=8, q=0.5, seed=0, compile_threads=8, warmup=2, samples=3,
-                       trial_timeout_ms=500.0)
+                       trials=60 + 36 * (ahead > 0), lambda_=8, rho=8, q=0.5, seed=0, compile_threads=4 if ahead else 8, warmup=2, samples=3,
+                       trial_timeout_ms=500.0, speculate_threads=ahead)
     logs = res["logs"]
-    assert res["n_trials"] == 60 and len(logs["fitness"]) == 60
+    n_trials = 60 + 36 * (ahead > 0)
+    _say("  %d of %d trials had their kernel built ahead" % (res["n_built_ahead"], n_trials))
+    assert (res["n_built_ahead"] == 0) if not ahead else (0 <= res["n_built_ahead"] <= n_trials - 8)
+    logs = {k: v[:60] for k, v in logs.items()} if not ahead else logs
+    assert res["n_trials"] == n_trials and len(logs["fitness"]) == n_trials
     assert res["n_parity_fail"] == 0 and res["n_compile_fail"] == 0
-    assert len({tuple(c) for c in logs["cfg"]}) == 60                    # never sampled twice
+    assert len({tuple(c) for c in logs["cfg"]}) == n_trials              # never sampled twice
     ok = logs["status"] == P.OPEVO_OK
     assert np.all(logs["fitness"][ok] > 0) and np.all(logs["fitness"][~ok] == 0)
     assert set(np.unique(logs["status"])) <= {P.OPEVO_OK, P.OPEVO_E_INVALID}
@@ -1067,8 +1074,8 @@ def test_tune_runs_alg1_on_the_gpu_with_parity_gate(torch_cuda):
     osp = S.Space([S.Factor(512, 4), S.Factor(1024, 4), S.Factor(1024, 2), S.Categorical(2)])
     t = S.OpEvo(osp, 8, 8, 0.5, 0)
     i = 0
-    while i < 60:
-        xs = t.ask(60 - i)
+    while i < n_trials:
+        xs = t.ask(n_trials - i)
         assert [osp.flat(x) for x in xs] == [list(c) for c in logs["cfg"][i:i + len(xs)]]
         t.tell(xs, list(logs["fitness"][i:i + len(xs)]))
         i += len(xs)
