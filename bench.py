@@ -16,6 +16,7 @@ The cost of a trial (compile + run + gate + search step) is reported as `config.
 Inputs are seeded, synthetic and resident in HBM before any timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--trials N] [--workload mm8192_bf16] [--seed 0]
+    python bench.py --sweep --workload mm1_bf16 --trials 400 > sweep.jsonl     # Sec. 5.5 sensitivity + controls
 """
 import argparse
 import json
@@ -79,6 +80,13 @@ def main() -> int:
                     help="comma-separated configuration to measure the roofline object on instead of this run's "
                          "best (for hardware-counter runs, whose per-dispatch overhead perturbs the timings "
                          "that steer the search)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of one run: the sensitivity sweep of Sec. 5.5 (q, lambda) with a plain-EA and a random-search "
+                         "control, `--trials` trials per run, every run parity-gated; prints JSON lines")
+    ap.add_argument("--sweep-q", default="0.1,0.3,0.5,0.7,0.9", help="mutation rates tried at lambda = rho = 8")
+    ap.add_argument("--sweep-lambda", default="4,16,32", help="parent sizes tried at q = 0.5 (rho = 8)")
+    ap.add_argument("--sweep-uniform", default="0.2,0.5", help="resampling probabilities of the plain-EA control")
+    ap.add_argument("--sweep-seeds", default="0,1,2")
     ap.add_argument("--no-build-ahead", action="store_true",
                     help="do not build a guess of the next generation on spare compile workers while the current one is timed")
     ap.add_argument("--copy-probe", action="store_true",
@@ -172,13 +180,48 @@ def main() -> int:
 
     timeout_ms = args.timeout_ms if args.timeout_ms > 0 else max(10.0, 100.0 * flops / (2.0 * 8192.0 ** 3))
 
-    def tune(trials, seed):
+    def tune(trials, seed, lam=8, q=0.5, mutation=0):
         return P.opevo_tune(op, variant, da.data_ptr(), db.data_ptr(), dc.data_ptr(), dref.data_ptr(), stream,
                             ref_row_index=drows.data_ptr() if drows is not None else None,
                             n_ref_rows=int(rows.size) if rows is not None else 0, ref_row_len=row_len,
-                            trials=trials, lambda_=8, rho=8, q=0.5, seed=seed, compile_threads=8,
+                            trials=trials, lambda_=lam, rho=8, q=q, seed=seed, compile_threads=8,
                             warmup=3, launches_per_sample=0, samples=5, trial_timeout_ms=timeout_ms, progress_every=100,
-                            tol_max_scaled=tol[0], tol_rel_fro=tol[1], speculate_threads=0 if args.no_build_ahead else 8)
+                            tol_max_scaled=tol[0], tol_rel_fro=tol[1], mutation=mutation,
+                            speculate_threads=0 if args.no_build_ahead else 8)
+
+    trials = args.trials if args.trials > 0 else GRADED_TRIALS.get(args.workload, 500)
+    if args.sweep:
+        # Hyperparameter sensitivity (Sec. 5.5: mutation rate q, parent size lambda) and two controls: Alg. 1 with
+        # a mutation that ignores the parameter graphs (per parameter, with probability p, a uniformly random
+        # vertex: a plain evolutionary algorithm) and uniform random search (Alg. 1 with lambda = the budget, i.e.
+        # nothing but its initial, uniformly random, duplicate-free generation).  Every run goes through the same
+        # parity gate as the benchmark.  One JSON line per run, one per setting (mean and std over the seeds).
+        seeds = [int(x) for x in args.sweep_seeds.split(",")]
+        marks = [m for m in (50, 100, 200, 300, 400, 500, 750, 1000) if m <= trials]
+        settings = [("q=%s lambda=8" % x, float(x), 8, 0) for x in args.sweep_q.split(",") if x]
+        settings += [("q=0.5 lambda=%s" % x, 0.5, int(x), 0) for x in args.sweep_lambda.split(",") if x]
+        settings += [("uniform mutation p=%s lambda=8" % x, float(x), 8, 1) for x in args.sweep_uniform.split(",") if x]
+        settings += [("uniform random search", 0.5, trials, 0)]
+        failures = 0
+        for name, q, lam, mutation in settings:
+            curves = []
+            for seed in seeds:
+                r = tune(trials, seed, lam=lam, q=q, mutation=mutation)
+                f = r["logs"]["fitness"][: int(r["n_trials"])]
+                curve = [float(np.max(f[:m])) if f.size else 0.0 for m in marks]
+                curves.append(curve)
+                failures += int(r["n_parity_fail"])
+                print(json.dumps({"workload": args.workload, "space": args.space or "default", "setting": name, "seed": seed,
+                                  "trials": int(r["n_trials"]), "best_after": dict(zip(map(str, marks), [round(c, 2) for c in curve])),
+                                  "n_invalid": int(r["n_invalid"]), "n_parity_fail": int(r["n_parity_fail"]),
+                                  "wall_s": round(float(r["wall_s"]), 1)}), flush=True)
+            arr = np.asarray(curves)
+            print(json.dumps({"workload": args.workload, "space": args.space or "default", "setting": name, "seeds": seeds,
+                              "mean_best_after": dict(zip(map(str, marks), [round(float(x), 2) for x in arr.mean(axis=0)])),
+                              "std_best_after": dict(zip(map(str, marks), [round(float(x), 2) for x in arr.std(axis=0)]))}), flush=True)
+        P.opevo_op_destroy(op)
+        P.opevo_compile_pool_stop()
+        return 0 if failures == 0 else 1
 
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
@@ -186,7 +229,6 @@ def main() -> int:
         torch.neg(src, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    trials = args.trials if args.trials > 0 else GRADED_TRIALS.get(args.workload, 500)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     res = tune(trials, seed=args.seed)

@@ -1,6 +1,7 @@
 // Operator descriptors, configuration spaces and the configuration decoder.
 #include "op.hpp"
 
+#include <cstdlib>
 #include <cstring>
 #include <algorithm>
 #include <new>
@@ -353,7 +354,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                     const int64_t unit = 1024 * nw / std::gcd(int64_t(1024) * nw, BK * 2);
                     rows = (rows + unit - 1) / unit * unit;
                     rows_a = (rows_a + unit - 1) / unit * unit;
-                    if (rows * BK * 2 / (1024 * nw) <= 8 && rows_a * BK * 2 / (1024 * nw) <= 8)
+                    if (rows * BK * 2 / (1024 * nw) <= 16 && rows_a * BK * 2 / (1024 * nw) <= 16)
                         nstage_dlds = dlds_stages(rows_a, rows, false);
                 }
                 if (nstage_dlds) { path = 3; bnr = rows; anr = rows_a; BKP = BK; ragged = false; TMacc = TM; TNacc = TN32; }
