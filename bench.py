@@ -89,6 +89,10 @@ def main() -> int:
     ap.add_argument("--sweep-seeds", default="0,1,2")
     ap.add_argument("--no-build-ahead", action="store_true",
                     help="do not build a guess of the next generation on spare compile workers while the current one is timed")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="MatMul only, context: also time the vendor library's GEMM (torch.matmul) on the same operands, with "
+                         "B as stored ([K][N]) and with B packed [N][K] beforehand (packing not timed); reported under "
+                         "config.vendor_gemm, never as `value`")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one elementwise pass over 256 MiB (reads 256 MiB, writes 256 MiB): the "
                          "known-size reference that scales the HBM counters of a profiler run")
@@ -299,6 +303,25 @@ def main() -> int:
                     "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None,
                     "same_kernel_on_zero_operands": round(flops / (ms_zero * 1e-3) * 1e-12, 2) if ms_zero else None}
 
+    vendor = None
+    if args.vendor_gemm and w["kind"] == "matmul" and dtype != "f32":
+        M_, N_, K_ = w["dims"]
+        va, vb = da.view(M_, K_), db.view(K_, N_)
+        vbt = vb.t().contiguous()
+
+        def vendor_time(f):
+            for _ in range(30):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(60):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / 60
+        vendor = {"b_as_stored_tflops": round(flops / (vendor_time(lambda: va @ vb) * 1e-3) * 1e-12, 1),
+                  "b_packed_beforehand_tflops": round(flops / (vendor_time(lambda: va @ vbt.t()) * 1e-3) * 1e-12, 1)}
+
     out = {
         "metric": "best-found TFLOP/s after the trial budget of an OpEvo run (and fraction of %s dense MFMA peak)" % {"f16": "fp16", "f32": "fp32"}.get(dtype, dtype),
         "value": round(best, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -318,7 +341,8 @@ def main() -> int:
                    "n_built_ahead": int(res["n_built_ahead"]),
                    "n_invalid": int(res["n_invalid"]), "n_compile_fail": int(res["n_compile_fail"]),
                    "n_parity_fail": int(res["n_parity_fail"]), "parity_failures": parity_failures, "parity_gate": sample,
-                   "timing": "per trial: 25 ms warm-up, then median of 5 back-to-back samples of >= 200 us; inputs cache-warm"},
+                   "timing": "per trial: 25 ms warm-up, then median of 5 back-to-back samples of >= 200 us; inputs cache-warm",
+                   **({"vendor_gemm": vendor} if vendor else {})},
         "roofline": roofline,
         "cpu_baseline": {"value": round(oracle_flops / oracle_s * 1e-12, 6), "unit": "TFLOP/s", "cores": threads,
                          "kind": "oracle", "sample": sample, "seconds": round(oracle_s, 2), "host_cores_visible": cores},
