@@ -89,6 +89,10 @@ def main() -> int:
     ap.add_argument("--sweep-seeds", default="0,1,2")
     ap.add_argument("--no-build-ahead", action="store_true",
                     help="do not build a guess of the next generation on spare compile workers while the current one is timed")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="context: also time the best-found kernel on all-zero operands (no operand bits toggle, so the "
+                         "power-managed clock stays high); off by default so that a profiler's per-kernel average covers "
+                         "launches on the workload's operands only")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="MatMul only, context: also time the vendor library's GEMM (torch.matmul) on the same operands, with "
                          "B as stored ([K][N]) and with B packed [N][K] beforehand (packing not timed); reported under "
@@ -261,7 +265,7 @@ def main() -> int:
         # the same kernel on all-zero operands (no operand bits toggle, so the power-managed clock stays
         # high): not the workload, only a measure of how much of the gap to the peak is the schedule's
         ms_zero = None
-        if dtype != "f32" and P.opevo_op_bytes(op) < 4e9:
+        if args.zero_operands and dtype != "f32" and P.opevo_op_bytes(op) < 4e9:
             za, zb = torch.zeros_like(da), torch.zeros_like(db)
             ms_zero, _ = P.opevo_kernel_time(kernel, za.data_ptr(), zb.data_ptr(), dc.data_ptr(), stream,
                                              warmup=3, launches_per_sample=20, samples=3)
