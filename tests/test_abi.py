@@ -24,6 +24,25 @@ def test_header_symbols_are_exported_and_bound():
     assert sorted(P.binding.EXPORTED) == names
 
 
+def test_oracle_header_matches_the_oracle_library():
+    """include/oracle_tensor.h: every entry point it declares is exported by the oracle's own library, and its
+    prototypes agree with the definitions (the C file compiled with the header force-included)."""
+    import subprocess
+    from oracle import tensor as T
+    header = os.path.join(ROOT, "include", "oracle_tensor.h")
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(oracle_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["oracle_bmm", "oracle_conv2d", "oracle_conv_out_extent", "oracle_matmul", "oracle_matmul_entries",
+                     "oracle_matmul_rows", "oracle_num_threads", "oracle_set_threads"]
+    lib = ctypes.CDLL(T.build())
+    for n in names:
+        assert hasattr(lib, n), "oracle library does not export " + n
+    subprocess.run(["gcc", "-fsyntax-only", "-fopenmp", "-Wall", "-Werror", "-include", header,
+                    os.path.join(ROOT, "oracle", "tensor_oracle.c")], check=True)
+    # the product's header and sources never mention the oracle's
+    assert "oracle_tensor.h" not in open(os.path.join(ROOT, "include", "opevo.h")).read()
+
+
 def test_status_names_and_error_text():
     assert P.opevo_status_name(0) == "OK" and P.opevo_status_name(-3) == "E_INVALID"
     try:
