@@ -89,6 +89,9 @@ def main() -> int:
     ap.add_argument("--sweep-seeds", default="0,1,2")
     ap.add_argument("--no-build-ahead", action="store_true",
                     help="do not build a guess of the next generation on spare compile workers while the current one is timed")
+    ap.add_argument("--compile-deadline-s", type=float, default=15.0,
+                    help="an instantiation that takes longer than this on a compile worker is not waited for and its configuration "
+                         "scores 0 (a few convolution members take a minute or more to compile); 0 = no limit")
     ap.add_argument("--zero-operands", action="store_true",
                     help="context: also time the best-found kernel on all-zero operands (no operand bits toggle, so the "
                          "power-managed clock stays high); off by default so that a profiler's per-kernel average covers "
@@ -112,6 +115,7 @@ def main() -> int:
     # 8 compile workers for the generation being evaluated (Sec. 6) and 8 that build a guess of the next one
     # ahead of time; all forked before the GPU is touched
     P.opevo_compile_pool_start(8 if args.no_build_ahead else 16)
+    P.opevo_compile_pool_deadline(max(0.0, args.compile_deadline_s))
     pool_kind = P.opevo_compile_pool_kind()
     import torch
     from oracle import tensor as oracle_tensor   # cpu_baseline leg and reference rows only
@@ -338,7 +342,7 @@ def main() -> int:
                    "ms_per_trial": round(wall / max(1, res["n_trials"]) * 1e3, 2),
                    "compile_pool": {1: "%d worker executables (hipRTC of /opt/rocm)", 0: "%d forked workers (hipRTC of the process)",
                                     -1: "none (%d asked for): in-process hipRTC"}.get(pool_kind, "%d") % (8 if args.no_build_ahead else 16),
-                   "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {v: k for k, v in names.items()}[variant],
+                   "compile_deadline_s": args.compile_deadline_s, "lambda": 8, "rho": 8, "q": 0.5, "seed": args.seed, "space": {v: k for k, v in names.items()}[variant],
                    "best_cfg": [int(x) for x in res["best_cfg"]], "frac_of_peak": round(best / PEAK_TFLOPS[dtype], 4),
                    "trials_to_best": trials_to_best, "trials_to_99pct": trials_to_99,
                    "tuning_wall_s": round(wall, 2), "compile_s": round(res["compile_s"], 2), "run_s": round(res["run_s"], 2),

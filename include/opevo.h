@@ -306,6 +306,14 @@ int opevo_kernel_defines(const opevo_op *op, int variant, const int32_t *cfg,
 int opevo_compile_pool_start(int n_workers, int *n_running);
 int opevo_compile_pool_stop(void);
 int opevo_compile_pool_kind(int *kind);
+/* A limit on the time a caller waits for one instantiation on a worker (seconds; 0, the default, = none).
+ * hipRTC cannot be interrupted and no process is started once the GPU may be open, so a compilation that
+ * overruns is left to finish in the background (its worker returns to the pool afterwards, the result is
+ * dropped) while the call is answered OPEVO_E_INVALID at the deadline: the configuration counts as one that
+ * cannot be evaluated (Sec. 4.2: fitness 0).  A few members of the convolution spaces (one wave gathering a
+ * long slab value by value, fully unrolled) take a minute or more to compile on a loaded host and would
+ * otherwise hold up their whole generation.  No effect without a pool. */
+int opevo_compile_pool_deadline(double seconds);
 
 /* Instantiate: render + hipRTC-compile for gfx950 (works without a GPU).  Returns
  * OPEVO_E_INVALID for an invalid configuration (no kernel), OPEVO_E_HIPRTC on a compile

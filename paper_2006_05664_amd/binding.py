@@ -121,6 +121,7 @@ _SIGNATURES = {
     "opevo_compile_pool_start": [C.c_int, C.POINTER(C.c_int)],
     "opevo_compile_pool_stop": [],
     "opevo_compile_pool_kind": [C.POINTER(C.c_int)],
+    "opevo_compile_pool_deadline": [C.c_double],
     "opevo_kernel_plan": [_vp, C.c_int, _i32p, C.POINTER(opevo_plan)],
     "opevo_kernel_defines": [_vp, C.c_int, _i32p, C.c_char_p, C.c_size_t],
     "opevo_kernel_build": [_vp, C.c_int, _i32p, C.POINTER(_vp), _f64p],
@@ -453,6 +454,10 @@ def opevo_compile_pool_start(n_workers: int) -> int:
 
 def opevo_compile_pool_stop() -> None:
     _check(lib.opevo_compile_pool_stop())
+
+
+def opevo_compile_pool_deadline(seconds: float) -> None:
+    _check(lib.opevo_compile_pool_deadline(seconds))
 
 
 def opevo_compile_pool_kind() -> int:

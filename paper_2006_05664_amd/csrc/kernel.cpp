@@ -35,6 +35,8 @@ int build_kernel(const opevo_op &op, int variant, const int32_t *cfg, opevo_kern
     CompileResult r;
     const bool cached = code_cache_get(key, r.code);
     if (!cached) r = pool_compile(d.tmpl, d.defines);
+    if (r.status == OPEVO_E_INVALID)
+        return fail(r.status, "invalid configuration: %s [%s]", r.log.c_str(), d.kernel_name.c_str());
     if (r.status != OPEVO_OK)
         return fail(r.status, "hipRTC failed for [%s]: %s", d.defines.c_str(), r.log.c_str());
     // A direct-to-LDS member whose K loop did not unroll compiles into a code object of hundreds of

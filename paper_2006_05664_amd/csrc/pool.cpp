@@ -1,16 +1,19 @@
 // Pool of hipRTC worker processes: see pool.hpp.
 #include "pool.hpp"
 
+#include <cerrno>
 #include <condition_variable>
 #include <csignal>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <thread>
 
 #include <dirent.h>
 #include <dlfcn.h>
 #include <fcntl.h>
+#include <poll.h>
 #include <sys/types.h>
 #include <sys/wait.h>
 #include <unistd.h>
@@ -31,6 +34,7 @@ std::mutex g_mu;
 std::condition_variable g_cv;
 std::vector<Worker> g_workers;
 int g_kind = -1;
+double g_deadline_s = 0.0;        // > 0: a caller waits no longer than this for a compilation on a worker
 
 // Has this process opened the GPU (KFD or a render node)?  Then it must not exec any more.
 bool gpu_is_open()
@@ -89,6 +93,12 @@ int pool_kind()
 {
     std::lock_guard<std::mutex> lock(g_mu);
     return g_workers.empty() ? -1 : g_kind;
+}
+
+void pool_set_deadline(double seconds)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_deadline_s = seconds;
 }
 
 int pool_start(int n)
@@ -181,8 +191,45 @@ CompileResult pool_compile(const std::string &tmpl, const std::string &defines)
     CompileResult res;
     int32_t status = 0;
     std::string code;
-    const bool ok = write_str(to, tmpl) && write_str(to, defines) && read_all(from, &status, sizeof status) &&
-                    read_all(from, &res.ms, sizeof res.ms) && read_str(from, code) && read_str(from, res.log);
+    bool ok = write_str(to, tmpl) && write_str(to, defines);
+    // A worker answers only when its compilation has ended.  With a deadline set, wait for the first byte of the
+    // answer no longer than that.  hipRTC cannot be interrupted and no process is started once the GPU may be
+    // open, so an overrunning compilation is left to finish: the caller is answered at once that the
+    // configuration cannot be evaluated (Sec. 4.2: fitness 0), and a detached thread takes the late answer off
+    // the pipe and hands the worker back to the pool.
+    double deadline_s;
+    pid_t pid;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        deadline_s = g_deadline_s;
+        pid = g_workers[idx].pid;
+    }
+    if (ok && deadline_s > 0.0) {
+        pollfd pfd = {from, POLLIN, 0};
+        int rc;
+        do rc = poll(&pfd, 1, int(deadline_s * 1e3)); while (rc < 0 && errno == EINTR);
+        if (rc == 0) {
+            std::thread([idx, from, pid]() {
+                int32_t st = 0;
+                double ms = 0.0;
+                std::string code, log;
+                const bool fine = read_all(from, &st, sizeof st) && read_all(from, &ms, sizeof ms) && read_str(from, code) && read_str(from, log);
+                {
+                    std::lock_guard<std::mutex> lock(g_mu);
+                    if (size_t(idx) < g_workers.size() && g_workers[idx].pid == pid) {   // the pool may have been stopped meanwhile
+                        g_workers[idx].busy = false;
+                        if (!fine) g_workers[idx].dead = true;
+                    }
+                }
+                g_cv.notify_all();
+            }).detach();
+            res.status = OPEVO_E_INVALID;
+            res.log = "compilation exceeded the deadline of " + std::to_string(deadline_s) + " s";
+            return res;
+        }
+    }
+    ok = ok && read_all(from, &status, sizeof status) &&
+         read_all(from, &res.ms, sizeof res.ms) && read_str(from, code) && read_str(from, res.log);
     {
         std::lock_guard<std::mutex> lock(g_mu);
         if (size_t(idx) < g_workers.size()) {
@@ -212,6 +259,13 @@ int opevo_compile_pool_start(int n_workers, int *n_running)
 int opevo_compile_pool_stop(void)
 {
     opevo::pool_stop();
+    return OPEVO_OK;
+}
+
+int opevo_compile_pool_deadline(double seconds)
+{
+    if (!(seconds >= 0.0) || seconds > 1e6) return opevo::fail(OPEVO_E_ARG, "compile_pool_deadline: seconds must be in [0, 1e6]");
+    opevo::pool_set_deadline(seconds);
     return OPEVO_OK;
 }
 

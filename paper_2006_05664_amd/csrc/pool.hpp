@@ -38,6 +38,9 @@ void pool_stop();
 int pool_size();
 // 1 if the workers are the stand-alone executable, 0 if forks of this process, -1 if no pool.
 int pool_kind();
+// seconds > 0: a caller waits no longer than this for a compilation on a worker; an overrunning one is answered
+// OPEVO_E_INVALID while the worker finishes it in the background
+void pool_set_deadline(double seconds);
 // Compiles on a free worker (blocks until one is free); in-process if the pool is not running
 // or the worker died.
 CompileResult pool_compile(const std::string &tmpl, const std::string &defines);
