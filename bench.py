@@ -65,8 +65,8 @@ def main() -> int:
                          "number of workgroups that share an output tile (partial sums added atomically)")
     ap.add_argument("--split-reduction", action="store_true",
                     help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
-    ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T"],
-                    help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4C for Conv2d, else TILE4)")
+    ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T", "TILE4A"],
+                    help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4C for Conv2d, TILE4A for the 16-bit 8192^3 MatMul, else TILE4)")
     ap.add_argument("--extended", action="store_true",
                     help="tune in the extended space (launch order as a permutation, group width as a discrete parameter)")
     ap.add_argument("--oracle-rows", type=int, default=32,
@@ -137,11 +137,13 @@ def main() -> int:
             return 2
         variant = P.OPEVO_TILE4P
     names = {"TILE2": P.OPEVO_TILE2, "TILE4": P.OPEVO_TILE4, "TILE4X": P.OPEVO_TILE4X, "TILE4P": P.OPEVO_TILE4P,
-             "TILE4K": P.OPEVO_TILE4K, "TILE4C": P.OPEVO_TILE4C, "TILE4T": P.OPEVO_TILE4T}
+             "TILE4K": P.OPEVO_TILE4K, "TILE4C": P.OPEVO_TILE4C, "TILE4T": P.OPEVO_TILE4T, "TILE4A": P.OPEVO_TILE4A}
     if args.space:
         variant = names[args.space]
     elif w["kind"] == "conv2d" and variant == P.OPEVO_TILE4:
         variant = P.OPEVO_TILE4C    # the conv space with the reduction split and the channels-last choice
+    elif args.workload.startswith("mm8192") and dtype != "f32" and variant == P.OPEVO_TILE4:
+        variant = P.OPEVO_TILE4A    # the MatMul space with the MFMA atom as a choice (the power-limited size)
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
     flops = P.opevo_op_flops(op)
     a_host, b_host = synth.workload_inputs(args.workload)
@@ -260,6 +262,7 @@ def main() -> int:
     ms = None
     ceiling = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=True) if dtype != "f32" else None
     ceiling0 = P.opevo_mfma_ceiling(synth.DTYPE_CODE[dtype], stream, random_data=False) if dtype != "f32" else None
+    ceiling16 = P.opevo_mfma_ceiling_atom(synth.DTYPE_CODE[dtype], stream, random_data=True, atom=16) if dtype != "f32" else None
     roof_cfg = [int(x) for x in args.roofline_cfg.split(",")] if args.roofline_cfg else res["best_cfg"]
     if best > 0 or args.roofline_cfg:
         kernel, _ = P.opevo_kernel_build(op, variant, roof_cfg)
@@ -308,6 +311,7 @@ def main() -> int:
                     "kernel_ms": round(ms, 5), "kernel": kname,
                     "mfma_only_ceiling": round(ceiling, 1) if ceiling else None,
                     "mfma_only_ceiling_zero_operands": round(ceiling0, 1) if ceiling0 else None,
+                    "mfma_only_ceiling_16x16x32_atoms": round(ceiling16, 1) if ceiling16 else None,
                     "frac_of_ceiling": round(achieved / ceiling, 4) if ceiling else None,
                     "same_kernel_on_zero_operands": round(flops / (ms_zero * 1e-3) * 1e-12, 2) if ms_zero else None}
 

@@ -247,8 +247,16 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         pre-pass kernel that transposes B to [N][K] into a workspace the kernel object owns; both
  *         operands are then K-contiguous and read from LDS with plain 16-byte fragment reads.  Only
  *         members of the direct-to-LDS template have such a kernel; elsewhere bpack = 1 runs the
- *         bpack = 0 kernel. */
-typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4, OPEVO_TILE4C = 5, OPEVO_TILE4T = 6 } opevo_variant;
+ *         bpack = 0 kernel.
+ *  TILE4A: MatMul only: TILE4 plus a binary choice of the MFMA atom,
+ *         MatMul  M(4) N(4) K(2) unroll{0,1} atom{0,1}
+ *         atom = 1: members of the direct-to-LDS template multiply with 16x16x32 atoms instead of 32x32x16 ones
+ *         (same tiles, same LDS traffic, twice the MFMA instructions, a quarter of the accumulator updates per
+ *         flop: under the chip's power limit the matrix pipes sustain about a tenth more flops per second on
+ *         changing operands that way, while kernels bound by instruction issue lose).  Elsewhere, and where the
+ *         unrolled loop body would grow too long, atom = 1 runs the atom = 0 kernel. */
+typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4, OPEVO_TILE4C = 5, OPEVO_TILE4T = 6,
+               OPEVO_TILE4A = 7 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
@@ -379,6 +387,10 @@ int opevo_kernel_time(opevo_kernel *kernel, const void *a, const void *b, void *
  * Kernel results are best read against both.  Allocates and frees a small device buffer.
  * Synchronises `stream`. */
 int opevo_mfma_ceiling(int in_dtype, int random_data, void *stream, double *tflops);
+/* The same with the MFMA atom named: 32 = 32x32x16 (what opevo_mfma_ceiling measures), 16 = 16x16x32.  On
+ * operands that change, the device sustains more flops per second with the 16x16x32 atom (fewer accumulator
+ * updates per flop, so less power per flop); on all-zero operands slightly fewer. */
+int opevo_mfma_ceiling_atom(int in_dtype, int random_data, int atom, void *stream, double *tflops);
 
 /* Parity gate: c and ref are DEVICE fp32 arrays of n elements.
  * max_scaled = max |c-ref| / (|ref|+1), rel_fro = ||c-ref||_F / ||ref||_F (0 if both 0).

@@ -25,7 +25,7 @@ OPEVO_E_HIPRTC, OPEVO_E_HIP, OPEVO_E_PARITY, OPEVO_E_TOO_LARGE, OPEVO_E_STATE = 
 OPEVO_FACTOR, OPEVO_PERMUTATION, OPEVO_DISCRETE, OPEVO_CATEGORICAL = 0, 1, 2, 3
 OPEVO_MATMUL, OPEVO_BMM, OPEVO_CONV2D, OPEVO_BMM_TA = 0, 1, 2, 3
 OPEVO_F32, OPEVO_BF16, OPEVO_F16 = 0, 1, 2
-OPEVO_TILE2, OPEVO_TILE4, OPEVO_TILE4X, OPEVO_TILE4P, OPEVO_TILE4K, OPEVO_TILE4C, OPEVO_TILE4T = 0, 1, 2, 3, 4, 5, 6
+OPEVO_TILE2, OPEVO_TILE4, OPEVO_TILE4X, OPEVO_TILE4P, OPEVO_TILE4K, OPEVO_TILE4C, OPEVO_TILE4T, OPEVO_TILE4A = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 class OpevoError(RuntimeError):
@@ -134,6 +134,7 @@ _SIGNATURES = {
     "opevo_kernel_launch": [_vp, _vp, _vp, _vp, _vp],
     "opevo_kernel_time": [_vp, _vp, _vp, _vp, _vp, C.c_int, C.c_double, C.c_int, C.c_int, C.c_double, _f64p, _f64p],
     "opevo_mfma_ceiling": [C.c_int, C.c_int, _vp, _f64p],
+    "opevo_mfma_ceiling_atom": [C.c_int, C.c_int, C.c_int, _vp, _f64p],
     "opevo_compare_f32": [_vp, _vp, C.c_int64, _vp, _f64p, _f64p],
     "opevo_compare_rows_f32": [_vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _f64p, _f64p],
     "opevo_compare_f32_static": [_vp, _vp, C.c_int64, _vp, _vp],
@@ -536,6 +537,12 @@ def opevo_kernel_time(kernel, a: int, b: int, c: int, stream: int = 0, warmup: i
 def opevo_mfma_ceiling(in_dtype: int = OPEVO_BF16, stream: int = 0, random_data: bool = True) -> float:
     v = C.c_double()
     _check(lib.opevo_mfma_ceiling(in_dtype, 1 if random_data else 0, stream, C.byref(v)))
+    return v.value
+
+
+def opevo_mfma_ceiling_atom(in_dtype: int = OPEVO_BF16, stream: int = 0, random_data: bool = True, atom: int = 32) -> float:
+    v = C.c_double()
+    _check(lib.opevo_mfma_ceiling_atom(in_dtype, 1 if random_data else 0, atom, stream, C.byref(v)))
     return v.value
 
 

@@ -269,13 +269,19 @@ int opevo_kernel_resources(opevo_kernel *k, int *vgprs, int *sgprs, int *spill_b
 
 int opevo_mfma_ceiling(int in_dtype, int random_data, void *stream_, double *tflops)
 {
+    return opevo_mfma_ceiling_atom(in_dtype, random_data, 32, stream_, tflops);
+}
+
+int opevo_mfma_ceiling_atom(int in_dtype, int random_data, int atom, void *stream_, double *tflops)
+{
     if (!tflops || (in_dtype != OPEVO_BF16 && in_dtype != OPEVO_F16))
         return fail(OPEVO_E_ARG, "mfma_ceiling: bf16 or fp16 only");
+    if (atom != 16 && atom != 32) return fail(OPEVO_E_ARG, "mfma_ceiling: atom must be 16 (16x16x32) or 32 (32x32x16)");
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int blocks = 2048, iters = 2048;
     std::ostringstream d;
     d << "-DKERNEL_NAME=opevo_mfma_peak -DIN_DTYPE=" << in_dtype << " -DITERS=" << iters
-      << " -DOP=0 -DBATCH_INNER=1";
+      << " -DOP=0 -DBATCH_INNER=1 -DPEAK_ATOM=" << atom;
     CompileResult r = pool_compile("mfma_peak", d.str());
     if (r.status != OPEVO_OK) return fail(r.status, "hipRTC failed for the MFMA ceiling kernel: %s", r.log.c_str());
     opevo_kernel k;

@@ -13,6 +13,7 @@ using namespace opevo;
 static const int kMaxThreads = 1024;            // threads per workgroup on gfx950
 static const int kMaxLds = 160 * 1024;          // LDS bytes per workgroup on gfx950
 static const int64_t kMaxDldsBody = 256;        // unrolled K-loop body of the direct-to-LDS template, instructions
+static const int64_t kMaxDldsBody16 = 400;      // the same for members on 16x16x32 atoms
 static const int kMaxAcc = 256;                 // fp32 accumulators per lane kept in registers
 static const int kPad = 8;                      // LDS row padding of the MFMA template (elements)
 
@@ -95,6 +96,12 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
         // transposed to [N][K] by a pre-pass before every launch
         if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the space with a packed second operand exists for MatMul only");
         descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 2), flag("unroll"), flag("bpack")};
+        return OPEVO_OK;
+    }
+    if (variant == OPEVO_TILE4A) {
+        // MatMul with the MFMA atom of direct-to-LDS members as a second binary choice: 32x32x16 or 16x16x32
+        if (op.kind != OPEVO_MATMUL) return fail(OPEVO_E_ARG, "the space with a choice of MFMA atom exists for MatMul only");
+        descs = {factor("M", op.M, 4), factor("N", op.N, 4), factor("K", op.K, 2), flag("unroll"), flag("atom")};
         return OPEVO_OK;
     }
     if (variant == OPEVO_TILE4C) {
@@ -182,7 +189,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
     bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P || variant == OPEVO_TILE4K ||
-                       variant == OPEVO_TILE4C || variant == OPEVO_TILE4T);
+                       variant == OPEVO_TILE4C || variant == OPEVO_TILE4T || variant == OPEVO_TILE4A);
+    int atom16 = 0;                        // MatMul, TILE4A: 1 = 16x16x32 atoms on direct-to-LDS members
     int bpack = 0;                         // MatMul, TILE4T: 1 = second operand transposed to [N][K] by a pre-pass
     int layout = 0;                        // Conv2d, TILE4C: 1 = channels-last operands (pre-pass)
     int64_t subm = 1, subn = 1;            // sub-tiles a workgroup computes one after another (folded members)
@@ -203,8 +211,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         if (variant == OPEVO_TILE4K) { ksplit = c[8]; b1 = ksplit; ksteps = c[9]; BK = c[10]; flagv = c[11]; }
         else { ksteps = c[8]; BK = c[9]; flagv = c[10]; }
         if (variant == OPEVO_TILE4T) bpack = c[11];
+        if (variant == OPEVO_TILE4A) atom16 = c[11];
         BM = WM * TM; BN = WN * TN;
-        tile4_width = int(c - cfg) + (variant == OPEVO_TILE4K || variant == OPEVO_TILE4T ? 12 : 11);
+        tile4_width = int(c - cfg) + (variant == OPEVO_TILE4K || variant == OPEVO_TILE4T || variant == OPEVO_TILE4A ? 12 : 11);
     } else {   // conv: B(2) Cout(4) H(4) W(4) R(2) flag
         const int32_t *c = cfg;
         const int64_t nb1 = c[0]; nb2 = c[1];
@@ -306,11 +315,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                          BK % 8 == 0 && op.b_elems() * 2 + 256 < (int64_t(1) << 32) &&
                          op.hin + 2 * op.pad + op.hk < 32768 && op.win + 2 * op.pad + op.wk < 32768;   // coordinates in 15 bits
     int nstage_dlds = 0;
+    bool dlds_atom16 = false;
     int64_t bnr = BN;   // rows of the second operand's stage part on the direct-to-LDS template when it is K-contiguous
     int64_t anr = BM;   // rows of the first operand's stage part there
     // Direct global->LDS streaming (path 3) of a pipelined member whose slabs split into whole 1 KiB wave
     // loads: `rows_b` rows of BK K-contiguous elements for the second operand (0: it is stored [K][N]).
-    auto dlds_stages = [&](int64_t rows_a, int64_t rows_b, bool a_km_rows) -> int {
+    auto dlds_stages = [&](int64_t rows_a, int64_t rows_b, bool a_km_rows, bool atoms16 = false) -> int {
         const int64_t nw = WM * WN;
         if (subm * subn > 1) return 0;   // folded members stay on the register-staged template
         if (64 * nw > kMaxThreads || !(BK == 32 || BK == 64 || BK == 128)) return 0;
@@ -328,9 +338,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         // per stage and MFMA step the MFMAs and fragment reads, per stage the loads.  Bodies
         // past this size were seen not to unroll (code objects of 0.5-1.5 MB instead of 20 KB);
         // such members use the register-staged template instead.
-        const int64_t mi = TM / 32, ni = (TN + 31) / 32, kk = BK / 16;
+        const int64_t at = atoms16 ? 16 : 32;
+        const int64_t mi = TM / at, ni = (TN + at - 1) / at, kk = BK / (atoms16 ? 32 : 16);
         const int64_t body = st_found * (kk * (mi * ni + (op.trans_a ? 2 : 1) * mi + (rows_b ? 1 : 2) * ni) + per);
-        return body > kMaxDldsBody ? 0 : st_found;
+        // 16x16x32 atoms: twice the MFMAs for the same tile; such bodies (up to 128 x 128 wave tiles on slabs of 32)
+        // were checked to unroll (code objects of about 30 KiB)
+        return body > (atoms16 ? kMaxDldsBody16 : kMaxDldsBody) ? 0 : st_found;
     };
     if (four_level && op.dtype != OPEVO_F32) {
         if (op.kind == OPEVO_CONV2D) {
@@ -386,6 +399,11 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     if (path == 1 && flagv == 1 && stage_lds && op.kind != OPEVO_CONV2D) {
         nstage_dlds = dlds_stages(BM, b_packed ? BN : 0, op.trans_a);
         if (nstage_dlds) path = 3;
+        // TILE4A, atom = 1: the same member on 16x16x32 atoms (MatMul with row-major operands; a member whose body
+        // would grow too long keeps the 32x32x16 atoms)
+        if (nstage_dlds && atom16 == 1 && op.kind == OPEVO_MATMUL && !op.trans_a && !b_packed && BK % 32 == 0 &&
+            dlds_stages(BM, 0, false, true) == nstage_dlds && (BK % 64 == 0 || nstage_dlds % 2 == 0))   // one K step per slab: an even ring
+            dlds_atom16 = true;
     }
     const bool b_kmajor = path == 3 && (b_packed || op.kind == OPEVO_CONV2D);
     const bool nhwc = nhwc_ok && (path == 1 || path == 2 || path == 3);
@@ -457,7 +475,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     {
         std::ostringstream nm;
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
-           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : variant == OPEVO_TILE4C ? "c" : variant == OPEVO_TILE4T ? "t" : four_level ? "4" : "2");
+           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : variant == OPEVO_TILE4C ? "c" : variant == OPEVO_TILE4T ? "t" : variant == OPEVO_TILE4A ? "a" : four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
@@ -468,7 +486,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
       << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
       << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv << " -DA_TRANS=" << (op.trans_a ? 1 : 0);
     if (path != 0) {
-        D << " -DATOM=" << (path == 2 ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
+        D << " -DATOM=" << ((path == 2 || dlds_atom16) ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
           << " -DNSTAGE=" << nstage << " -DNSTG=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
         if (nwr != WM * WN) D << " -DNWR=" << nwr;

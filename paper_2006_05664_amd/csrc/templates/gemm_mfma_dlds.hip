@@ -40,16 +40,34 @@
 //    precedes the image in the workspace.  A wave tile may be ragged along N (TN no multiple of
 //    32): the overhang is computed and not stored.
 
+// ATOM: 32 = 32x32x16 MFMAs (16 accumulators per lane and atom), 16 = 16x16x32 MFMAs (4 accumulators: half the
+// flops per instruction, but a 32-deep dot product per accumulator update; under the chip's power limit the matrix
+// pipes sustain more flops per second on changing operands with these).  Lane l holds, for atom row or column
+// l % ATOM, the 8 reduction values from 8 * (l / ATOM) of a KA-wide step.
 #if IN_DTYPE == 1
 typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
+#if ATOM == 16
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0)
+#else
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#endif
 #else
 typedef __attribute__((ext_vector_type(8))) _Float16 frag_t;
+#if ATOM == 16
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0)
+#else
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+#endif
 #endif
 typedef __attribute__((ext_vector_type(4))) short v4s;
 typedef __attribute__((ext_vector_type(8))) short v8s;
+#if ATOM == 16
+typedef __attribute__((ext_vector_type(4))) float acc_t;
+#else
 typedef f32x16 acc_t;
+#endif
+constexpr int ACC_N = ATOM == 16 ? 4 : 16;      // accumulators per lane and atom
+constexpr int KA = ATOM == 16 ? 32 : 16;        // reduction values one MFMA consumes
 
 #ifndef B_KMAJOR
 #define B_KMAJOR 0
@@ -64,8 +82,11 @@ typedef f32x16 acc_t;
 #error "Conv2d runs on this template with channels-last operands only"
 #endif
 constexpr int NW = NT / 64;
-constexpr int MI = TM / 32, NI = (TN + 31) / 32;
-constexpr int KK = BK / 16;                                   // MFMA K steps per slab
+constexpr int MI = TM / ATOM, NI = (TN + ATOM - 1) / ATOM;
+constexpr int KK = BK / KA;                                   // MFMA K steps per slab
+#if ATOM == 16 && (A_TRANS || OP == OP_CONV || B_KMAJOR)
+#error "16x16x32 atoms: MatMul / BatchMatMul with row-major operands as stored only"
+#endif
 #if B_KMAJOR
 constexpr int B_STAGE = BNR * BK;   // BNR rows of BK: the BN columns of the tile, rounded up to whole wave loads
 #else
@@ -92,10 +113,28 @@ constexpr int PER = LA + LB;
 
 #if A_TRANS
 __device__ __forceinline__ int a_swz(int krow) { return ((krow / A_RPW) % A_SWM) << 2; }
+#elif ATOM == 16
+// 16-row atoms: lanes 0-15 read 16 rows at one chunk, lanes 16-31 the same rows at the next chunk, and so on.
+// A 16-byte LDS read is served in four turns of 16 lanes; the first takes lanes 0-3, 12-15, 20-23 and 24-27, the
+// second the other lanes below 32, the last two the same lanes plus 32 (the grouping that explains the bank
+// conflict counts measured for the 32-row pattern, none, and for this pattern under the 32-row permutation and
+// under a first attempt, two-way each).  The permutations below put the 16 lanes of every turn on 16 different
+// 16-byte bank groups for every K step (found by enumerating the linear maps from the row's low four bits).
+__device__ __forceinline__ int a_swz(int row)
+{
+    const int b1 = (row >> 1) & 1, b2 = (row >> 2) & 1, b3 = (row >> 3) & 1;
+    return ACH == 4 ? (b3 << 1) : ACH == 8 ? (b1 | (b2 << 1) | (b3 << 2)) : (row & 15);
+}
 #else
 __device__ __forceinline__ int a_swz(int row) { return (row / A_RPW) % ACH; }
 #endif
+#if ATOM == 16 && !B_KMAJOR
+// with 16-column atoms the two 16-lane groups that read B together sit 8 k rows apart on the same columns:
+// rows whose bit 3 differs are moved 32 bytes apart as well
+__device__ __forceinline__ int b_swz(int krow) { return (((krow / B_RPW) % B_SWM) << 2) ^ (((krow >> 3) & 1) << 1); }
+#else
 __device__ __forceinline__ int b_swz(int krow) { return ((krow / B_RPW) % B_SWM) << 2; }
+#endif
 
 // One wave-wide 16-byte-per-lane load whose destination is LDS: lane i's 16 bytes, read from
 // base + off (base wave-uniform, off per lane), land at lds_base + 16 * i (lds_base wave-uniform,
@@ -123,6 +162,8 @@ constexpr int lane_period(int per_row, int swz_rows)
 constexpr int PA = lane_period(ACH, A_RPW * A_SWM), PB = lane_period(BCH, B_RPW * B_SWM);
 #elif B_KMAJOR
 constexpr int PA = lane_period(ACH, A_RPW * ACH), PB = PA;
+#elif ATOM == 16
+constexpr int PA = lane_period(ACH, 16), PB = lane_period(BCH, 16);   // both permutations repeat every 16 rows   // B's permutation repeats every 16 k rows
 #else
 constexpr int PA = lane_period(ACH, A_RPW * ACH), PB = lane_period(BCH, B_RPW * B_SWM);
 #endif
@@ -240,8 +281,8 @@ __device__ __forceinline__ void issue_piece(int t, const u16 *__restrict__ Ab, c
 }
 __device__ __forceinline__ frag_t read_a(const u16 *stage, int wm, int lane, int kk, int i)
 {
-    const int row = wm * TM + i * 32 + (lane & 31);
-    const int kc = kk * 2 + (lane >> 5);
+    const int row = wm * TM + i * ATOM + (lane % ATOM);
+    const int kc = kk * (KA / 8) + lane / ATOM;
     return __builtin_bit_cast(frag_t, *(const u32x4 *)(stage + row * BK + ((kc ^ a_swz(row)) << 3)));
 }
 #if A_TRANS
@@ -258,16 +299,21 @@ __device__ __forceinline__ v4s read_a_half(const u16 *stage, int wm, int lane, i
 #if B_KMAJOR
 __device__ __forceinline__ frag_t read_bk(const u16 *stage, int wn, int lane, int kk, int j)
 {
-    const int row = wn * TN + j * 32 + (lane & 31);
-    const int kc = kk * 2 + (lane >> 5);
+    const int row = wn * TN + j * ATOM + (lane % ATOM);
+    const int kc = kk * (KA / 8) + lane / ATOM;
     return __builtin_bit_cast(frag_t, *(const u32x4 *)(stage + A_STAGE + row * BK + ((kc ^ a_swz(row)) << 3)));
 }
 #endif
 __device__ __forceinline__ v4s read_b_half(const u16 *stage, int wn, int lane, int kk, int j, int r)
 {
     const int s = lane & 15;
+#if ATOM == 16
+    const int n = wn * TN + j * 16 + 4 * (s & 3);
+    const int krow = kk * 32 + 8 * (lane >> 4) + 4 * r + (s >> 2);
+#else
     const int n = wn * TN + j * 32 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
     const int krow = kk * 16 + 8 * (lane >> 5) + 4 * r + (s >> 2);
+#endif
     const u16 *p = stage + A_STAGE + krow * BN + (((n >> 3) ^ b_swz(krow)) << 3) + (n & 7);
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)p);
 }
@@ -332,7 +378,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int r = 0; r < ACC_N; ++r) acc[i][j][r] = 0.f;
 
         if (bi > 0) {               // the previous batch: own loads landed, every wave done reading the stages
             WAIT_VMCNT(0);
@@ -400,7 +446,10 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
         for (int k = 0; k < NRG; ++k) group_read(0, ring, 0, k);
 
-        // One group of MFMA steps.  Its MFMAs use buffer half kg & 1; between them the wave issues, one
+        // One group of MFMA steps.  Its MFMAs use one buffer half (the halves alternate from group to group: with
+        // an even number of groups per slab that is kg & 1; with a single group per slab, which 16x16x32 atoms on
+        // slabs of 32 have, the slab's parity, which is its stage's because the ring has an even number of stages);
+        // between them the wave issues, one
         // or two at a time, the reads of the next group's fragments and (in the last group of a slab,
         // after the barrier) the loads that refill the stage.  sched_barrier pins that order.
         auto slab_step = [&](int q, int s) {
@@ -409,11 +458,13 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
                 const bool last = kg + 1 == KG;
                 const int nact = NRG + (last ? PER : 0);
                 const u16 *nstage = ring + (last ? (s + 1) % NSTG : s) * STAGE;
-                const int nkg = last ? 0 : kg + 1, nh = (kg + 1) & 1;
+                static_assert(KG % 2 == 0 || NSTG % 2 == 0, "buffer halves must alternate at compile time");
+                const int cur = (((s & 1) * (KG & 1)) + kg) & 1;
+                const int nkg = last ? 0 : kg + 1, nh = cur ^ 1;
 #pragma unroll
                 for (int m = 0; m < SLOTS; ++m) {
                     const int g = m / (MI * NI), i = (m % (MI * NI)) / NI, j = m % NI;
-                    acc[i][j] = MFMA(A_FRAG((kg & 1) * G + g, i), B_FRAG((kg & 1) * G + g, j), acc[i][j]);
+                    acc[i][j] = MFMA(A_FRAG(cur * G + g, i), B_FRAG(cur * G + g, j), acc[i][j]);
                     if (m == 0 && last) {
                         WAIT_LGKM_VMCNT((NSTG - 2) * PER);
                         BARRIER();
@@ -449,20 +500,20 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         // a load that arrives after the workgroup's LDS has been handed to another workgroup would
         // write into memory this kernel no longer owns.
         WAIT_VMCNT(0);
-        // Epilogue: an atom's result sits with column (l % 32) in lane l, register r being
-        // row 8*(r/4) + 4*(l/32) + r%4.
+        // Epilogue: an atom's result sits with column (l % ATOM) in lane l; 32x32 atoms: register r is
+        // row 8*(r/4) + 4*(l/32) + r%4; 16x16 atoms: row 4*(l/16) + r.
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r / 4) + 4 * (lane / 32) + r % 4;
+                for (int r = 0; r < ACC_N; ++r) {
+                    const int row = ATOM == 16 ? 4 * (lane / 16) + r : 8 * (r / 4) + 4 * (lane / 32) + r % 4;
 #if OP == OP_CONV
                     if (TN % 32 != 0 && j * 32 + (lane & 31) >= TN) continue;   // overhang of a ragged wave tile
                     float *dst = &C[conv_c_index(cb, m0 + wm * TM + i * 32 + row, wn * TN + j * 32 + (lane & 31))];
 #else
-                    float *dst = &Cb[(long)(m0 + wm * TM + i * 32 + row) * N + n0 + wn * TN + j * 32 + (lane & 31)];
+                    float *dst = &Cb[(long)(m0 + wm * TM + i * ATOM + row) * N + n0 + wn * TN + j * ATOM + (lane % ATOM)];
 #endif
 #if KSPLIT > 1
                     c_out(dst, acc[i][j][r]);

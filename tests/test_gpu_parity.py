@@ -439,7 +439,7 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
     _say("  oracle rows/entries for 8192^3 ...")
     ref_rows = T.matmul_rows(w.a_host, w.b_host, rows)
     ref_ent = T.matmul_entries(w.a_host, w.b_host, ei, ej)
-    V4, VT = P.OPEVO_TILE4, P.OPEVO_TILE4T
+    V4, VT, VA = P.OPEVO_TILE4, P.OPEVO_TILE4T, P.OPEVO_TILE4A
     # (label, space, configuration, template path the decoder must choose)
     cases = [("direct-to-LDS 256x256, 4 waves of 128x128, 2 stages of 64", V4, [32, 2, 1, 128, 32, 2, 1, 128, 128, 64, 1], 3),
              ("direct-to-LDS 256x128, 8 waves, 4 stages of 32", V4, [32, 4, 2, 32, 64, 2, 2, 32, 256, 32, 1], 3),
@@ -455,7 +455,13 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
              ("second operand transposed by the pre-pass, 256x256, 4 waves, 4 stages of 32", VT, [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1, 1], 3),
              ("second operand transposed by the pre-pass, 256x256, 8 waves, 2 stages of 64", VT, [32, 2, 4, 32, 32, 4, 8, 8, 128, 64, 1, 1], 3),
              ("second operand transposed by the pre-pass, 128x128, 2 stages of 128", VT, [64, 2, 2, 32, 64, 2, 2, 32, 64, 128, 1, 1], 3),
-             ("bpack = 1 on a register-staged member: inert", VT, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1], 1)]
+             ("bpack = 1 on a register-staged member: inert", VT, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1], 1),
+             ("direct-to-LDS on 16x16x32 atoms, 256x256, 4 waves of 128x128, 4 stages of 32", VA, [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1, 1], 3),
+             ("direct-to-LDS on 16x16x32 atoms, 256x256, 8 waves of 128x64, 4 stages of 32", VA, [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1, 1], 3),
+             ("direct-to-LDS on 16x16x32 atoms, 256x256, 4 waves of 256x64, 4 stages of 32", VA, [32, 1, 256, 1, 32, 4, 4, 16, 256, 32, 1, 1], 3),
+             ("direct-to-LDS on 16x16x32 atoms, 128x256, 4 waves of 64x128, 3 stages of 64", VA, [64, 2, 2, 32, 32, 2, 4, 32, 128, 64, 1, 1], 3),
+             ("direct-to-LDS on 16x16x32 atoms, 128x128, 4 waves of 64x64, 2 stages of 128", VA, [64, 2, 2, 32, 64, 2, 2, 32, 64, 128, 1, 1], 3),
+             ("atom = 1 on a register-staged member: inert", VA, [32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1], 1)]
     for cfg in w.random_valid(V4, 6, seed=606, want_paths=(1, 2, 3)):
         cases.append(("random", V4, list(cfg), None))
     for label, variant, cfg, path in cases:
@@ -464,6 +470,8 @@ def test_matmul_8192_bf16_sampled_rows_and_entries(torch_cuda):
             assert P.opevo_kernel_plan(w.op, variant, cfg).path == path, label
         if variant == VT:
             assert ("-DB_KMAJOR=1" in P.opevo_kernel_defines(w.op, variant, cfg)) == (path == 3), label
+        if variant == VA:
+            assert ("-DATOM=16" in P.opevo_kernel_defines(w.op, variant, cfg).split()) == (path == 3), label
         out = w.run(variant, cfg)
         if out is None:
             assert label == "random", label
@@ -508,6 +516,39 @@ def test_matmul_second_operand_packed_by_a_prepass(torch_cuda):
     w = Workload(torch_cuda, "matmul", (192, 320, 448), "bf16", 77)
     for cfg in w.random_valid(V, 8, seed=1313, want_paths=(3,)):
         w.check(V, cfg, "random")
+    w.close()
+
+
+def test_matmul_on_16x16x32_atoms_of_the_direct_to_lds_template(torch_cuda):
+    """TILE4A: M(4) N(4) K(2) unroll atom.  atom = 1 on a direct-to-LDS member: the same tiles multiplied with
+    16x16x32 MFMAs (B's stage part permuted for the 16-column transposing reads); elsewhere inert."""
+    V = P.OPEVO_TILE4A
+    w = Workload(torch_cuda, "matmul", (512, 1024, 1024), "bf16", 1235)
+    for label, cfg, _ in MM1_CASES:
+        c = list(cfg) + [1]
+        plan = P.opevo_kernel_plan(w.op, V, c)
+        assert plan.path == P.opevo_kernel_plan(w.op, P.OPEVO_TILE4, cfg).path, label
+        if plan.path != 3:
+            assert "-DATOM=16" not in P.opevo_kernel_defines(w.op, V, c).split() or plan.path == 2, label
+        w.check(V, c, label + ", atom 1")
+    n16 = 0
+    for cfg in w.random_valid(V, 24, seed=1616, want_paths=(3,)):
+        n16 += "-DATOM=16" in P.opevo_kernel_defines(w.op, V, cfg).split()
+        w.check(V, cfg, "random")
+    assert n16 >= 6, n16
+    w.close()
+    # a shape whose axes are no powers of two (multi-prime factor graphs)
+    w = Workload(torch_cuda, "matmul", (192, 320, 448), "bf16", 77)
+    for cfg in w.random_valid(V, 12, seed=1717, want_paths=(3,)):
+        w.check(V, cfg, "random")
+    w.close()
+    # fp16 inputs
+    w = Workload(torch_cuda, "matmul", (256, 256, 512), "f16", 78)
+    for label, cfg in [("128x128, 4 waves of 64x64, slabs of 64", [2, 2, 2, 32, 2, 2, 2, 32, 8, 64, 1, 1]),
+                       ("64x128, 2 waves of 64x64, slabs of 32", [4, 1, 2, 32, 2, 2, 2, 32, 16, 32, 1, 1])]:
+        plan = P.opevo_kernel_plan(w.op, V, cfg)
+        assert plan.path == 3 and "-DATOM=16" in P.opevo_kernel_defines(w.op, V, cfg).split(), label
+        w.check(V, cfg, label)
     w.close()
 
 

@@ -552,3 +552,66 @@ def test_packed_second_operand_templates_compile(label, kd, cfg):
     kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4T, cfg)
     assert 1000 < P.opevo_kernel_code_size(kernel) < (128 << 10)
     P.opevo_kernel_destroy(kernel)
+
+
+# ---------------------------------------------------------------- MatMul: the MFMA atom of direct-to-LDS members as a choice (TILE4A)
+def test_atom_choice_space_and_its_decoding():
+    op = _op((P.OPEVO_MATMUL, (8192, 8192, 8192)), P.OPEVO_BF16)
+    V = P.OPEVO_TILE4A
+    sp = P.opevo_op_space(op, V)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["M", "N", "K", "unroll", "atom"] and P.opevo_space_width(sp) == 12
+    assert P.opevo_space_size(sp) == 2 * P.opevo_space_size(P.opevo_op_space(op, P.OPEVO_TILE4))
+    P.opevo_space_destroy(sp)
+    for other in (CONV56, (P.OPEVO_BMM, (128, 128, 128, 64))):
+        with pytest.raises(P.OpevoError):
+            P.opevo_op_space(_op(other, P.OPEVO_BF16), V)
+    cfg = [32, 2, 8, 16, 32, 4, 2, 32, 256, 32, 1]                 # 256 x 256 tile, 8 waves of 128 x 64, 4 stages of 32
+    for atom in (0, 1):
+        plan = P.opevo_kernel_plan(op, V, cfg + [atom])
+        same = P.opevo_kernel_plan(op, P.OPEVO_TILE4, cfg)
+        d = P.opevo_kernel_defines(op, V, cfg + [atom]).split()
+        # same tiles, same ring, same accumulators per lane: only the atom differs
+        assert (plan.status, plan.path, plan.lds_bytes, plan.block, plan.acc_per_lane) == (P.OPEVO_OK, 3, same.lds_bytes, same.block, same.acc_per_lane)
+        assert ("-DATOM=16" in d) == (atom == 1) and ("-DATOM=32" in d) == (atom == 0)
+    # inert on the other templates, ...
+    for c in ([32, 2, 1, 128, 32, 2, 1, 128, 512, 16, 1, 1], [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 0, 1]):
+        assert P.opevo_kernel_plan(op, V, c).path == 1 and "-DATOM=32" in P.opevo_kernel_defines(op, V, c).split()
+    # ... with a transposed first operand there is no such space at all, and a member whose ring has an odd number of
+    # stages keeps the 32x32x16 atoms when a slab is a single K step of the small atom (the fragment buffers alternate
+    # per step, and which one a step uses must be known at compile time)
+    mm = _op((P.OPEVO_MATMUL, (512, 1024, 1024)), P.OPEVO_BF16)
+    n_odd = 0
+    sp = P.opevo_op_space(mm, V)
+    rng = P.opevo_rng_create(5)
+    for _ in range(40000):
+        c = P.opevo_space_random(sp, rng)
+        plan = P.opevo_kernel_plan(mm, V, c)
+        if plan.status != P.OPEVO_OK or plan.path != 3 or c[11] != 1:
+            continue
+        d = dict(t[2:].split("=") for t in P.opevo_kernel_defines(mm, V, c).split(":", 1)[1].split() if "=" in t)
+        if int(d["NSTG"]) % 2 == 1 and int(d["BK"]) == 32:
+            n_odd += 1
+            assert d["ATOM"] == "32", list(c)
+        if d["ATOM"] == "16":
+            assert int(d["BK"]) % 32 == 0 and int(d["TM"]) % 16 == 0 and "B_KMAJOR" not in d and d["A_TRANS"] == "0"
+    P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+
+
+TILE4A_COMPILE_CASES = [
+    ("256x256, 8 waves of 128x64, 2 stages of 64 (the member the 8192^3 searches end on)", (P.OPEVO_MATMUL, (8192, 8192, 8192)), [32, 2, 64, 2, 32, 4, 4, 16, 128, 64, 1, 1]),
+    ("256x256, 4 waves of 128x128, 4 stages of 32: 64 MFMAs per step", (P.OPEVO_MATMUL, (8192, 8192, 8192)), [32, 2, 2, 64, 32, 2, 2, 64, 256, 32, 1, 1]),
+    ("one wave of 32 x 64, slabs of 64", MM1, [16, 1, 1, 32, 16, 1, 2, 32, 16, 64, 1, 1]),
+    ("2 stages of 128", MM1, [4, 2, 1, 64, 8, 2, 1, 64, 8, 128, 1, 1]),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg", TILE4A_COMPILE_CASES, ids=[c[0] for c in TILE4A_COMPILE_CASES])
+def test_direct_to_lds_members_on_16x16x32_atoms_compile_fully_unrolled(label, kd, cfg):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4A, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == 3, (plan.reason, plan.path)
+    assert "-DATOM=16" in P.opevo_kernel_defines(op, P.OPEVO_TILE4A, cfg).split()
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4A, cfg)
+    assert 1000 < P.opevo_kernel_code_size(kernel) < (128 << 10)
+    P.opevo_kernel_destroy(kernel)
