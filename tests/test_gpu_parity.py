@@ -57,7 +57,10 @@ REFUSED_RANDOM = []         # seeded random members refused for the same reason
 # refused fails its test: it was chosen to cover a code path and no longer does.
 MAY_SPILL = ("may spill: 128 x 16 tile, one wave, slab 128, two partitions", "may spill: the same with one partition",
              # derived from a TILE4 case by splitting its reduction: the split costs the registers that were left
-             "mfma32 8 rows x 56, 3 partition(s), layout 0")
+             "mfma32 8 rows x 56, 3 partition(s), layout 0",
+             # derived from a TILE4 case by choosing the small atom: four waves per SIMD leave 128 registers each, and two
+             # sets of 16x16x32 fragments for a 64 x 64 wave tile need more than the 64 left beside the accumulators
+             "direct-to-LDS, 16 waves of 64x64, atom 1")
 N_RANDOM = [0]              # seeded random members checked
 
 
