@@ -65,7 +65,7 @@ def main() -> int:
                          "number of workgroups that share an output tile (partial sums added atomically)")
     ap.add_argument("--split-reduction", action="store_true",
                     help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
-    ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T", "TILE4A"],
+    ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T", "TILE4A", "TILE4L"],
                     help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4C for Conv2d, TILE4A for the 16-bit 8192^3 MatMul, else TILE4)")
     ap.add_argument("--extended", action="store_true",
                     help="tune in the extended space (launch order as a permutation, group width as a discrete parameter)")
@@ -137,7 +137,7 @@ def main() -> int:
             return 2
         variant = P.OPEVO_TILE4P
     names = {"TILE2": P.OPEVO_TILE2, "TILE4": P.OPEVO_TILE4, "TILE4X": P.OPEVO_TILE4X, "TILE4P": P.OPEVO_TILE4P,
-             "TILE4K": P.OPEVO_TILE4K, "TILE4C": P.OPEVO_TILE4C, "TILE4T": P.OPEVO_TILE4T, "TILE4A": P.OPEVO_TILE4A}
+             "TILE4K": P.OPEVO_TILE4K, "TILE4C": P.OPEVO_TILE4C, "TILE4T": P.OPEVO_TILE4T, "TILE4A": P.OPEVO_TILE4A, "TILE4L": P.OPEVO_TILE4L}
     if args.space:
         variant = names[args.space]
     elif w["kind"] == "conv2d" and variant == P.OPEVO_TILE4:

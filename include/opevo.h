@@ -254,9 +254,22 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         (same tiles, same LDS traffic, twice the MFMA instructions, a quarter of the accumulator updates per
  *         flop: under the chip's power limit the matrix pipes sustain about a tenth more flops per second on
  *         changing operands that way, while kernels bound by instruction issue lose).  Elsewhere, and where the
- *         unrolled loop body would grow too long, atom = 1 runs the atom = 0 kernel. */
+ *         unrolled loop body would grow too long, atom = 1 runs the atom = 0 kernel.
+ *  TILE4L: Conv2d only: the input channels in two factors and a three-way choice of the operand path,
+ *         Conv2d  B(2) Cout(4) H(4) W(4) Cin(2) unroll{0,1} layout{0,1,2},  Cin = (slabs, channels per slab)
+ *         layout = 0: operands as the caller stores them, reduction walked as (ci, r, s): a slab is the slab's
+ *         channels with all their Hk*Wk taps (TILE4 with R = (slabs, channels per slab * Hk * Wk)).
+ *         layout = 1: channels-last copies written by a pre-pass inside the timed launch, as in TILE4C;
+ *         walked as (r, s, ci), a slab being the slab's channels under one tap.
+ *         layout = 2: an LDS-resident image patch (App. B.3's loop nest with the taps innermost): per slab the
+ *         workgroup stages the input pixels under its box of output pixels once, channels fastest, straight from
+ *         the NCHW image, and the slab's part of the OIHW kernel tensor re-ordered tap by tap; every tap then
+ *         reads its operands from that patch at a fixed offset from the output pixel.  One launch, no pre-pass,
+ *         each staged pixel re-used by all taps that touch it.  16-bit inputs, an even image width, slabs of
+ *         whole 16 channels (32 on 16x16x32 atoms), at most 16 waves, and patch + kernel-tensor part within the
+ *         LDS; elsewhere layout = 2 runs the layout = 0 kernel.  Same sum in another order. */
 typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4, OPEVO_TILE4C = 5, OPEVO_TILE4T = 6,
-               OPEVO_TILE4A = 7 } opevo_variant;
+               OPEVO_TILE4A = 7, OPEVO_TILE4L = 8 } opevo_variant;
 
 /* dims:  MATMUL {M, N, K}            C[M,N] = A[M,K] B[K,N]
  *        BMM    {B, M, N, K}         C[b] = A[b] B[b]
@@ -279,7 +292,8 @@ int opevo_op_space(const opevo_op *op, int variant, opevo_space **out);
 typedef struct {
     int32_t status;        /* OPEVO_OK or OPEVO_E_INVALID                                      */
     int32_t path;          /* 0 scalar FMA, 1 MFMA 32x32x16, 2 MFMA 16x16x32, 3 MFMA 32x32x16 with
-                              operands streamed global -> LDS directly, 4 fp32 MFMA 32x32x2    */
+                              operands streamed global -> LDS directly, 4 fp32 MFMA 32x32x2,
+                              5 Conv2d with an LDS-resident image patch (either atom)          */
     int32_t grid[3];
     int32_t block;         /* threads per workgroup                                            */
     int32_t lds_bytes;

@@ -25,7 +25,7 @@ OPEVO_E_HIPRTC, OPEVO_E_HIP, OPEVO_E_PARITY, OPEVO_E_TOO_LARGE, OPEVO_E_STATE = 
 OPEVO_FACTOR, OPEVO_PERMUTATION, OPEVO_DISCRETE, OPEVO_CATEGORICAL = 0, 1, 2, 3
 OPEVO_MATMUL, OPEVO_BMM, OPEVO_CONV2D, OPEVO_BMM_TA = 0, 1, 2, 3
 OPEVO_F32, OPEVO_BF16, OPEVO_F16 = 0, 1, 2
-OPEVO_TILE2, OPEVO_TILE4, OPEVO_TILE4X, OPEVO_TILE4P, OPEVO_TILE4K, OPEVO_TILE4C, OPEVO_TILE4T, OPEVO_TILE4A = 0, 1, 2, 3, 4, 5, 6, 7
+OPEVO_TILE2, OPEVO_TILE4, OPEVO_TILE4X, OPEVO_TILE4P, OPEVO_TILE4K, OPEVO_TILE4C, OPEVO_TILE4T, OPEVO_TILE4A, OPEVO_TILE4L = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 
 class OpevoError(RuntimeError):

@@ -143,8 +143,9 @@ int time_kernel(opevo_kernel *k, const void *a, const void *b, void *c, hipStrea
     if (samples < 1) return fail(OPEVO_E_ARG, "kernel_time: samples must be >= 1");
     if (int rc = load_kernel(k)) return rc;
     unsigned long long *ctl = nullptr;
-    // the scalar template and folded members of the register-staged templates honour a deadline
-    if (timeout_ms > 0.0 && k->plan.path != 3)
+    // the scalar template and folded members of the register-staged templates honour a deadline (the direct-to-LDS
+    // and LDS-resident-patch templates have no folded members)
+    if (timeout_ms > 0.0 && k->plan.path != 3 && k->plan.path != 5)
         if (int rc = deadline_ctl(&ctl)) return rc;
     // samples + 1 events: the samples run back to back, without a host round trip (and an idle
     // GPU) between them; only the first, estimating launch is followed by a synchronisation

@@ -112,6 +112,17 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
                  factor("R", op.K, 3), flag("unroll"), flag("layout")};
         return OPEVO_OK;
     }
+    if (variant == OPEVO_TILE4L) {
+        // Conv2d with the input channels in two factors (slabs, channels per slab; every slab holds all the
+        // taps) and a three-way choice of how the operands reach the matrix units: gathered from the NCHW
+        // image value by value, channels-last copies written by a pre-pass, or an LDS-resident image patch
+        // filled straight from the NCHW image
+        if (op.kind != OPEVO_CONV2D) return fail(OPEVO_E_ARG, "the space with an LDS-resident image patch exists for Conv2d only");
+        descs = {factor("B", op.nimg, 2), factor("Cout", op.M, 4), factor("H", op.hout, 4), factor("W", op.wout, 4),
+                 factor("Cin", op.cin, 2), flag("unroll"), flag("layout")};
+        descs.back().n_values = 3;
+        return OPEVO_OK;
+    }
     if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
     switch (op.kind) {
     case OPEVO_MATMUL:
@@ -189,7 +200,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int flagv = 0;
     int64_t nb2 = 1, BH = 1, BW = 1, h1 = 1, w1 = 1;
     bool four_level = (variant == OPEVO_TILE4 || variant == OPEVO_TILE4X || variant == OPEVO_TILE4P || variant == OPEVO_TILE4K ||
-                       variant == OPEVO_TILE4C || variant == OPEVO_TILE4T || variant == OPEVO_TILE4A);
+                       variant == OPEVO_TILE4C || variant == OPEVO_TILE4T || variant == OPEVO_TILE4A || variant == OPEVO_TILE4L);
     int atom16 = 0;                        // MatMul, TILE4A: 1 = 16x16x32 atoms on direct-to-LDS members
     int bpack = 0;                         // MatMul, TILE4T: 1 = second operand transposed to [N][K] by a pre-pass
     int layout = 0;                        // Conv2d, TILE4C: 1 = channels-last operands (pre-pass)
@@ -198,6 +209,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t box[6] = {1, 1, 1, 1, 1, 1};   // C_in, H_k, W_k as (boxes, box extent) pairs
     bool tap_box = false;
     int64_t kunroll = 0;                   // 0: the template's default
+    int64_t patch_cs = 0;                  // Conv2d, TILE4L, layout 2: channels per slab of the LDS-resident patch (0: not on that template)
+    int patch_atom = 0, patch_stages = 1;
     int tile4_width = 0;   // slots of the four-level part, after which the launch-order parameters follow
 
     if (!four_level) {
@@ -239,6 +252,34 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         } else if (variant == OPEVO_TILE4C) {
             ksplit = c[14]; b1 = ksplit; ksteps = c[15]; BK = c[16]; flagv = c[17]; layout = c[18];
             tile4_width = 19;
+        } else if (variant == OPEVO_TILE4L) {
+            const int64_t taps = op.hk * op.wk;
+            flagv = c[16];
+            tile4_width = 18;
+            if (c[17] == 1) { layout = 1; ksteps = taps * c[14]; BK = c[15]; }   // channels-last walk (r, s, ci): a slab is c[15] channels of one tap
+            else { ksteps = c[14]; BK = c[15] * taps; }                          // walk (ci, r, s): a slab is c[15] channels with all their taps
+            // layout 2: the LDS-resident patch, for members it can hold (the others run as with layout 0).
+            // 32x32x16 atoms need slabs of whole 16 channels, 16x16x32 atoms of 32; the wave's pixel side is
+            // rounded up to whole atoms while that at most doubles the work; the atom that wastes less is taken.
+            if (c[17] == 2 && op.dtype != OPEVO_F32) {
+                const int64_t cs = c[15], nw = WM * WN, nt = 64 * nw;
+                auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
+                auto fits = [&](int64_t at) {
+                    return TM % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(TN, at) <= 2 * TN && TM * up(TN, at) <= 64 * kMaxAcc;
+                };
+                const int at = fits(32) && (!fits(16) || up(TN, 32) == up(TN, 16)) ? 32 : fits(16) ? 16 : 0;
+                const int64_t ph = (BH - 1) * op.stride + op.hk, pw = (BW - 1) * op.stride + op.wk;
+                const int st = (flagv && ksteps > 1) ? 2 : 1;
+                const int64_t lds_p = st * ((nb2 * ph * pw + taps * WM * TM) * (cs + 8) + 64) * 2;   // + the dump words of a stage
+                const int64_t fill_p = (cs * nb2 * ph * (pw / 2 + 1) + nt - 1) / nt, fill_a = (WM * TM * cs * taps / 8 + nt - 1) / nt;
+                // registers: a lane has 512 / (waves per SIMD); the fill keeps 3 per pair of pixels and 6 per piece of the
+                // kernel tensor (plan and data in flight) next to the accumulators; 64 are left for fragments and addresses
+                const int64_t regs = 512 / ((nw + 3) / 4) - (at ? TM * up(TN, at) / 64 : 0) - 64;
+                if (at && nt <= kMaxThreads && lds_p <= kMaxLds && op.win % 2 == 0 && 3 * fill_p + 6 * fill_a <= regs &&
+                    op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
+                    patch_cs = cs; patch_atom = at; patch_stages = st;
+                }
+            }
         } else {
             ksteps = c[14]; BK = c[15]; flagv = c[16];
             tile4_width = 17;
@@ -255,7 +296,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     //    multiple of 32;
     //  * more than 16 waves (below): the workgroup runs the largest divisor of their number that fits,
     //    and every real wave takes the tiles of several waves one after another, each with the whole K loop.
-    if (four_level) {
+    if (four_level && !patch_cs) {
         auto smallest_prime = [](int64_t n) { for (int64_t q = 2; q * q <= n; ++q) if (n % q == 0) return q; return n; };
         // The registers a lane may use depend on how many waves share a SIMD (512 for one, 256 for two,
         // 128 for four): a member that is folded anyway gets wave tiles that leave room for fragments
@@ -391,6 +432,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             path = 4; BKP = (BK + 7) / 8 * 8; TMacc = TMp; TNacc = TNp;
         }
     }
+    if (patch_cs) { path = 5; BKP = BK; ragged = false; TMacc = TM; TNacc = (TN + patch_atom - 1) / patch_atom * patch_atom; }
     const bool stage_lds = path == 4 || !(op.kind == OPEVO_BMM && four_level && flagv == 0 && path != 0);
     // Direct global->LDS streaming (path 3) for pipelined MatMul / BMM members of 32x32 atoms whose
     // slabs split into whole 1 KiB wave loads and whose row lengths suit the chunk permutation.  With
@@ -426,7 +468,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         if (NT > 256) NT = 256;
     }
     int64_t acc = (path == 0) ? (BM * BN + NT - 1) / NT : (TMacc * TNacc) / 64;
-    const int nstage = path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
+    const int nstage = path == 5 ? patch_stages : path == 3 ? nstage_dlds : (path != 0 && flagv && ksteps > 1) ? 2 : 1;
     int64_t lds = 0;
     if (path == 0) lds = (BM * BK + BK * BN) * 4;
     else if (path == 4 && op.kind == OPEVO_CONV2D) {
@@ -435,6 +477,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     }
     else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (anr + (b_kmajor ? bnr : BN)) * BK * 2;
+    else if (path == 5)
+        lds = nstage * ((nb2 * ((BH - 1) * op.stride + op.hk) * ((BW - 1) * op.stride + op.wk) + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
     p.path = path;
@@ -461,7 +505,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                                                        : (BM * (BK / 4) + NT - 1) / NT + (BK * (BN / 4) + NT - 1) / NT;
         if (chunks * 4 > 256) invalid(p, "%ld staging registers per lane > 256", long(chunks * 4));
     }
-    else if (path != 0 && path != 3 && stage_lds) {
+    else if (path != 0 && path != 3 && path != 5 && stage_lds) {
         // register budget of the slab in flight: 16-byte pieces per thread
         const int64_t a_chunks = op.trans_a ? 8 * (((BK / 8) * (BM / 8) + NT - 1) / NT) : (BM * (BKP / 8) + NT - 1) / NT;
         const int64_t b_chunks = (op.kind == OPEVO_CONV2D) ? (BN * (BKP / 8) + NT - 1) / NT
@@ -470,12 +514,12 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             invalid(p, "%ld staging registers per lane > 256", long((a_chunks + b_chunks) * 4));
     }
 
-    out.tmpl = path == 0 ? "gemm_scalar" : path == 3 ? "gemm_mfma_dlds" : path == 4 ? "gemm_mfma_f32" : "gemm_mfma";
+    out.tmpl = path == 0 ? "gemm_scalar" : path == 3 ? "gemm_mfma_dlds" : path == 4 ? "gemm_mfma_f32" : path == 5 ? "conv_patch" : "gemm_mfma";
     // one symbol per configuration, so profiles list each instantiated kernel on its own line
     {
         std::ostringstream nm;
         nm << "opevo_" << (op.kind == OPEVO_MATMUL ? "mm" : op.kind == OPEVO_BMM ? (op.trans_a ? "bmmt" : "bmm") : "conv")
-           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : variant == OPEVO_TILE4C ? "c" : variant == OPEVO_TILE4T ? "t" : variant == OPEVO_TILE4A ? "a" : four_level ? "4" : "2");
+           << (variant == OPEVO_TILE4P ? "p" : variant == OPEVO_TILE4K ? "k" : variant == OPEVO_TILE4C ? "c" : variant == OPEVO_TILE4T ? "t" : variant == OPEVO_TILE4A ? "a" : variant == OPEVO_TILE4L ? "l" : four_level ? "4" : "2");
         int width = 0;
         for (const auto &d : descs) width += d.type == OPEVO_FACTOR ? d.nu : d.type == OPEVO_PERMUTATION ? d.n_values : 1;
         for (int i = 0; i < width; ++i) nm << "_" << cfg[i];
@@ -486,7 +530,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
       << " -DK=" << op.K << " -DBM=" << BM << " -DBN=" << BN << " -DBK=" << BK << " -DKSTEPS=" << ksteps
       << " -DNT=" << NT << " -DBATCH_INNER=" << binner << " -DFLAG=" << flagv << " -DA_TRANS=" << (op.trans_a ? 1 : 0);
     if (path != 0) {
-        D << " -DATOM=" << ((path == 2 || dlds_atom16) ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
+        D << " -DATOM=" << (path == 5 ? patch_atom : (path == 2 || dlds_atom16) ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
           << " -DNSTAGE=" << nstage << " -DNSTG=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
         if (nwr != WM * WN) D << " -DNWR=" << nwr;
@@ -510,6 +554,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     if (tap_box)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
           << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
+    if (path == 5) D << " -DCS=" << patch_cs;
     if (b_kmajor) D << " -DB_KMAJOR=1 -DBNR=" << bnr;
     if (path == 3 && anr != BM) D << " -DANR=" << anr;
     if (kunroll) D << " -DKUNROLL=" << kunroll;

@@ -1,0 +1,276 @@
+// Conv2d kernel template with an LDS-resident image patch (bf16 / fp16 inputs, fp32 accumulation) for gfx950.
+//
+// The convolution of App. B.3 (Eq. 5 with stride and padding) as an implicit GEMM whose operands stay in
+// the layouts the caller hands over (image NCHW, kernel tensor OIHW): no pre-pass, one launch.
+// A workgroup owns BM output channels x a box of NB2 images x BH rows x BW pixels, as on the other
+// templates; WM x WN waves, wave (wm, wn) owning channels [wm*TM, +TM) and columns [wn*TN, +TN) of the
+// flattened box, in ATOM x ATOM MFMA atoms (32x32x16 or 16x16x32).
+//
+// The reduction is walked in KSTEPS slabs of CS input channels, every slab with all HK*WK taps.  Per slab
+// the workgroup holds in LDS
+//   * the patch: the input pixels under its box for the slab's channels, channels fastest,
+//     P[image][py][px][CS (+8)], PH = (BH-1)*STRIDE + HK rows by PW = (BW-1)*STRIDE + WK columns.  An output
+//     pixel (y, x) under tap (r, s) reads patch pixel (y*STRIDE + r, x*STRIDE + s): the 8 channels an MFMA lane
+//     wants are 16 contiguous bytes, and the tap is a compile-time offset from the lane's own pixel, so one
+//     staged pixel serves all the taps that touch it.  Positions outside the image (padding) are zeros: both
+//     stages are cleared once, and the fill only ever writes positions inside the image, whose place in the
+//     patch is the same for every slab.
+//   * the kernel tensor's part, A[tap][BM][CS (+8)], so that an A fragment is 16 contiguous bytes too.
+// Both parts are transposed on the way in: a thread loads 4-byte pairs of pixels of one channel (rows of the
+// NCHW image are contiguous in x; WIN is even, so aligned pairs never straddle a row) or 16-byte pieces of a
+// kernel-tensor row (CS*HK*WK contiguous values, channel-major) into registers and writes the values to
+// their transposed places one by one (2-byte LDS stores).  The padding of 8 elements per row makes 16
+// consecutive rows start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
+//
+// FLAG = 1: two stages; the global loads of slab s+1 are in flight (in registers) while slab s is multiplied,
+//           and are written to the other stage afterwards: one barrier per slab.
+// FLAG = 0: one stage: load, barrier, store, barrier, multiply.
+
+#if IN_DTYPE == 1
+typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
+#define MFMA_32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#define MFMA_16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0)
+#else
+typedef __attribute__((ext_vector_type(8))) _Float16 frag_t;
+#define MFMA_32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+#define MFMA_16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0)
+#endif
+
+#if ATOM == 32
+typedef f32x16 acc_t;
+#define KA 16
+#define NACC 16
+#define MFMA(a, b, c) MFMA_32(a, b, c)
+#else
+typedef f32x4 acc_t;
+#define KA 32
+#define NACC 4
+#define MFMA(a, b, c) MFMA_16(a, b, c)
+#endif
+
+constexpr int T = HK * WK;                                    // taps
+constexpr int PH = (BH - 1) * STRIDE + HK, PW = (BW - 1) * STRIDE + WK;
+constexpr int NPIX = NB2 * PH * PW;                           // patch pixels
+constexpr int PITCH = CS + 8;                                 // elements per patch pixel / per kernel-tensor row
+constexpr int DUMP = 64;                                      // elements at the end of a stage that take the stores of pixels outside the patch
+constexpr int P_STAGE = NPIX * PITCH, A_STAGE = T * BM * PITCH, STAGE = P_STAGE + A_STAGE + DUMP;   // elements
+constexpr int MI = TM / ATOM, NI = (TN + ATOM - 1) / ATOM;    // atoms per wave tile (the last column of atoms may hang over)
+constexpr int KK = CS / KA;                                   // MFMA steps per tap
+static_assert(TM % ATOM == 0 && CS % KA == 0 && WIN % 2 == 0 && BK == CS * T && KSTEPS * CS == CIN, "decoder and template disagree");
+static_assert(NSTG * STAGE * 2 <= 160 * 1024, "stages exceed the LDS");
+
+// patch fill: tasks of one aligned pair of pixels each, pair index fastest, then patch row, image, channel
+constexpr int NPAIR = PW / 2 + 1;                             // aligned pairs that cover PW columns from either parity
+constexpr int P_TASKS = CS * NB2 * PH * NPAIR;
+constexpr int NPT = (P_TASKS + NT - 1) / NT;
+// kernel-tensor fill: 16-byte pieces, piece index along the row fastest
+constexpr int PPR = CS * T / 8;                               // pieces per row of a slab
+constexpr int A_PIECES = BM * PPR;
+constexpr int NAP = (A_PIECES + NT - 1) / NT;
+
+struct Fill {
+    u32 pg[NPT];     // byte offset of the pair inside the image tensor for slab 0
+    u32 pd0[NPT], pd1[NPT];   // element offsets in the stage of the pair's two pixels; one that is outside the patch or the
+                              // image goes to the dump words at the end of the stage (the stores are unconditional)
+    u32 ag[NAP];     // byte offset of the piece inside the kernel tensor for slab 0
+    u32 ad[NAP];     // element offset of the piece's first value in the A part | its tap << 24; ~0: no piece
+};
+struct Regs {
+    u32 p[NPT];
+    u32x4 a[NAP];
+};
+
+__device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, int tid)
+{
+    const int yin0 = cb.y0 * STRIDE - PAD_CONV, xin0 = cb.x0 * STRIDE - PAD_CONV;
+    const int xs = xin0 & ~1;                                 // first aligned pair at or left of the patch
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int q = tid + i * NT;
+        const int jp = q % NPAIR, py = (q / NPAIR) % PH, b = (q / (NPAIR * PH)) % NB2, c = q / (NPAIR * PH * NB2);
+        const int y = yin0 + py, x = xs + 2 * jp, px = x - xin0;   // px: patch column of the pair's first pixel (-1 .. PW)
+        const bool in = (P_TASKS % NT == 0 || q < P_TASKS) && y >= 0 && y < HIN && x >= 0 && x < WIN;
+        const bool v0 = in && px >= 0 && px < PW, v1 = in && px + 1 >= 0 && px + 1 < PW;
+        f.pg[i] = (v0 || v1) ? 2u * (u32)((((cb.nb0 + b) * CIN + c) * HIN + y) * WIN + x) : 0u;
+        const int d0 = ((b * PH + py) * PW + px) * PITCH + c, dump = STAGE - DUMP + (tid & 31) * 2;
+        f.pd0[i] = (u32)(v0 ? d0 : dump);
+        f.pd1[i] = (u32)(v1 ? d0 + PITCH : dump + 1);
+    }
+#pragma unroll
+    for (int i = 0; i < NAP; ++i) {
+        const int q = tid + i * NT;
+        const int m = q / PPR, p = q % PPR;
+        const int c = (8 * p) / T, tap = (8 * p) % T;
+        const bool on = A_PIECES % NT == 0 || q < A_PIECES;
+        f.ag[i] = on ? 2u * (u32)((m0 + m) * K + 8 * p) : 0u;
+        f.ad[i] = on ? (u32)((tap * BM + m) * PITCH + c) | ((u32)tap << 24) : ~0u;
+    }
+}
+
+// global loads of slab s into registers (unconditional: a task with nothing to do reads the slab's first bytes)
+__device__ __forceinline__ void load_slab(Regs &r, const Fill &f, const u16 *__restrict__ A, const u16 *__restrict__ B, int s)
+{
+    const char *Bs = (const char *)(B + (long)s * CS * HIN * WIN);
+    const char *As = (const char *)(A + (long)s * CS * T);
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) r.p[i] = *(const u32 *)(Bs + f.pg[i]);
+#pragma unroll
+    for (int i = 0; i < NAP; ++i) r.a[i] = *(const u32x4 *)(As + f.ag[i]);
+}
+
+// P = the stage (the patch part is first), As = its kernel-tensor part
+__device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u16 *P, u16 *As)
+{
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        P[f.pd0[i]] = (u16)(r.p[i] & 0xffffu);
+        P[f.pd1[i]] = (u16)(r.p[i] >> 16);
+    }
+#pragma unroll
+    for (int i = 0; i < NAP; ++i) {
+        if (A_PIECES % NT != 0 && f.ad[i] == ~0u) continue;
+        int d = (int)(f.ad[i] & 0xffffffu), tap = (int)(f.ad[i] >> 24);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const u32 w = r.a[i][j / 2];
+            As[d] = (u16)((j & 1) ? (w >> 16) : (w & 0xffffu));
+            // the next value of the row: the next tap of the same channel, or tap 0 of the next channel
+            if (++tap == T) { tap = 0; d += 1 - (T - 1) * BM * PITCH; }
+            else d += BM * PITCH;
+        }
+    }
+}
+
+// fragments of step (tap, kk): MI rows of atoms from the A part, NI columns of atoms from the patch
+__device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], const u16 *As, const u16 *P,
+                                           int a_lane, const int (&b_lane)[NI], int tap, int kk)
+{
+    const int r = tap / WK, s = tap % WK;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+        af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA));
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+        bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PW + s) * PITCH + kk * KA));
+}
+
+__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
+{
+    constexpr int STEPS = T * KK;
+    if constexpr (STEPS * (MI * NI + MI + NI) <= 512) {
+        // fully unrolled; the fragments of step t+1 are read before the MFMAs of step t are issued
+        frag_t af[2][MI], bf[2][NI];
+        load_frags(af[0], bf[0], As, P, a_lane, b_lane, 0, 0);
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            if (t + 1 < STEPS) load_frags(af[(t + 1) & 1], bf[(t + 1) & 1], As, P, a_lane, b_lane, (t + 1) / KK, (t + 1) % KK);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[t & 1][i], bf[t & 1][j], acc[i][j]);
+        }
+    } else {
+        // long slabs (many taps): the loop over taps stays a loop
+#pragma unroll 1
+        for (int tap = 0; tap < T; ++tap) {
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                frag_t af[MI], bf[NI];
+                load_frags(af, bf, As, P, a_lane, b_lane, tap, kk);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[i], bf[j], acc[i][j]);
+            }
+        }
+    }
+}
+
+extern "C" __global__ __launch_bounds__(NT)
+void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__restrict__ C,
+                  unsigned long long *ctl /* unused: members of this template are never folded */)
+{
+    extern __shared__ __attribute__((aligned(16))) u16 smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane % ATOM, lk = (lane / ATOM) * 8;
+    const BlockId bid = block_id();
+    const ColBlock cb = col_block(bid.n);
+    const int wm = wave / WN, wn = wave % WN;
+    const int m0 = bid.m * BM;
+
+    // zeros everywhere first: the patch positions that lie outside the image are never written again
+    {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < NSTG * STAGE / 8; i += NT) ((u32x4 *)smem)[i] = zero;
+    }
+    Fill fill;
+    plan_fill(fill, cb, m0, tid);
+
+    // this lane's place in the fragments: its row of the A part, and per column of atoms its output pixel's
+    // patch pixel under tap (0, 0) (columns past the wave tile read the tile's last pixel and are not stored)
+    const int a_lane = (wm * TM + lrow) * PITCH + lk;
+    int b_lane[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int ct = j * ATOM + lrow;
+        const int cn = wn * TN + (ct < TN ? ct : TN - 1);
+        const int b = cn / (BH * BW), y = (cn / BW) % BH, x = cn % BW;
+        b_lane[j] = ((b * PH + y * STRIDE) * PW + x * STRIDE) * PITCH + lk;
+    }
+
+    acc_t acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < NACC; ++r) acc[i][j][r] = 0.f;
+
+    Regs regs;
+#if FLAG
+    load_slab(regs, fill, A, B, 0);
+    __syncthreads();                                   // the zeros are in place
+    store_slab(regs, fill, smem, smem + P_STAGE);
+    __syncthreads();
+#pragma unroll 1
+    for (int s = 0; s < KSTEPS; ++s) {
+        u16 *cur = smem + (s & 1) * STAGE, *nxt = smem + ((s + 1) & 1) * STAGE;
+        // branch-free body (the loads must not sink below the MFMAs): past the last slab the last one is loaded
+        // and stored once more, into the stage nobody reads any longer
+        load_slab(regs, fill, A, B, s + 1 < KSTEPS ? s + 1 : KSTEPS - 1);
+        __builtin_amdgcn_sched_barrier(0);             // all loads are issued before the first MFMA ...
+        compute_slab(acc, cur + P_STAGE, cur, a_lane, b_lane);
+        __builtin_amdgcn_sched_barrier(0);             // ... and waited for after the last
+        store_slab(regs, fill, nxt, nxt + P_STAGE);
+        __syncthreads();
+    }
+#else
+#pragma unroll 1
+    for (int s = 0; s < KSTEPS; ++s) {
+        load_slab(regs, fill, A, B, s);
+        __syncthreads();                               // slab s-1 has been multiplied (first pass: the zeros are in place)
+        store_slab(regs, fill, smem, smem + P_STAGE);
+        __syncthreads();
+        compute_slab(acc, smem + P_STAGE, smem, a_lane, b_lane);
+    }
+#endif
+
+    // Epilogue.  An atom's result sits with column (l % ATOM) in lane l; 32x32: register r is row
+    // 8*(r/4) + 4*(l/32) + r%4; 16x16: register r is row 4*(l/16) + r.
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int ct = j * ATOM + lrow;
+            if (TN % ATOM != 0 && ct >= TN) continue;
+            const int cn = wn * TN + ct;
+#pragma unroll
+            for (int r = 0; r < NACC; ++r) {
+                const int row = (ATOM == 32) ? 8 * (r / 4) + 4 * (lane / 32) + r % 4 : 4 * (lane / 16) + r;
+                const int gm = m0 + wm * TM + i * ATOM + row;
+                C[conv_c_index(cb, gm, cn)] = acc[i][j][r];
+            }
+        }
+    }
+}

@@ -1,0 +1,269 @@
+"""CPU re-computation of the LDS-resident-patch Conv2d template (csrc/templates/conv_patch.hip).
+
+The template's index arithmetic is written out again here, thread by thread, from the constants the decoder
+hands it: which global bytes every thread loads for every slab, where it puts each value in LDS, which LDS
+bytes every lane reads for every fragment, and which output element every accumulator is stored to.  Checked:
+every global access lies inside its tensor and is aligned to its width, every LDS access lies inside the
+stage, the fill writes every in-image patch position and every kernel-tensor value exactly once (and nothing
+else but the dump words), and the sum the fragments form is the convolution (small shapes: compared with a
+direct convolution written with independent index arithmetic; exact on integer data).
+No GPU is needed: nothing is launched."""
+import re
+
+import numpy as np
+import pytest
+
+import paper_2006_05664_amd as P
+
+V = P.OPEVO_TILE4L
+
+
+def defines(op, cfg):
+    text = P.opevo_kernel_defines(op, V, cfg)
+    tmpl, rest = text.split(":", 1)
+    out = {}
+    for tok in rest.split():
+        m = re.match(r"-D(\w+)=(-?\d+)$", tok)
+        if m:
+            out[m.group(1)] = int(m.group(2))
+    return tmpl.strip(), out
+
+
+def emulate(dims, cfg, img=None, ker=None, blocks=None):
+    """Re-computes the kernel for the given workgroups (all by default).  Returns the output tensor if operands are given."""
+    nimg, cin, hin, win, cout, hk, wk, stride, pad = dims
+    op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, V, cfg)
+    tmpl, D = defines(op, cfg)
+    assert plan.status == 0 and plan.path == 5 and tmpl == "conv_patch", (plan.status, plan.path, tmpl, plan.reason)
+    g = D.__getitem__
+    M, K, BM, BK, KSTEPS, NT = g("M"), g("K"), g("BM"), g("BK"), g("KSTEPS"), g("NT")
+    ATOM, WM, WN, TM, TN, NSTG, CS = g("ATOM"), g("WM"), g("WN"), g("TM"), g("TN"), g("NSTG"), g("CS")
+    CIN, HIN, WIN, HK, WK, S, PAD = g("CIN"), g("HIN"), g("WIN"), g("HK"), g("WK"), g("STRIDE"), g("PAD_CONV")
+    HOUT, WOUT, NB2, BH, BW, H1, W1 = g("HOUT"), g("WOUT"), g("NB2"), g("BH"), g("BW"), g("H1"), g("W1")
+    assert (CIN, HIN, WIN, HK, WK, S, PAD, M) == (cin, hin, win, hk, wk, stride, pad, cout)
+    T = HK * WK
+    PH, PW = (BH - 1) * S + HK, (BW - 1) * S + WK
+    NPIX = NB2 * PH * PW
+    PITCH, DUMP = CS + 8, 64
+    P_STAGE, A_STAGE = NPIX * PITCH, T * BM * PITCH
+    STAGE = P_STAGE + A_STAGE + DUMP
+    KA = 16 if ATOM == 32 else 32
+    NACC = 16 if ATOM == 32 else 4
+    MI, NI, KK = TM // ATOM, (TN + ATOM - 1) // ATOM, CS // KA
+    assert TM % ATOM == 0 and CS % KA == 0 and WIN % 2 == 0 and BK == CS * T and KSTEPS * CS == CIN and K == CIN * T
+    assert NSTG * STAGE * 2 == plan.lds_bytes <= 160 * 1024
+    assert NT == 64 * WM * WN == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
+    assert MI * NI * NACC == plan.acc_per_lane <= 256
+    NPAIR = PW // 2 + 1
+    P_TASKS = CS * NB2 * PH * NPAIR
+    NPT = (P_TASKS + NT - 1) // NT
+    PPR = CS * T // 8
+    A_PIECES = BM * PPR
+    NAP = (A_PIECES + NT - 1) // NT
+    img_bytes, ker_bytes = nimg * cin * hin * win * 2, cout * K * 2
+    grid = list(plan.grid)
+    assert grid[0] * NB2 * BH * BW == nimg * HOUT * WOUT and grid[1] * BM == M and grid[2] == 1
+    have = img is not None
+    out = np.full((nimg, cout, HOUT, WOUT), np.nan) if have else None
+    written = np.zeros((nimg, cout, HOUT, WOUT), dtype=np.int32)
+    if blocks is None:
+        blocks = [(bx, by) for bx in range(grid[0]) for by in range(grid[1])]
+    if have:
+        img_flat, ker_flat = img.reshape(-1), ker.reshape(-1)
+    for bx, by in blocks:
+        x0, y0, nb0 = (bx % W1) * BW, ((bx // W1) % H1) * BH, (bx // (W1 * H1)) * NB2
+        m0 = by * BM
+        yin0, xin0 = y0 * S - PAD, x0 * S - PAD
+        xs = xin0 & ~1
+        # ---- the fill plan of every thread
+        tid = np.arange(NT)
+        pg, pd0, pd1 = [], [], []
+        for i in range(NPT):
+            q = tid + i * NT
+            jp, py, b, c = q % NPAIR, (q // NPAIR) % PH, (q // (NPAIR * PH)) % NB2, q // (NPAIR * PH * NB2)
+            y, x = yin0 + py, xs + 2 * jp
+            px = x - xin0
+            inside = (q < P_TASKS) & (y >= 0) & (y < HIN) & (x >= 0) & (x < WIN)
+            v0 = inside & (px >= 0) & (px < PW)
+            v1 = inside & (px + 1 >= 0) & (px + 1 < PW)
+            goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + c) * HIN + y) * WIN + x), 0)
+            d0 = ((b * PH + py) * PW + px) * PITCH + c
+            dump = STAGE - DUMP + (tid & 31) * 2
+            pg.append(goff); pd0.append(np.where(v0, d0, dump)); pd1.append(np.where(v1, d0 + PITCH, dump + 1))
+        ag, ad, atap, aon = [], [], [], []
+        for i in range(NAP):
+            q = tid + i * NT
+            m, p = q // PPR, q % PPR
+            c, tap = (8 * p) // T, (8 * p) % T
+            on = q < A_PIECES
+            ag.append(np.where(on, 2 * ((m0 + m) * K + 8 * p), 0)); ad.append((tap * BM + m) * PITCH + c); atap.append(tap); aon.append(on)
+        # ---- bounds and alignment of every global load, for every slab
+        for s in range(KSTEPS):
+            for i in range(NPT):
+                o = 2 * s * CS * HIN * WIN + pg[i]
+                assert (o >= 0).all() and (o + 4 <= img_bytes).all() and (o % 4 == 0).all(), ("image load", bx, by, s, i)
+            for i in range(NAP):
+                o = 2 * s * CS * T + ag[i]
+                assert (o >= 0).all() and (o + 16 <= ker_bytes).all() and (o % 16 == 0).all(), ("kernel-tensor load", bx, by, s, i)
+        # ---- the LDS stores of one slab: destinations and what lands there (the plan is the same for every slab)
+        src = np.full(STAGE, -1, dtype=np.int64)   # which global element (of slab 0) each LDS element receives; -1: never written (zeros)
+        hits = np.zeros(STAGE, dtype=np.int32)
+        for i in range(NPT):
+            for dst, e in ((pd0[i], 0), (pd1[i], 1)):
+                assert (dst >= 0).all() and (dst < STAGE).all(), ("patch store", bx, by, i)
+                real = dst < STAGE - DUMP
+                assert (dst[real] < P_STAGE).all()
+                np.add.at(hits, dst[real], 1)
+                src[dst[real]] = pg[i][real] // 2 + e
+        asrc = np.full(STAGE, -1, dtype=np.int64)
+        for i in range(NAP):
+            d, tap = ad[i].copy(), atap[i].copy()
+            for j in range(8):
+                dd = P_STAGE + d[aon[i]]
+                assert (dd >= P_STAGE).all() and (dd < P_STAGE + A_STAGE).all(), ("kernel-tensor store", bx, by, i, j)
+                np.add.at(hits, dd, 1)
+                asrc[dd] = ag[i][aon[i]] // 2 + j
+                tap = tap + 1
+                wrap = tap == T
+                d = np.where(wrap, d + 1 - (T - 1) * BM * PITCH, d + BM * PITCH)
+                tap = np.where(wrap, 0, tap)
+        assert hits.max() <= 1, "an LDS element is written twice in one slab"
+        # coverage: every patch position inside the image, every channel of the slab; every kernel-tensor value
+        for b in range(NB2):
+            for py in range(PH):
+                for px in range(PW):
+                    y, x = yin0 + py, xin0 + px
+                    base = ((b * PH + py) * PW + px) * PITCH
+                    if 0 <= y < HIN and 0 <= x < WIN:
+                        want = (((nb0 + b) * CIN + np.arange(CS)) * HIN + y) * WIN + x
+                        assert (src[base:base + CS] == want).all(), ("patch position", bx, by, b, py, px)
+                    else:
+                        assert (hits[base:base + CS] == 0).all(), ("padding position written", bx, by, b, py, px)
+                    assert (hits[base + CS:base + PITCH] == 0).all()
+        for tap in range(T):
+            for m in range(BM):
+                base = P_STAGE + (tap * BM + m) * PITCH
+                want = (m0 + m) * K + np.arange(CS) * T + tap
+                assert (asrc[base:base + CS] == want).all(), ("kernel-tensor value", bx, by, tap, m)
+        # ---- fragments: every lane's reads, and (with operands) the sum they form
+        lane = np.arange(64)
+        lrow, lk = lane % ATOM, (lane // ATOM) * 8
+        for wave in range(WM * WN):
+            wm, wn = wave // WN, wave % WN
+            a_lane = (wm * TM + lrow) * PITCH + lk
+            for j in range(NI):
+                ct = j * ATOM + lrow
+                cn = wn * TN + np.minimum(ct, TN - 1)
+                b, y, x = cn // (BH * BW), (cn // BW) % BH, cn % BW
+                b_lane = ((b * PH + y * S) * PW + x * S) * PITCH + lk
+                for i in range(MI):
+                    accv = np.zeros((ATOM, ATOM)) if have else None   # [row][column]
+                    for s in range(KSTEPS if have else 1):
+                        for tap in range(T):
+                            r, sx = tap // WK, tap % WK
+                            for kk in range(KK):
+                                ao = P_STAGE + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA
+                                bo = b_lane + (r * PW + sx) * PITCH + kk * KA
+                                assert (ao % 8 == 0).all() and (bo % 8 == 0).all()
+                                assert (ao >= P_STAGE).all() and (ao + 8 <= P_STAGE + A_STAGE).all(), "A fragment outside its part"
+                                assert (bo >= 0).all() and (bo + 8 <= P_STAGE).all(), "B fragment outside the patch"
+                                if have:
+                                    # lane l supplies 8 reduction values of row / column l % ATOM; lanes with equal l / ATOM pair up
+                                    av = np.zeros((64, 8)); bv = np.zeros((64, 8))
+                                    for t in range(8):
+                                        sa, sb = asrc[ao + t], src[bo + t]
+                                        assert (sa >= 0).all(), "A fragment reads an unwritten element"
+                                        av[:, t] = ker_flat[sa + s * CS * T]
+                                        bv[:, t] = np.where(sb >= 0, img_flat[np.maximum(sb, 0) + s * CS * HIN * WIN], 0.0)
+                                    for grp in range(64 // ATOM):
+                                        sel = slice(grp * ATOM, (grp + 1) * ATOM)
+                                        accv += av[sel] @ bv[sel].T
+                    # epilogue: lane l holds column l % ATOM; register r holds the row stated in the template
+                    for l in range(64):
+                        if ct[l] >= TN:
+                            continue
+                        c2 = wn * TN + ct[l]
+                        nb, yy, xx = nb0 + c2 // (BH * BW), y0 + (c2 // BW) % BH, x0 + c2 % BW
+                        for rr in range(NACC):
+                            row = 8 * (rr // 4) + 4 * (l // 32) + rr % 4 if ATOM == 32 else 4 * (l // 16) + rr
+                            gm = m0 + wm * TM + i * ATOM + row
+                            assert 0 <= nb < nimg and 0 <= gm < cout and 0 <= yy < HOUT and 0 <= xx < WOUT
+                            written[nb, gm, yy, xx] += 1
+                            if have:
+                                out[nb, gm, yy, xx] = accv[row, l % ATOM]
+    return out, written
+
+
+def direct_conv(img, ker, stride, pad):
+    n, cin, h, w = img.shape
+    cout, _, hk, wk = ker.shape
+    padded = np.zeros((n, cin, h + 2 * pad, w + 2 * pad))
+    padded[:, :, pad:pad + h, pad:pad + w] = img
+    ho, wo = (h + 2 * pad - hk) // stride + 1, (w + 2 * pad - wk) // stride + 1
+    out = np.zeros((n, cout, ho, wo))
+    for r in range(hk):
+        for s in range(wk):
+            win = padded[:, :, r:r + (ho - 1) * stride + 1:stride, s:s + (wo - 1) * stride + 1:stride]
+            out += np.einsum("nchw,oc->nohw", win, ker[:, :, r, s])
+    return out
+
+
+SMALL = [
+    # dims (B, Cin, H, W, Cout, Hk, Wk, stride, pad), configuration B(2) Cout(4) H(4) W(4) Cin(2) unroll layout
+    ("3x3 pad 1, 32x32 atoms, ragged pixel side", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 2, 16, 1, 2]),
+    ("3x3 pad 1, 16x16 atoms, two channel waves", (2, 64, 4, 8, 64, 3, 3, 1, 1), [2, 1, 2, 2, 1, 16, 1, 1, 2, 2, 2, 1, 1, 4, 2, 32, 1, 2]),
+    ("3x3 no padding, single stage", (1, 32, 6, 6, 32, 3, 3, 1, 0), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 2, 2, 2, 16, 0, 2]),
+    ("5x5 pad 1, 16x16 atoms", (1, 32, 8, 6, 32, 5, 5, 1, 1), [1, 1, 1, 2, 1, 16, 1, 2, 1, 3, 1, 1, 1, 4, 1, 32, 1, 2]),
+    ("5x5 pad 2, boxes of 3 columns", (1, 16, 6, 6, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 1, 1, 1, 6, 2, 1, 1, 3, 1, 16, 1, 2]),
+    ("3x3 stride 2 pad 1", (1, 32, 8, 8, 32, 3, 3, 2, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2]),
+    ("1x1", (2, 32, 4, 4, 64, 1, 1, 1, 0), [2, 1, 1, 2, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2]),
+]
+
+
+@pytest.mark.parametrize("label,dims,cfg", SMALL, ids=[c[0] for c in SMALL])
+def test_the_patch_template_computes_the_convolution(label, dims, cfg):
+    rng = np.random.default_rng(7)
+    nimg, cin, hin, win, cout, hk, wk, stride, pad = dims
+    img = rng.integers(-3, 4, size=(nimg, cin, hin, win)).astype(np.float64)
+    ker = rng.integers(-3, 4, size=(cout, cin, hk, wk)).astype(np.float64)
+    out, written = emulate(dims, cfg, img, ker)
+    assert (written == 1).all(), "every output element is stored exactly once"
+    assert np.array_equal(out, direct_conv(img, ker, stride, pad))
+
+
+FULL = [
+    ("conv14, 32 channels x one image, 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
+    ("conv14, 64 channels x two rows", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2]),
+    ("conv14, 16x16 atoms, 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
+    ("conv56, 64 channels x 4 rows", (1, 64, 56, 56, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2]),
+]
+
+
+@pytest.mark.parametrize("label,dims,cfg", FULL, ids=[c[0] for c in FULL])
+def test_addresses_at_full_size(label, dims, cfg):
+    """The graded shapes: bounds, alignment and coverage for the corner, edge and interior workgroups."""
+    op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, V, cfg)
+    gx, gy = plan.grid[0], plan.grid[1]
+    blocks = sorted({(bx, by) for bx in {0, 1, gx // 2, gx - 2, gx - 1} for by in {0, gy - 1} if 0 <= bx < gx})
+    emulate(dims, cfg, blocks=blocks)
+
+
+def test_members_outside_the_patch_template_run_as_layout_0():
+    """layout 2 is inert where the template cannot hold the member: the plan is the layout-0 member's."""
+    dims = (32, 256, 14, 14, 256, 3, 3, 1, 1)
+    op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
+    for cfg in ([32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 32, 8, 1],     # slabs of 8 channels
+                [32, 1, 256, 1, 1, 1, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1],    # one channel per workgroup
+                [1, 32, 1, 1, 2, 128, 1, 1, 1, 14, 1, 1, 1, 14, 8, 32, 1]): # 32 images in one box: no room in the LDS
+        p2 = P.opevo_kernel_plan(op, V, cfg + [2])
+        p0 = P.opevo_kernel_plan(op, V, cfg + [0])
+        assert p2.path != 5
+        assert (p2.status, p2.path, list(p2.grid), p2.block, p2.lds_bytes) == (p0.status, p0.path, list(p0.grid), p0.block, p0.lds_bytes)
+    # odd image width
+    op27 = P.opevo_op_create(P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2), P.OPEVO_BF16)
+    assert P.opevo_kernel_plan(op27, V, [4, 1, 2, 1, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 1, 2]).path != 5
+    # fp32 inputs
+    opf = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_F32)
+    assert P.opevo_kernel_plan(opf, V, [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]).path != 5
