@@ -149,6 +149,19 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
     return OPEVO_OK;
 }
 
+// Row pitch and per-image pitch (in pixels) of the LDS-resident patch for a box of bh x bw output pixels:
+// (bh-1)*stride + hk rows of (bw-1)*stride + wk pixels.  padded (unit stride only): the row pitch and the image
+// pitch are raised to be congruent to bw and to bh*bw modulo 16, so that consecutive output pixels of the
+// flattened box read consecutive groups of LDS banks.
+static void patch_pitches(const opevo_op &op, int64_t bh, int64_t bw, bool padded, int64_t &row, int64_t &image)
+{
+    const int64_t ph = (bh - 1) * op.stride + op.hk, pw = (bw - 1) * op.stride + op.wk;
+    row = pw; image = ph * pw;
+    if (!padded || op.stride != 1) return;
+    row = pw + ((bw - pw) % 16 + 16) % 16;
+    image = ph * row + ((bh * bw - ph * row) % 16 + 16) % 16;
+}
+
 static void invalid(opevo_plan &p, const char *fmt, long a = 0, long b = 0)
 {
     p.status = OPEVO_E_INVALID;
@@ -211,6 +224,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     int64_t kunroll = 0;                   // 0: the template's default
     int64_t patch_cs = 0;                  // Conv2d, TILE4L, layout 2: channels per slab of the LDS-resident patch (0: not on that template)
     int patch_atom = 0, patch_stages = 1;
+    int64_t patch_row = 0, patch_image = 0;   // its row pitch and image pitch in pixels
     int tile4_width = 0;   // slots of the four-level part, after which the launch-order parameters follow
 
     if (!four_level) {
@@ -270,14 +284,21 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                 const int at = fits(32) && (!fits(16) || up(TN, 32) == up(TN, 16)) ? 32 : fits(16) ? 16 : 0;
                 const int64_t ph = (BH - 1) * op.stride + op.hk, pw = (BW - 1) * op.stride + op.wk;
                 const int st = (flagv && ksteps > 1) ? 2 : 1;
-                const int64_t lds_p = st * ((nb2 * ph * pw + taps * WM * TM) * (cs + 8) + 64) * 2;   // + the dump words of a stage
-                const int64_t fill_p = (cs * nb2 * ph * (pw / 2 + 1) + nt - 1) / nt, fill_a = (WM * TM * cs * taps / 8 + nt - 1) / nt;
-                // registers: a lane has 512 / (waves per SIMD); the fill keeps 3 per pair of pixels and 6 per piece of the
-                // kernel tensor (plan and data in flight) next to the accumulators; 64 are left for fragments and addresses
+                // the padded pitches if the LDS has room for them, else the plain ones
+                int64_t prow = 0, pimage = 0, lds_p = 0;
+                for (int padded = 1; padded >= 0; --padded) {
+                    patch_pitches(op, BH, BW, padded == 1, prow, pimage);
+                    lds_p = st * ((nb2 * pimage + taps * WM * TM) * (cs + 8) + 64) * 2;   // + the dump words of a stage
+                    if (lds_p <= kMaxLds) break;
+                }
+                // the fill: per thread, tasks of two channels x two pixels (image) and of two channels x all taps (kernel tensor)
+                const int64_t fill_p = (cs / 2 * (pw / 2 + 1) * ph * nb2 + nt - 1) / nt, fill_a = (WM * TM * cs / 2 + nt - 1) / nt;
+                // registers: a lane has 512 / (waves per SIMD); the fill keeps 5 per image task and taps + 2 per kernel-tensor
+                // task (plan and data in flight) next to the accumulators; 64 are left for fragments and addresses
                 const int64_t regs = 512 / ((nw + 3) / 4) - (at ? TM * up(TN, at) / 64 : 0) - 64;
-                if (at && nt <= kMaxThreads && lds_p <= kMaxLds && op.win % 2 == 0 && 3 * fill_p + 6 * fill_a <= regs &&
+                if (at && nt <= kMaxThreads && lds_p <= kMaxLds && op.win % 2 == 0 && 5 * fill_p + (taps + 2) * fill_a <= regs &&
                     op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
-                    patch_cs = cs; patch_atom = at; patch_stages = st;
+                    patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage;
                 }
             }
         } else {
@@ -478,7 +499,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (anr + (b_kmajor ? bnr : BN)) * BK * 2;
     else if (path == 5)
-        lds = nstage * ((nb2 * ((BH - 1) * op.stride + op.hk) * ((BW - 1) * op.stride + op.wk) + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2;
+        lds = nstage * ((nb2 * patch_image + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2;
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
     p.path = path;
@@ -554,7 +575,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     if (tap_box)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
           << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
-    if (path == 5) D << " -DCS=" << patch_cs;
+    if (path == 5) D << " -DCS=" << patch_cs << " -DPWP=" << patch_row << " -DIPIX=" << patch_image;
     if (b_kmajor) D << " -DB_KMAJOR=1 -DBNR=" << bnr;
     if (path == 3 && anr != BM) D << " -DANR=" << anr;
     if (kunroll) D << " -DKUNROLL=" << kunroll;

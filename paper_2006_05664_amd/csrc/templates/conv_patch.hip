@@ -9,18 +9,18 @@
 // The reduction is walked in KSTEPS slabs of CS input channels, every slab with all HK*WK taps.  Per slab
 // the workgroup holds in LDS
 //   * the patch: the input pixels under its box for the slab's channels, channels fastest,
-//     P[image][py][px][CS (+8)], PH = (BH-1)*STRIDE + HK rows by PW = (BW-1)*STRIDE + WK columns.  An output
+//     P[image][py][px][CS (+8)], PH = (BH-1)*STRIDE + HK rows by PW = (BW-1)*STRIDE + WK columns (row pitch PWP >= PW).  An output
 //     pixel (y, x) under tap (r, s) reads patch pixel (y*STRIDE + r, x*STRIDE + s): the 8 channels an MFMA lane
 //     wants are 16 contiguous bytes, and the tap is a compile-time offset from the lane's own pixel, so one
 //     staged pixel serves all the taps that touch it.  Positions outside the image (padding) are zeros: both
 //     stages are cleared once, and the fill only ever writes positions inside the image, whose place in the
 //     patch is the same for every slab.
 //   * the kernel tensor's part, A[tap][BM][CS (+8)], so that an A fragment is 16 contiguous bytes too.
-// Both parts are transposed on the way in: a thread loads 4-byte pairs of pixels of one channel (rows of the
-// NCHW image are contiguous in x; WIN is even, so aligned pairs never straddle a row) or 16-byte pieces of a
-// kernel-tensor row (CS*HK*WK contiguous values, channel-major) into registers and writes the values to
-// their transposed places one by one (2-byte LDS stores).  The padding of 8 elements per row makes 16
-// consecutive rows start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
+// Both parts are transposed on the way in, two channels at a time: a thread loads 4-byte pairs of pixels of two
+// channels (rows of the NCHW image are contiguous in x; WIN is even, so aligned pairs never straddle a row), or the
+// 2*HK*WK contiguous values of two input channels of one output channel, swaps halves in registers and stores
+// 4-byte words (one pixel or tap, its two channels).  The padding of 8 elements per row makes 16 consecutive rows
+// start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
 //
 // FLAG = 1: two stages; the global loads of slab s+1 are in flight (in registers) while slab s is multiplied,
 //           and are written to the other stage afterwards: one barrier per slab.
@@ -50,7 +50,12 @@ typedef f32x4 acc_t;
 
 constexpr int T = HK * WK;                                    // taps
 constexpr int PH = (BH - 1) * STRIDE + HK, PW = (BW - 1) * STRIDE + WK;
-constexpr int NPIX = NB2 * PH * PW;                           // patch pixels
+// PWP, IPIX (from the host): row pitch and image pitch of the patch in pixels.  The lanes of an MFMA read consecutive
+// output pixels of the flattened box, BW to a row; with unit stride and room in the LDS the host makes the row
+// pitch congruent to BW modulo 16 (and the image pitch to BH*BW), so that the patch pixel of output pixel n sits at
+// n modulo 16 and any 16 lanes served together start in 16 different groups of banks (PITCH / 8 is odd).
+static_assert(PWP >= PW && IPIX >= PH * PWP, "patch pitches too small");
+constexpr int NPIX = NB2 * IPIX;
 constexpr int PITCH = CS + 8;                                 // elements per patch pixel / per kernel-tensor row
 constexpr int DUMP = 64;                                      // elements at the end of a stage that take the stores of pixels outside the patch
 constexpr int P_STAGE = NPIX * PITCH, A_STAGE = T * BM * PITCH, STAGE = P_STAGE + A_STAGE + DUMP;   // elements
@@ -59,25 +64,29 @@ constexpr int KK = CS / KA;                                   // MFMA steps per 
 static_assert(TM % ATOM == 0 && CS % KA == 0 && WIN % 2 == 0 && BK == CS * T && KSTEPS * CS == CIN, "decoder and template disagree");
 static_assert(NSTG * STAGE * 2 <= 160 * 1024, "stages exceed the LDS");
 
-// patch fill: tasks of one aligned pair of pixels each, pair index fastest, then patch row, image, channel
+// Patch fill: a task is two channels x an aligned pair of pixels: two 4-byte loads (one per channel), a 2 x 2
+// transposition in registers, two 4-byte LDS stores (one per pixel: its two channels).  Channel pair fastest
+// across the lanes (their stores fall into consecutive banks), then the pair of pixels along the row (their
+// loads into one cache line), then patch row, then image.
+constexpr int CP = CS / 2;                                    // channel pairs of a slab
 constexpr int NPAIR = PW / 2 + 1;                             // aligned pairs that cover PW columns from either parity
-constexpr int P_TASKS = CS * NB2 * PH * NPAIR;
+constexpr int P_TASKS = CP * NPAIR * PH * NB2;
 constexpr int NPT = (P_TASKS + NT - 1) / NT;
-// kernel-tensor fill: 16-byte pieces, piece index along the row fastest
-constexpr int PPR = CS * T / 8;                               // pieces per row of a slab
-constexpr int A_PIECES = BM * PPR;
-constexpr int NAP = (A_PIECES + NT - 1) / NT;
+// Kernel-tensor fill: a task is one output channel x two input channels: the 2*T values of the two channels are
+// contiguous in the OIHW tensor (T 4-byte loads); tap t of both channels makes one 4-byte LDS store.
+constexpr int A_TASKS = BM * CP;
+constexpr int NAT = (A_TASKS + NT - 1) / NT;
 
 struct Fill {
-    u32 pg[NPT];     // byte offset of the pair inside the image tensor for slab 0
-    u32 pd0[NPT], pd1[NPT];   // element offsets in the stage of the pair's two pixels; one that is outside the patch or the
-                              // image goes to the dump words at the end of the stage (the stores are unconditional)
-    u32 ag[NAP];     // byte offset of the piece inside the kernel tensor for slab 0
-    u32 ad[NAP];     // element offset of the piece's first value in the A part | its tap << 24; ~0: no piece
+    u32 pg[NPT];              // byte offset inside the image tensor of the task's pair of pixels, first channel, slab 0
+    u32 pd0[NPT], pd1[NPT];   // 4-byte word in the stage of each of the two pixels (this channel pair); a pixel outside
+                              // the patch or the image goes to the dump words at the end of the stage: unconditional stores
+    u32 ag[NAT];              // byte offset inside the kernel tensor of the task's 2*T values, slab 0
+    u32 ad[NAT];              // 4-byte word in the A part of tap 0 (the taps follow BM rows apart)
 };
 struct Regs {
-    u32 p[NPT];
-    u32x4 a[NAP];
+    u32 p[NPT][2];
+    u32 a[NAT][T];
 };
 
 __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, int tid)
@@ -87,23 +96,22 @@ __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, i
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
         const int q = tid + i * NT;
-        const int jp = q % NPAIR, py = (q / NPAIR) % PH, b = (q / (NPAIR * PH)) % NB2, c = q / (NPAIR * PH * NB2);
+        const int cp = q % CP, jp = (q / CP) % NPAIR, py = (q / (CP * NPAIR)) % PH, b = q / (CP * NPAIR * PH);
         const int y = yin0 + py, x = xs + 2 * jp, px = x - xin0;   // px: patch column of the pair's first pixel (-1 .. PW)
         const bool in = (P_TASKS % NT == 0 || q < P_TASKS) && y >= 0 && y < HIN && x >= 0 && x < WIN;
         const bool v0 = in && px >= 0 && px < PW, v1 = in && px + 1 >= 0 && px + 1 < PW;
-        f.pg[i] = (v0 || v1) ? 2u * (u32)((((cb.nb0 + b) * CIN + c) * HIN + y) * WIN + x) : 0u;
-        const int d0 = ((b * PH + py) * PW + px) * PITCH + c, dump = STAGE - DUMP + (tid & 31) * 2;
+        const int d0 = ((b * IPIX + py * PWP + px) * PITCH) / 2 + cp, dump = (STAGE - DUMP) / 2 + (tid & 31);
+        f.pg[i] = (v0 || v1) ? 2u * (u32)((((cb.nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x) : 0u;
         f.pd0[i] = (u32)(v0 ? d0 : dump);
-        f.pd1[i] = (u32)(v1 ? d0 + PITCH : dump + 1);
+        f.pd1[i] = (u32)(v1 ? d0 + PITCH / 2 : dump);
     }
 #pragma unroll
-    for (int i = 0; i < NAP; ++i) {
+    for (int i = 0; i < NAT; ++i) {
         const int q = tid + i * NT;
-        const int m = q / PPR, p = q % PPR;
-        const int c = (8 * p) / T, tap = (8 * p) % T;
-        const bool on = A_PIECES % NT == 0 || q < A_PIECES;
-        f.ag[i] = on ? 2u * (u32)((m0 + m) * K + 8 * p) : 0u;
-        f.ad[i] = on ? (u32)((tap * BM + m) * PITCH + c) | ((u32)tap << 24) : ~0u;
+        const int cp = q % CP, m = q / CP;
+        const bool on = A_TASKS % NT == 0 || q < A_TASKS;
+        f.ag[i] = on ? 2u * (u32)((m0 + m) * K + 2 * cp * T) : 0u;
+        f.ad[i] = on ? (u32)(m * PITCH / 2 + cp) : ~0u;
     }
 }
 
@@ -113,30 +121,35 @@ __device__ __forceinline__ void load_slab(Regs &r, const Fill &f, const u16 *__r
     const char *Bs = (const char *)(B + (long)s * CS * HIN * WIN);
     const char *As = (const char *)(A + (long)s * CS * T);
 #pragma unroll
-    for (int i = 0; i < NPT; ++i) r.p[i] = *(const u32 *)(Bs + f.pg[i]);
+    for (int i = 0; i < NPT; ++i) {
+        r.p[i][0] = *(const u32 *)(Bs + f.pg[i]);
+        r.p[i][1] = *(const u32 *)(Bs + f.pg[i] + 2 * HIN * WIN);   // the next channel (offset 0 for an idle task: still inside the tensor)
+    }
 #pragma unroll
-    for (int i = 0; i < NAP; ++i) r.a[i] = *(const u32x4 *)(As + f.ag[i]);
+    for (int i = 0; i < NAT; ++i)
+#pragma unroll
+        for (int t = 0; t < T; ++t) r.a[i][t] = *(const u32 *)(As + f.ag[i] + 4 * t);
 }
 
-// P = the stage (the patch part is first), As = its kernel-tensor part
-__device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u16 *P, u16 *As)
+// S = the stage as 4-byte words (the patch part is first, the kernel-tensor part follows)
+__device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u32 *S)
 {
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
-        P[f.pd0[i]] = (u16)(r.p[i] & 0xffffu);
-        P[f.pd1[i]] = (u16)(r.p[i] >> 16);
+        S[f.pd0[i]] = (r.p[i][0] & 0xffffu) | (r.p[i][1] << 16);         // first pixel: its two channels
+        S[f.pd1[i]] = (r.p[i][0] >> 16) | (r.p[i][1] & 0xffff0000u);     // second pixel
     }
+    u32 *SA = S + P_STAGE / 2;
 #pragma unroll
-    for (int i = 0; i < NAP; ++i) {
-        if (A_PIECES % NT != 0 && f.ad[i] == ~0u) continue;
-        int d = (int)(f.ad[i] & 0xffffffu), tap = (int)(f.ad[i] >> 24);
+    for (int i = 0; i < NAT; ++i) {
+        if (A_TASKS % NT != 0 && f.ad[i] == ~0u) continue;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const u32 w = r.a[i][j / 2];
-            As[d] = (u16)((j & 1) ? (w >> 16) : (w & 0xffffu));
-            // the next value of the row: the next tap of the same channel, or tap 0 of the next channel
-            if (++tap == T) { tap = 0; d += 1 - (T - 1) * BM * PITCH; }
-            else d += BM * PITCH;
+        for (int t = 0; t < T; ++t) {
+            // value t of the run is tap t of the first channel, value T + t tap t of the second
+            const u32 lo = r.a[i][t / 2], hi = r.a[i][(T + t) / 2];
+            const u32 l16 = (t % 2) ? (lo >> 16) : (lo & 0xffffu);
+            const u32 h16 = ((T + t) % 2) ? (hi & 0xffff0000u) : (hi << 16);
+            SA[f.ad[i] + t * (BM * PITCH / 2)] = l16 | h16;
         }
     }
 }
@@ -151,7 +164,7 @@ __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], c
         af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA));
 #pragma unroll
     for (int j = 0; j < NI; ++j)
-        bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PW + s) * PITCH + kk * KA));
+        bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PWP + s) * PITCH + kk * KA));
 }
 
 __device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
@@ -216,7 +229,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         const int ct = j * ATOM + lrow;
         const int cn = wn * TN + (ct < TN ? ct : TN - 1);
         const int b = cn / (BH * BW), y = (cn / BW) % BH, x = cn % BW;
-        b_lane[j] = ((b * PH + y * STRIDE) * PW + x * STRIDE) * PITCH + lk;
+        b_lane[j] = (b * IPIX + y * STRIDE * PWP + x * STRIDE) * PITCH + lk;
     }
 
     acc_t acc[MI][NI];
@@ -231,7 +244,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #if FLAG
     load_slab(regs, fill, A, B, 0);
     __syncthreads();                                   // the zeros are in place
-    store_slab(regs, fill, smem, smem + P_STAGE);
+    store_slab(regs, fill, (u32 *)smem);
     __syncthreads();
 #pragma unroll 1
     for (int s = 0; s < KSTEPS; ++s) {
@@ -242,7 +255,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         __builtin_amdgcn_sched_barrier(0);             // all loads are issued before the first MFMA ...
         compute_slab(acc, cur + P_STAGE, cur, a_lane, b_lane);
         __builtin_amdgcn_sched_barrier(0);             // ... and waited for after the last
-        store_slab(regs, fill, nxt, nxt + P_STAGE);
+        store_slab(regs, fill, (u32 *)nxt);
         __syncthreads();
     }
 #else
@@ -250,7 +263,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     for (int s = 0; s < KSTEPS; ++s) {
         load_slab(regs, fill, A, B, s);
         __syncthreads();                               // slab s-1 has been multiplied (first pass: the zeros are in place)
-        store_slab(regs, fill, smem, smem + P_STAGE);
+        store_slab(regs, fill, (u32 *)smem);
         __syncthreads();
         compute_slab(acc, smem + P_STAGE, smem, a_lane, b_lane);
     }

@@ -44,7 +44,9 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     assert (CIN, HIN, WIN, HK, WK, S, PAD, M) == (cin, hin, win, hk, wk, stride, pad, cout)
     T = HK * WK
     PH, PW = (BH - 1) * S + HK, (BW - 1) * S + WK
-    NPIX = NB2 * PH * PW
+    PWP, IPIX = g("PWP"), g("IPIX")
+    assert PWP >= PW and IPIX >= PH * PWP
+    NPIX = NB2 * IPIX
     PITCH, DUMP = CS + 8, 64
     P_STAGE, A_STAGE = NPIX * PITCH, T * BM * PITCH
     STAGE = P_STAGE + A_STAGE + DUMP
@@ -55,12 +57,12 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     assert NSTG * STAGE * 2 == plan.lds_bytes <= 160 * 1024
     assert NT == 64 * WM * WN == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
     assert MI * NI * NACC == plan.acc_per_lane <= 256
+    CP = CS // 2
     NPAIR = PW // 2 + 1
-    P_TASKS = CS * NB2 * PH * NPAIR
+    P_TASKS = CP * NPAIR * PH * NB2
     NPT = (P_TASKS + NT - 1) // NT
-    PPR = CS * T // 8
-    A_PIECES = BM * PPR
-    NAP = (A_PIECES + NT - 1) // NT
+    A_TASKS = BM * CP
+    NAT = (A_TASKS + NT - 1) // NT
     img_bytes, ker_bytes = nimg * cin * hin * win * 2, cout * K * 2
     grid = list(plan.grid)
     assert grid[0] * NB2 * BH * BW == nimg * HOUT * WOUT and grid[1] * BM == M and grid[2] == 1
@@ -81,61 +83,59 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         pg, pd0, pd1 = [], [], []
         for i in range(NPT):
             q = tid + i * NT
-            jp, py, b, c = q % NPAIR, (q // NPAIR) % PH, (q // (NPAIR * PH)) % NB2, q // (NPAIR * PH * NB2)
+            cp, jp, py, b = q % CP, (q // CP) % NPAIR, (q // (CP * NPAIR)) % PH, q // (CP * NPAIR * PH)
             y, x = yin0 + py, xs + 2 * jp
             px = x - xin0
             inside = (q < P_TASKS) & (y >= 0) & (y < HIN) & (x >= 0) & (x < WIN)
             v0 = inside & (px >= 0) & (px < PW)
             v1 = inside & (px + 1 >= 0) & (px + 1 < PW)
-            goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + c) * HIN + y) * WIN + x), 0)
-            d0 = ((b * PH + py) * PW + px) * PITCH + c
-            dump = STAGE - DUMP + (tid & 31) * 2
-            pg.append(goff); pd0.append(np.where(v0, d0, dump)); pd1.append(np.where(v1, d0 + PITCH, dump + 1))
-        ag, ad, atap, aon = [], [], [], []
-        for i in range(NAP):
+            goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x), 0)
+            d0 = ((b * IPIX + py * PWP + px) * PITCH) // 2 + cp      # 4-byte words
+            dump = (STAGE - DUMP) // 2 + (tid & 31)
+            pg.append(goff); pd0.append(np.where(v0, d0, dump)); pd1.append(np.where(v1, d0 + PITCH // 2, dump))
+        ag, ad, aon = [], [], []
+        for i in range(NAT):
             q = tid + i * NT
-            m, p = q // PPR, q % PPR
-            c, tap = (8 * p) // T, (8 * p) % T
-            on = q < A_PIECES
-            ag.append(np.where(on, 2 * ((m0 + m) * K + 8 * p), 0)); ad.append((tap * BM + m) * PITCH + c); atap.append(tap); aon.append(on)
+            cp, m = q % CP, q // CP
+            on = q < A_TASKS
+            ag.append(np.where(on, 2 * ((m0 + m) * K + 2 * cp * T), 0)); ad.append(m * PITCH // 2 + cp); aon.append(on)
         # ---- bounds and alignment of every global load, for every slab
         for s in range(KSTEPS):
             for i in range(NPT):
-                o = 2 * s * CS * HIN * WIN + pg[i]
-                assert (o >= 0).all() and (o + 4 <= img_bytes).all() and (o % 4 == 0).all(), ("image load", bx, by, s, i)
-            for i in range(NAP):
-                o = 2 * s * CS * T + ag[i]
-                assert (o >= 0).all() and (o + 16 <= ker_bytes).all() and (o % 16 == 0).all(), ("kernel-tensor load", bx, by, s, i)
+                for ch in range(2):
+                    o = 2 * s * CS * HIN * WIN + pg[i] + ch * 2 * HIN * WIN
+                    assert (o >= 0).all() and (o + 4 <= img_bytes).all() and (o % 4 == 0).all(), ("image load", bx, by, s, i)
+            for i in range(NAT):
+                for t in range(T):
+                    o = 2 * s * CS * T + ag[i] + 4 * t
+                    assert (o >= 0).all() and (o + 4 <= ker_bytes).all() and (o % 4 == 0).all(), ("kernel-tensor load", bx, by, s, i)
         # ---- the LDS stores of one slab: destinations and what lands there (the plan is the same for every slab)
         src = np.full(STAGE, -1, dtype=np.int64)   # which global element (of slab 0) each LDS element receives; -1: never written (zeros)
         hits = np.zeros(STAGE, dtype=np.int32)
         for i in range(NPT):
-            for dst, e in ((pd0[i], 0), (pd1[i], 1)):
-                assert (dst >= 0).all() and (dst < STAGE).all(), ("patch store", bx, by, i)
-                real = dst < STAGE - DUMP
-                assert (dst[real] < P_STAGE).all()
-                np.add.at(hits, dst[real], 1)
-                src[dst[real]] = pg[i][real] // 2 + e
+            for dst, e in ((pd0[i], 0), (pd1[i], 1)):        # word of pixel e: low half = first channel, high half = second
+                assert (dst >= 0).all() and (2 * dst + 1 < STAGE).all(), ("patch store", bx, by, i)
+                real = 2 * dst < STAGE - DUMP
+                assert (2 * dst[real] + 1 < P_STAGE).all()
+                for ch in range(2):
+                    np.add.at(hits, 2 * dst[real] + ch, 1)
+                    src[2 * dst[real] + ch] = pg[i][real] // 2 + ch * HIN * WIN + e
         asrc = np.full(STAGE, -1, dtype=np.int64)
-        for i in range(NAP):
-            d, tap = ad[i].copy(), atap[i].copy()
-            for j in range(8):
-                dd = P_STAGE + d[aon[i]]
-                assert (dd >= P_STAGE).all() and (dd < P_STAGE + A_STAGE).all(), ("kernel-tensor store", bx, by, i, j)
-                np.add.at(hits, dd, 1)
-                asrc[dd] = ag[i][aon[i]] // 2 + j
-                tap = tap + 1
-                wrap = tap == T
-                d = np.where(wrap, d + 1 - (T - 1) * BM * PITCH, d + BM * PITCH)
-                tap = np.where(wrap, 0, tap)
+        for i in range(NAT):
+            for t in range(T):
+                dd = P_STAGE + 2 * (ad[i][aon[i]] + t * (BM * PITCH // 2))
+                assert (dd >= P_STAGE).all() and (dd + 1 < P_STAGE + A_STAGE).all(), ("kernel-tensor store", bx, by, i, t)
+                for ch in range(2):                            # value t of the run of 2*T, value T + t
+                    np.add.at(hits, dd + ch, 1)
+                    asrc[dd + ch] = ag[i][aon[i]] // 2 + ch * T + t
         assert hits.max() <= 1, "an LDS element is written twice in one slab"
         # coverage: every patch position inside the image, every channel of the slab; every kernel-tensor value
         for b in range(NB2):
             for py in range(PH):
-                for px in range(PW):
+                for px in range(PWP):
                     y, x = yin0 + py, xin0 + px
-                    base = ((b * PH + py) * PW + px) * PITCH
-                    if 0 <= y < HIN and 0 <= x < WIN:
+                    base = (b * IPIX + py * PWP + px) * PITCH
+                    if 0 <= y < HIN and 0 <= x < WIN and px < PW:
                         want = (((nb0 + b) * CIN + np.arange(CS)) * HIN + y) * WIN + x
                         assert (src[base:base + CS] == want).all(), ("patch position", bx, by, b, py, px)
                     else:
@@ -156,7 +156,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                 ct = j * ATOM + lrow
                 cn = wn * TN + np.minimum(ct, TN - 1)
                 b, y, x = cn // (BH * BW), (cn // BW) % BH, cn % BW
-                b_lane = ((b * PH + y * S) * PW + x * S) * PITCH + lk
+                b_lane = (b * IPIX + y * S * PWP + x * S) * PITCH + lk
                 for i in range(MI):
                     accv = np.zeros((ATOM, ATOM)) if have else None   # [row][column]
                     for s in range(KSTEPS if have else 1):
@@ -164,7 +164,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                             r, sx = tap // WK, tap % WK
                             for kk in range(KK):
                                 ao = P_STAGE + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA
-                                bo = b_lane + (r * PW + sx) * PITCH + kk * KA
+                                bo = b_lane + (r * PWP + sx) * PITCH + kk * KA
                                 assert (ao % 8 == 0).all() and (bo % 8 == 0).all()
                                 assert (ao >= P_STAGE).all() and (ao + 8 <= P_STAGE + A_STAGE).all(), "A fragment outside its part"
                                 assert (bo >= 0).all() and (bo + 8 <= P_STAGE).all(), "B fragment outside the patch"
