@@ -256,7 +256,7 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         changing operands that way, while kernels bound by instruction issue lose).  Elsewhere, and where the
  *         unrolled loop body would grow too long, atom = 1 runs the atom = 0 kernel.
  *  TILE4L: Conv2d only: the input channels in two factors and a three-way choice of the operand path,
- *         Conv2d  B(2) Cout(4) H(4) W(4) Cin(2) unroll{0,1} layout{0,1,2},  Cin = (slabs, channels per slab)
+ *         Conv2d  B(2) Cout(4) H(4) W(4) Cin(2) unroll{0,1} layout{0,1,2} kwaves{1,2,4,8},  Cin = (slabs, channels per slab)
  *         layout = 0: operands as the caller stores them, reduction walked as (ci, r, s): a slab is the slab's
  *         channels with all their Hk*Wk taps (TILE4 with R = (slabs, channels per slab * Hk * Wk)).
  *         layout = 1: channels-last copies written by a pre-pass inside the timed launch, as in TILE4C;
@@ -267,7 +267,12 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         reads its operands from that patch at a fixed offset from the output pixel.  One launch, no pre-pass,
  *         each staged pixel re-used by all taps that touch it.  16-bit inputs, an even image width, slabs of
  *         whole 16 channels (32 on 16x16x32 atoms), at most 16 waves, and patch + kernel-tensor part within the
- *         LDS; elsewhere layout = 2 runs the layout = 0 kernel.  Same sum in another order. */
+ *         LDS; elsewhere layout = 2 runs the layout = 0 kernel.  Same sum in another order.
+ *         kwaves (DISCRETE, layout = 2 only, inert elsewhere): that many waves share every wave tile and deal the
+ *         slab's MFMA steps (taps x groups of channels) round-robin among themselves; their partial sums are added
+ *         through LDS after the last slab, in the order of the waves (deterministic).  The workgroup then has
+ *         (waves along Cout) x (waves along the pixels) x kwaves waves; where it cannot hold them (16 waves, registers,
+ *         LDS for the final sum) the member runs with kwaves = 1. */
 typedef enum { OPEVO_TILE2 = 0, OPEVO_TILE4 = 1, OPEVO_TILE4X = 2, OPEVO_TILE4P = 3, OPEVO_TILE4K = 4, OPEVO_TILE4C = 5, OPEVO_TILE4T = 6,
                OPEVO_TILE4A = 7, OPEVO_TILE4L = 8 } opevo_variant;
 

@@ -41,6 +41,8 @@ static const double kGroupValues[] = {1, 2, 4, 8, 16};
 static const int kNumGroupValues = 5;
 static const double kUnrollSteps[] = {1, 2, 4, 8};
 static const int kNumUnrollSteps = 4;
+static const double kReductionWaves[] = {1, 2, 4, 8};
+static const int kNumReductionWaves = 4;
 
 static opevo_param_desc permutation(const char *name, int n)
 {
@@ -116,11 +118,12 @@ int op_param_descs(const opevo_op &op, int variant, std::vector<opevo_param_desc
         // Conv2d with the input channels in two factors (slabs, channels per slab; every slab holds all the
         // taps) and a three-way choice of how the operands reach the matrix units: gathered from the NCHW
         // image value by value, channels-last copies written by a pre-pass, or an LDS-resident image patch
-        // filled straight from the NCHW image
+        // filled straight from the NCHW image; for the last, the number of waves that share a wave tile and split
+        // the reduction steps of every slab among themselves
         if (op.kind != OPEVO_CONV2D) return fail(OPEVO_E_ARG, "the space with an LDS-resident image patch exists for Conv2d only");
         descs = {factor("B", op.nimg, 2), factor("Cout", op.M, 4), factor("H", op.hout, 4), factor("W", op.wout, 4),
-                 factor("Cin", op.cin, 2), flag("unroll"), flag("layout")};
-        descs.back().n_values = 3;
+                 factor("Cin", op.cin, 2), flag("unroll"), flag("layout"), discrete("kwaves", kReductionWaves, kNumReductionWaves)};
+        descs[descs.size() - 2].n_values = 3;
         return OPEVO_OK;
     }
     if (variant != OPEVO_TILE4 && variant != OPEVO_TILE4X) return fail(OPEVO_E_ARG, "unknown variant %d", variant);
@@ -223,7 +226,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     bool tap_box = false;
     int64_t kunroll = 0;                   // 0: the template's default
     int64_t patch_cs = 0;                  // Conv2d, TILE4L, layout 2: channels per slab of the LDS-resident patch (0: not on that template)
-    int patch_atom = 0, patch_stages = 1;
+    int patch_atom = 0, patch_stages = 1, patch_kw = 1;
     int64_t patch_row = 0, patch_image = 0;   // its row pitch and image pitch in pixels
     int tile4_width = 0;   // slots of the four-level part, after which the launch-order parameters follow
 
@@ -269,14 +272,16 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         } else if (variant == OPEVO_TILE4L) {
             const int64_t taps = op.hk * op.wk;
             flagv = c[16];
-            tile4_width = 18;
+            tile4_width = 19;
             if (c[17] == 1) { layout = 1; ksteps = taps * c[14]; BK = c[15]; }   // channels-last walk (r, s, ci): a slab is c[15] channels of one tap
             else { ksteps = c[14]; BK = c[15] * taps; }                          // walk (ci, r, s): a slab is c[15] channels with all their taps
             // layout 2: the LDS-resident patch, for members it can hold (the others run as with layout 0).
             // 32x32x16 atoms need slabs of whole 16 channels, 16x16x32 atoms of 32; the wave's pixel side is
             // rounded up to whole atoms while that at most doubles the work; the atom that wastes less is taken.
+            // kwaves: that many waves share every wave tile and split the MFMA steps of a slab (taps x channel groups);
+            // where the workgroup cannot hold them the member runs with one
             if (c[17] == 2 && op.dtype != OPEVO_F32) {
-                const int64_t cs = c[15], nw = WM * WN, nt = 64 * nw;
+                const int64_t cs = c[15];
                 auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
                 auto fits = [&](int64_t at) {
                     return TM % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(TN, at) <= 2 * TN && TM * up(TN, at) <= 64 * kMaxAcc;
@@ -291,14 +296,25 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                     lds_p = st * ((nb2 * pimage + taps * WM * TM) * (cs + 8) + 64) * 2;   // + the dump words of a stage
                     if (lds_p <= kMaxLds) break;
                 }
-                // the fill: per thread, tasks of two channels x two pixels (image) and of two channels x all taps (kernel tensor)
-                const int64_t fill_p = (cs / 2 * (pw / 2 + 1) * ph * nb2 + nt - 1) / nt, fill_a = (WM * TM * cs / 2 + nt - 1) / nt;
-                // registers: a lane has 512 / (waves per SIMD); the fill keeps 5 per image task and taps + 2 per kernel-tensor
-                // task (plan and data in flight) next to the accumulators; 64 are left for fragments and addresses
-                const int64_t regs = 512 / ((nw + 3) / 4) - (at ? TM * up(TN, at) / 64 : 0) - 64;
-                if (at && nt <= kMaxThreads && lds_p <= kMaxLds && op.win % 2 == 0 && 5 * fill_p + (taps + 2) * fill_a <= regs &&
-                    op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
-                    patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage;
+                for (int64_t kw = int64_t(kReductionWaves[c[18]]); kw >= 1 && at && !patch_cs; kw = kw > 1 ? 1 : 0) {
+                    const int64_t nw = WM * WN * kw, nt = 64 * nw;
+                    if (kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // more waves than steps
+                    // the fill: per thread, tasks of two channels x two pixels (image) and of two channels x all taps (kernel tensor)
+                    const int64_t fill_p = (cs / 2 * (pw / 2 + 1) * ph * nb2 + nt - 1) / nt, fill_a = (WM * TM * cs / 2 + nt - 1) / nt;
+                    // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
+                    // atom row and column), the fill (3 + 2 per image task, 2 + taps per kernel-tensor task: plan + data in
+                    // flight), 24 for addresses, 40 more where waves share a tile (the final sum).  A member that spills all
+                    // the same is refused when its kernel is loaded.
+                    const int64_t fill = 5 * fill_p + (2 + taps) * fill_a;
+                    const int64_t need = TM * up(TN, at) / 64 + 8 * (TM / at + up(TN, at) / at) + 24 + fill + (kw > 1 ? 40 : 0);
+                    const int64_t have = 512 / ((nw + 3) / 4);
+                    // adding the partial sums of kw waves needs room for one atom of every wave
+                    const int64_t lds_r = kw > 1 ? nw * (at == 32 ? 4 : 1) * 1024 : 0;
+                    if (nt <= kMaxThreads && lds_p <= kMaxLds && lds_r <= kMaxLds && op.win % 2 == 0 &&
+                        need <= have &&
+                        op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
+                        patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage; patch_kw = int(kw);
+                    }
                 }
             }
         } else {
@@ -474,10 +490,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     // needs M % 8 == 0 and LDS staging; other members run on the scalar template
     if (op.trans_a && (path == 1 || path == 2) && (op.M % 8 != 0 || !stage_lds)) path = 0;
 
-    int64_t NT, nwr = WM * WN;   // nwr: waves the workgroup really runs
+    int64_t NT, nwr = WM * WN * patch_kw;   // nwr: waves the workgroup really runs
     if (four_level) {
         if (path == 0) nwr = std::min<int64_t>(nwr, kMaxThreads / 64);   // the scalar template deals outputs round-robin to any number of threads
-        else while (nwr > kMaxThreads / 64) {      // largest divisor of WM * WN that fits
+        else while (path != 5 && nwr > kMaxThreads / 64) {      // largest divisor of WM * WN that fits
             int64_t best = 1;
             for (int64_t dv = kMaxThreads / 64; dv >= 1; --dv) if ((WM * WN) % dv == 0) { best = dv; break; }
             nwr = best;
@@ -498,8 +514,9 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     }
     else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (anr + (b_kmajor ? bnr : BN)) * BK * 2;
-    else if (path == 5)
-        lds = nstage * ((nb2 * patch_image + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2;
+    else if (path == 5)   // the stages, or (more than one wave per tile) one atom of every wave if that is more
+        lds = std::max<int64_t>(nstage * ((nb2 * patch_image + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2,
+                                patch_kw > 1 ? nwr * (patch_atom == 32 ? 4 : 1) * 1024 : 0);
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 
     p.path = path;
@@ -512,7 +529,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     p.tile[0] = int32_t(BM); p.tile[1] = int32_t(BN); p.tile[2] = int32_t(BK);
     p.wave_tile[0] = int32_t(four_level ? TM : BM); p.wave_tile[1] = int32_t(four_level ? TN : BN);
     p.sub_tiles[0] = int32_t(subm); p.sub_tiles[1] = int32_t(subn);
-    p.wave_passes = int32_t(four_level && nwr > 0 ? (WM * WN) / nwr : 1);
+    p.wave_passes = int32_t(four_level && nwr > 0 && path != 5 ? (WM * WN) / nwr : 1);
 
     // ---- black-box constraints made explicit: such members get fitness 0 (Sec. 4.2)
     if (NT > kMaxThreads) invalid(p, "%ld threads per workgroup > %ld", long(NT), long(kMaxThreads));
@@ -554,7 +571,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         D << " -DATOM=" << (path == 5 ? patch_atom : (path == 2 || dlds_atom16) ? 16 : 32) << " -DWM=" << WM << " -DWN=" << WN << " -DTM=" << TM
           << " -DTN=" << TN << " -DFM=" << FM << " -DFN=" << FN << " -DPAD=" << kPad
           << " -DNSTAGE=" << nstage << " -DNSTG=" << nstage << " -DSTAGE_LDS=" << (stage_lds ? 1 : 0);
-        if (nwr != WM * WN) D << " -DNWR=" << nwr;
+        if (nwr != WM * WN && path != 5) D << " -DNWR=" << nwr;
     }
     if (subm * subn > 1) {
         D << " -DSUBM=" << subm << " -DSUBN=" << subn;
@@ -575,7 +592,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     if (tap_box)
         D << " -DTAP_BOX=1 -DCI_O=" << box[0] << " -DCI_I=" << box[1] << " -DHK_O=" << box[2] << " -DHK_I=" << box[3]
           << " -DWK_O=" << box[4] << " -DWK_I=" << box[5];
-    if (path == 5) D << " -DCS=" << patch_cs << " -DPWP=" << patch_row << " -DIPIX=" << patch_image;
+    if (path == 5) D << " -DCS=" << patch_cs << " -DPWP=" << patch_row << " -DIPIX=" << patch_image << " -DKW=" << patch_kw << " -DLDS_BYTES=" << lds;
     if (b_kmajor) D << " -DB_KMAJOR=1 -DBNR=" << bnr;
     if (path == 3 && anr != BM) D << " -DANR=" << anr;
     if (kunroll) D << " -DKUNROLL=" << kunroll;

@@ -22,6 +22,10 @@
 // 4-byte words (one pixel or tap, its two channels).  The padding of 8 elements per row makes 16 consecutive rows
 // start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
 //
+// KW > 1: KW waves share every wave tile and split the reduction: of the HK*WK*(CS/KA) MFMA steps of a slab, wave k of the
+//           KW takes steps k, k + KW, ...; after the last slab the KW partial sums are added through LDS.  With few
+//           output atoms per compute unit (the 14 x 14 convolution: six) this is what lets a large wave tile, whose
+//           fragments are read from LDS once per step instead of once per wave, still keep all four SIMDs busy.
 // FLAG = 1: two stages; the global loads of slab s+1 are in flight (in registers) while slab s is multiplied,
 //           and are written to the other stage afterwards: one barrier per slab.
 // FLAG = 0: one stage: load, barrier, store, barrier, multiply.
@@ -61,16 +65,26 @@ constexpr int DUMP = 64;                                      // elements at the
 constexpr int P_STAGE = NPIX * PITCH, A_STAGE = T * BM * PITCH, STAGE = P_STAGE + A_STAGE + DUMP;   // elements
 constexpr int MI = TM / ATOM, NI = (TN + ATOM - 1) / ATOM;    // atoms per wave tile (the last column of atoms may hang over)
 constexpr int KK = CS / KA;                                   // MFMA steps per tap
+#ifndef KW
+#define KW 1                                                  // waves that share a wave tile and split the reduction steps of every slab
+#endif
+constexpr int STEPS = T * KK;                                 // MFMA steps of a slab
+constexpr int NWAVES = NT / 64;
+static_assert(NWAVES == WM * WN * KW && KW <= STEPS, "decoder and template disagree");
 static_assert(TM % ATOM == 0 && CS % KA == 0 && WIN % 2 == 0 && BK == CS * T && KSTEPS * CS == CIN, "decoder and template disagree");
 static_assert(NSTG * STAGE * 2 <= 160 * 1024, "stages exceed the LDS");
+static_assert(NSTG == (FLAG && KSTEPS > 1 ? 2 : 1), "a pipelined member with more than one slab has two stages, every other member one");
 
 // Patch fill: a task is two channels x an aligned pair of pixels: two 4-byte loads (one per channel), a 2 x 2
-// transposition in registers, two 4-byte LDS stores (one per pixel: its two channels).  Channel pair fastest
-// across the lanes (their stores fall into consecutive banks), then the pair of pixels along the row (their
-// loads into one cache line), then patch row, then image.
+// transposition in registers, two 4-byte LDS stores (one per pixel: its two channels).  Across the lanes four
+// channel pairs are fastest, then the pairs of pixels along the row, the rows and the images, then the remaining
+// channel pairs: 64 lanes load from 4 (or 8) channels, 64 contiguous bytes each, and store 16 pixels x 4 words,
+// which fall into different banks but for the stride of two pixels.
 constexpr int CP = CS / 2;                                    // channel pairs of a slab
 constexpr int NPAIR = PW / 2 + 1;                             // aligned pairs that cover PW columns from either parity
-constexpr int P_TASKS = CP * NPAIR * PH * NB2;
+constexpr int PAIRS = NPAIR * PH * NB2;
+constexpr int P_TASKS = CP * PAIRS;
+static_assert(CP % 4 == 0, "channel pairs are dealt to the lanes four at a time");
 constexpr int NPT = (P_TASKS + NT - 1) / NT;
 // Kernel-tensor fill: a task is one output channel x two input channels: the 2*T values of the two channels are
 // contiguous in the OIHW tensor (T 4-byte loads); tap t of both channels makes one 4-byte LDS store.
@@ -96,7 +110,8 @@ __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, i
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
         const int q = tid + i * NT;
-        const int cp = q % CP, jp = (q / CP) % NPAIR, py = (q / (CP * NPAIR)) % PH, b = q / (CP * NPAIR * PH);
+        const int pr = (q / 4) % PAIRS, cp = q / (4 * PAIRS) * 4 + q % 4;
+        const int jp = pr % NPAIR, py = (pr / NPAIR) % PH, b = pr / (NPAIR * PH);
         const int y = yin0 + py, x = xs + 2 * jp, px = x - xin0;   // px: patch column of the pair's first pixel (-1 .. PW)
         const bool in = (P_TASKS % NT == 0 || q < P_TASKS) && y >= 0 && y < HIN && x >= 0 && x < WIN;
         const bool v0 = in && px >= 0 && px < PW, v1 = in && px + 1 >= 0 && px + 1 < PW;
@@ -167,34 +182,52 @@ __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], c
         bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PWP + s) * PITCH + kk * KA));
 }
 
-__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
+// The MFMA steps WI, WI + KW, ... of a slab, fully unrolled; the fragments of the next step are read before the
+// MFMAs of this one are issued.
+template <int WI>
+__device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
 {
-    constexpr int STEPS = T * KK;
-    if constexpr (STEPS * (MI * NI + MI + NI) <= 512) {
-        // fully unrolled; the fragments of step t+1 are read before the MFMAs of step t are issued
-        frag_t af[2][MI], bf[2][NI];
-        load_frags(af[0], bf[0], As, P, a_lane, b_lane, 0, 0);
+    constexpr int NS = (STEPS - WI + KW - 1) / KW;
+    frag_t af[2][MI], bf[2][NI];
+    load_frags(af[0], bf[0], As, P, a_lane, b_lane, WI / KK, WI % KK);
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
-            if (t + 1 < STEPS) load_frags(af[(t + 1) & 1], bf[(t + 1) & 1], As, P, a_lane, b_lane, (t + 1) / KK, (t + 1) % KK);
+    for (int u = 0; u < NS; ++u) {
+        const int t = WI + (u + 1) * KW;
+        if (u + 1 < NS) load_frags(af[(u + 1) & 1], bf[(u + 1) & 1], As, P, a_lane, b_lane, t / KK, t % KK);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[u & 1][i], bf[u & 1][j], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);             // no more than two sets of fragments alive
+    }
+}
+template <int WI>
+__device__ __forceinline__ void compute_for_wave(int wk, acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
+{
+    if constexpr (WI + 1 < KW) {
+        if (wk == WI) compute_steps<WI>(acc, As, P, a_lane, b_lane);
+        else compute_for_wave<WI + 1>(wk, acc, As, P, a_lane, b_lane);
+    } else {
+        compute_steps<WI>(acc, As, P, a_lane, b_lane);
+    }
+}
+
+// wk: which of the KW waves of its tile this wave is (wave-uniform)
+__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI], int wk)
+{
+    if constexpr (STEPS * (MI * NI + MI + NI) <= 512) {
+        compute_for_wave<0>(wk, acc, As, P, a_lane, b_lane);
+    } else {
+        // long slabs (many taps): the loop over the steps stays a loop
+#pragma unroll 1
+        for (int t = wk; t < STEPS; t += KW) {
+            const int tap = t / KK, kk = t % KK;
+            frag_t af[MI], bf[NI];
+            load_frags(af, bf, As, P, a_lane, b_lane, tap, kk);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[t & 1][i], bf[t & 1][j], acc[i][j]);
-        }
-    } else {
-        // long slabs (many taps): the loop over taps stays a loop
-#pragma unroll 1
-        for (int tap = 0; tap < T; ++tap) {
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                frag_t af[MI], bf[NI];
-                load_frags(af, bf, As, P, a_lane, b_lane, tap, kk);
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[i], bf[j], acc[i][j]);
-            }
+                for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[i], bf[j], acc[i][j]);
         }
     }
 }
@@ -209,7 +242,8 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     const int lrow = lane % ATOM, lk = (lane / ATOM) * 8;
     const BlockId bid = block_id();
     const ColBlock cb = col_block(bid.n);
-    const int wm = wave / WN, wn = wave % WN;
+    const int wk = __builtin_amdgcn_readfirstlane(wave / (WM * WN));   // the wave's part of the reduction steps
+    const int wmn = wave % (WM * WN), wm = wmn / WN, wn = wmn % WN;
     const int m0 = bid.m * BM;
 
     // zeros everywhere first: the patch positions that lie outside the image are never written again
@@ -242,20 +276,22 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 
     Regs regs;
 #if FLAG
+    // Two stages: while slab s is multiplied the loads of slab s+1 are in flight; they are written to the other stage
+    // afterwards (one barrier per slab).  Branch-free body (the loads must not sink below the MFMAs): past the last slab
+    // the last one is loaded and stored once more, into the stage nobody reads any longer.  (Loading two slabs ahead
+    // into a second register set was measured: no faster, and the registers cost members their place on this template.)
     load_slab(regs, fill, A, B, 0);
     __syncthreads();                                   // the zeros are in place
     store_slab(regs, fill, (u32 *)smem);
     __syncthreads();
 #pragma unroll 1
     for (int s = 0; s < KSTEPS; ++s) {
-        u16 *cur = smem + (s & 1) * STAGE, *nxt = smem + ((s + 1) & 1) * STAGE;
-        // branch-free body (the loads must not sink below the MFMAs): past the last slab the last one is loaded
-        // and stored once more, into the stage nobody reads any longer
+        u16 *cur = smem + (s & 1) * STAGE, *nxt = smem + (NSTG == 2 ? (s + 1) & 1 : 0) * STAGE;
         load_slab(regs, fill, A, B, s + 1 < KSTEPS ? s + 1 : KSTEPS - 1);
         __builtin_amdgcn_sched_barrier(0);             // all loads are issued before the first MFMA ...
-        compute_slab(acc, cur + P_STAGE, cur, a_lane, b_lane);
-        __builtin_amdgcn_sched_barrier(0);             // ... and waited for after the last
-        store_slab(regs, fill, (u32 *)nxt);
+        compute_slab(acc, cur + P_STAGE, cur, a_lane, b_lane, wk);
+        __builtin_amdgcn_sched_barrier(0);             // ... and the stores follow the last
+        if (NSTG == 2) store_slab(regs, fill, (u32 *)nxt);
         __syncthreads();
     }
 #else
@@ -265,12 +301,13 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         __syncthreads();                               // slab s-1 has been multiplied (first pass: the zeros are in place)
         store_slab(regs, fill, (u32 *)smem);
         __syncthreads();
-        compute_slab(acc, smem + P_STAGE, smem, a_lane, b_lane);
+        compute_slab(acc, smem + P_STAGE, smem, a_lane, b_lane, wk);
     }
 #endif
 
     // Epilogue.  An atom's result sits with column (l % ATOM) in lane l; 32x32: register r is row
     // 8*(r/4) + 4*(l/32) + r%4; 16x16: register r is row 4*(l/16) + r.
+#if KW == 1
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -286,4 +323,51 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
             }
         }
     }
+#else
+    // The KW waves of a tile hold partial sums.  In passes of APP atoms (as many as the LDS holds for all waves), every
+    // wave writes its accumulators of the pass's atoms to LDS, R[atom][wave][4 registers][lane]; then wave k of a tile adds,
+    // in the order of the waves, the KW partial sums of the atoms k, k + KW, ... of the pass and stores them.
+    constexpr int ATOMS = MI * NI, Q = NACC / 4;
+    constexpr int APP_FIT = LDS_BYTES / (NWAVES * Q * 1024);
+    constexpr int APP = APP_FIT < ATOMS ? APP_FIT : ATOMS;
+    static_assert(APP >= 1, "the LDS cannot hold one atom of every wave");
+    f32x4 *R = (f32x4 *)smem;
+#pragma unroll
+    for (int a0 = 0; a0 < ATOMS; a0 += APP) {
+        __syncthreads();                               // the stages (or the previous pass) are no longer read
+#pragma unroll
+        for (int a = a0; a < a0 + APP && a < ATOMS; ++a)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const acc_t &v = acc[a / NI][a % NI];
+                const f32x4 w = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+                R[(((a - a0) * NWAVES + wave) * Q + q) * 64 + lane] = w;
+            }
+        __syncthreads();
+#pragma unroll 1
+        for (int a = a0 + wk; a < a0 + APP && a < ATOMS; a += KW) {
+            const int i = a / NI, j = a % NI;
+            const int ct = j * ATOM + lrow;
+            const int cn = wn * TN + (ct < TN ? ct : TN - 1);
+            const long c0 = conv_c_index(cb, m0 + wm * TM + i * ATOM, cn);   // row 0 of the atom; a row is HOUT*WOUT further
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                f32x4 sum = R[(((a - a0) * NWAVES + wmn) * Q + q) * 64 + lane];
+#pragma unroll
+                for (int k = 1; k < KW; ++k) {
+                    const f32x4 v = R[(((a - a0) * NWAVES + k * (WM * WN) + wmn) * Q + q) * 64 + lane];
+                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                }
+                if (TN % ATOM == 0 || ct < TN) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = 4 * q + e;
+                        const int row = (ATOM == 32) ? 8 * (r / 4) + 4 * (lane / 32) + r % 4 : 4 * (lane / 16) + r;
+                        C[c0 + (long)row * (HOUT * WOUT)] = sum[e];
+                    }
+                }
+            }
+        }
+    }
+#endif
 }

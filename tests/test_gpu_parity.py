@@ -874,7 +874,7 @@ def test_conv14_split_reduction_channels_last_full_size_and_alg1(torch_cuda):
 
 # ------------------------------------------------------------------ Conv2d with an LDS-resident image patch (TILE4L)
 def test_conv_with_an_lds_resident_patch(torch_cuda):
-    """TILE4L: B(2) Cout(4) H(4) W(4) Cin(2) unroll layout{0,1,2}.  layout = 2: the image patch under the workgroup's
+    """TILE4L: B(2) Cout(4) H(4) W(4) Cin(2) unroll layout{0,1,2} kwaves{1,2,4,8}.  layout = 2: the image patch under the workgroup's
     box and the slab's part of the kernel tensor are staged in LDS channels-last straight from the NCHW / OIHW
     operands (no pre-pass) and every tap reads them at a fixed offset.  Both atoms, one and two stages, ragged
     pixel tiles, boxes at every border, stride 2, 5x5 and 1x1 kernels, several images per box, fp16, the other two
@@ -890,16 +890,19 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
 
     w = Workload(torch_cuda, "conv2d", (1, 64, 56, 56, 64, 3, 3, 1, 1), "bf16", 1237)
     for label, cfg, atom in [
-            ("patch: 64 channels x 4 rows of 56, 4 waves, slabs of 32", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2], 16),
-            ("patch: the same, single stage", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 0, 2], 16),
-            ("patch: 32 channels x boxes of 8 x 28, slabs of 16, 8 waves", [1, 1, 2, 1, 1, 32, 7, 4, 1, 2, 2, 2, 1, 14, 4, 16, 1, 2], 32),
-            ("patch: 16x16 atoms, 16 channels per wave, boxes of 7 x 8 (ragged: 56 -> 64)", [1, 1, 2, 2, 1, 16, 8, 1, 1, 7, 7, 1, 1, 8, 2, 32, 1, 2], 16),
-            ("patch: one slab of 64 channels", [1, 1, 2, 1, 1, 32, 14, 2, 1, 2, 1, 2, 1, 28, 1, 64, 1, 2], 32)]:
+            ("patch: 64 channels x 4 rows of 56, 4 waves, slabs of 32", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 0], 16),
+            ("patch: the same, single stage", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 0, 2, 0], 16),
+            ("patch: 32 channels x boxes of 8 x 28, slabs of 16, 8 waves", [1, 1, 2, 1, 1, 32, 7, 4, 1, 2, 2, 2, 1, 14, 4, 16, 1, 2, 0], 32),
+            ("patch: 16x16 atoms, 16 channels per wave, boxes of 7 x 8 (ragged: 56 -> 64)", [1, 1, 2, 2, 1, 16, 8, 1, 1, 7, 7, 1, 1, 8, 2, 32, 1, 2, 0], 16),
+            ("patch: one slab of 64 channels", [1, 1, 2, 1, 1, 32, 14, 2, 1, 2, 1, 2, 1, 28, 1, 64, 1, 2, 0], 32),
+            ("patch: 64 channels x 2 rows of 56 shared by 4 waves (18 steps: 5, 5, 4, 4)", [1, 1, 1, 1, 2, 32, 28, 1, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 2], 16),
+            ("patch: 2 tiles of 32 x 112 shared by 2 waves each, single stage", [1, 1, 2, 1, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 4, 16, 0, 2, 1], 32),
+            ("patch: 32 x 56 shared by 8 waves, slabs of 64", [1, 1, 2, 1, 1, 32, 56, 1, 1, 1, 1, 1, 1, 56, 1, 64, 1, 2, 3], None)]:
         patch(w, cfg, label, atom)
     # the other two layouts of the space are the gather and the channels-last members of TILE4 / TILE4C
-    for label, cfg, path in [("layout 0: gather, slab = 8 channels x 9 taps", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 0], None),
-                             ("layout 1: channels last, slab = 32 channels of a tap", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 1], None),
-                             ("layout 2 where no patch member exists (slabs of 8 channels): the gather", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2], None)]:
+    for label, cfg, path in [("layout 0: gather, slab = 8 channels x 9 taps", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 0, 0], None),
+                             ("layout 1: channels last, slab = 32 channels of a tap", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 1, 0], None),
+                             ("layout 2 where no patch member exists (slabs of 8 channels): the gather", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None)]:
         plan = P.opevo_kernel_plan(w.op, V, cfg)
         assert plan.status == P.OPEVO_OK and plan.path != 5 and (path is None or plan.path == path), (label, plan.path)
         assert ("-DCONV_NHWC=1" in P.opevo_kernel_defines(w.op, V, cfg)) == (cfg[17] == 1), label
@@ -909,7 +912,7 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
     for cfg in w.random_valid(V, 12, seed=1302, want_paths=(0, 1, 2, 3)):
         w.check(V, cfg, "random")
     # one kernel object, launched again after the inputs changed
-    cfg = [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2]
+    cfg = [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 0]
     kernel, _ = P.opevo_kernel_build(w.op, V, cfg)
     w.b.mul_(2.0)                                  # image doubled (exact in bf16): the output must double
     out2 = w.run(V, cfg, kernel)
@@ -924,38 +927,42 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
     w.close()
     # stride 2 with padding 1 (taps outside the image on the top and left borders only), two images per box
     w = Workload(torch_cuda, "conv2d", (4, 32, 10, 10, 64, 3, 3, 2, 1), "bf16", 47)     # out 5x5
-    for label, cfg, atom in [("patch: stride 2, 2 images x 5 x 5 -> 64, 4 waves of 16 channels", [2, 2, 1, 4, 1, 16, 1, 1, 1, 5, 1, 1, 1, 5, 1, 32, 1, 2], 16),
-                             ("patch: stride 2, one image, 25 -> 32 pixels, slabs of 16", [4, 1, 2, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 2, 16, 1, 2], 32)]:
+    for label, cfg, atom in [("patch: stride 2, 2 images x 5 x 5 -> 64, 4 waves of 16 channels", [2, 2, 1, 4, 1, 16, 1, 1, 1, 5, 1, 1, 1, 5, 1, 32, 1, 2, 0], 16),
+                             ("patch: stride 2, one image, 25 -> 32 pixels, slabs of 16", [4, 1, 2, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 5, 2, 16, 1, 2, 0], 32)]:
         patch(w, cfg, label, atom)
     for cfg in w.random_valid(V, 8, seed=1303, want_paths=(5,)):
         w.check(V, cfg, "random")
     w.close()
     # 5x5 with padding 2, fp16
     w = Workload(torch_cuda, "conv2d", (4, 32, 12, 12, 32, 5, 5, 1, 2), "f16", 42)
-    for label, cfg, atom in [("patch: 5x5, 32 x (12 x 12), 4 waves of 32 x 36 -> 48", [4, 1, 1, 1, 1, 32, 1, 2, 1, 6, 1, 2, 1, 6, 1, 32, 1, 2], 16),
-                             ("patch: 5x5, boxes of 4 x 6, 2 slabs of 16", [4, 1, 1, 1, 1, 32, 3, 1, 1, 4, 2, 1, 1, 6, 2, 16, 1, 2], 32)]:
+    for label, cfg, atom in [("patch: 5x5, 32 x (12 x 12), 4 waves of 32 x 36 -> 48", [4, 1, 1, 1, 1, 32, 1, 2, 1, 6, 1, 2, 1, 6, 1, 32, 1, 2, 0], 16),
+                             ("patch: 5x5, boxes of 4 x 6, 2 slabs of 16", [4, 1, 1, 1, 1, 32, 3, 1, 1, 4, 2, 1, 1, 6, 2, 16, 1, 2, 0], 32)]:
         patch(w, cfg, label, atom)
     for cfg in w.random_valid(V, 8, seed=1304, want_paths=(5,)):
         w.check(V, cfg, "random")
     w.close()
     # 7x7 with padding 3: 49 taps, the loop over taps stays a loop
     w = Workload(torch_cuda, "conv2d", (2, 32, 12, 12, 32, 7, 7, 1, 3), "bf16", 49)
-    patch(w, [2, 1, 1, 2, 1, 16, 1, 2, 1, 6, 1, 1, 1, 12, 1, 32, 1, 2], "patch: 7x7, 4 waves of 16 x 72 -> 80, taps rolled", 16)
+    patch(w, [2, 1, 1, 2, 1, 16, 1, 2, 1, 6, 1, 1, 1, 12, 1, 32, 1, 2, 0], "patch: 7x7, 4 waves of 16 x 72 -> 80, taps rolled", 16)
     w.close()
     # 1x1 kernel without padding: the patch is the box itself
     w = Workload(torch_cuda, "conv2d", (2, 64, 8, 8, 64, 1, 1, 1, 0), "bf16", 48)
-    patch(w, [2, 1, 1, 2, 1, 32, 1, 1, 1, 8, 1, 1, 1, 8, 2, 32, 1, 2], "patch: 1x1, 2 waves of 32 x 64", 32)
+    patch(w, [2, 1, 1, 2, 1, 32, 1, 1, 1, 8, 1, 1, 1, 8, 2, 32, 1, 2, 0], "patch: 1x1, 2 waves of 32 x 64", 32)
     w.close()
 
 
 def test_conv14_with_an_lds_resident_patch_full_size_and_alg1(torch_cuda):
     V = P.OPEVO_TILE4L
     w = Workload(torch_cuda, "conv2d", (32, 256, 14, 14, 256, 3, 3, 1, 1), "bf16", 1239)
-    for label, cfg in [("patch: 32 channels x one image, 4 waves of 32 x 49 -> 64", [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
-                       ("patch: 64 channels x 2 rows, 4 waves, 16x16 atoms", [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2]),
-                       ("patch: 16x16 atoms, 8 waves, 2 images per box", [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
-                       ("patch: 7 waves of 32 x 28 -> 32, slabs of 64", [32, 1, 8, 1, 1, 32, 1, 7, 1, 2, 1, 1, 1, 14, 4, 64, 1, 2]),
-                       ("patch: 128 channels x 7 rows, 8 waves, slabs of 16", [32, 1, 2, 4, 1, 32, 2, 1, 1, 7, 1, 2, 1, 7, 16, 16, 1, 2])]:
+    for label, cfg in [("patch: 32 channels x one image, 4 waves of 32 x 49 -> 64", [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
+                       ("patch: 64 channels x 2 rows, 4 waves, 16x16 atoms", [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2, 0]),
+                       ("patch: 16x16 atoms, 8 waves, 2 images per box", [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
+                       ("patch: 7 waves of 32 x 28 -> 32, slabs of 32", [32, 1, 8, 1, 1, 32, 1, 7, 1, 2, 1, 1, 1, 14, 8, 32, 1, 2, 0]),
+                       ("patch: 128 channels x 7 rows, 8 waves, slabs of 16", [32, 1, 2, 4, 1, 32, 2, 1, 1, 7, 1, 2, 1, 7, 16, 16, 1, 2, 0]),
+                       ("patch: 64 channels x 7 rows (98 -> 128 pixels) shared by 4 waves", [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]),
+                       ("patch: 32 channels x 7 rows shared by 8 waves, two passes of the final sum", [32, 1, 8, 1, 1, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 3]),
+                       ("patch: 128 channels x 2 rows x 2 images shared by 4 waves, single stage", [16, 2, 2, 1, 4, 32, 7, 1, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 2]),
+                       ("patch: 2 tiles of 32 x 196 -> 224 shared by 2 waves each (9 steps: 5, 4)", [32, 1, 4, 2, 1, 32, 1, 1, 1, 14, 1, 1, 1, 14, 16, 16, 1, 2, 1])]:
         plan = P.opevo_kernel_plan(w.op, V, cfg)
         assert plan.status == P.OPEVO_OK and plan.path == 5, (label, plan.status, plan.path, plan.reason)
         w.check(V, cfg, label)

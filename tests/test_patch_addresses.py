@@ -44,7 +44,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     assert (CIN, HIN, WIN, HK, WK, S, PAD, M) == (cin, hin, win, hk, wk, stride, pad, cout)
     T = HK * WK
     PH, PW = (BH - 1) * S + HK, (BW - 1) * S + WK
-    PWP, IPIX = g("PWP"), g("IPIX")
+    PWP, IPIX, KW, LDS_BYTES = g("PWP"), g("IPIX"), g("KW"), g("LDS_BYTES")
     assert PWP >= PW and IPIX >= PH * PWP
     NPIX = NB2 * IPIX
     PITCH, DUMP = CS + 8, 64
@@ -54,8 +54,9 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     NACC = 16 if ATOM == 32 else 4
     MI, NI, KK = TM // ATOM, (TN + ATOM - 1) // ATOM, CS // KA
     assert TM % ATOM == 0 and CS % KA == 0 and WIN % 2 == 0 and BK == CS * T and KSTEPS * CS == CIN and K == CIN * T
-    assert NSTG * STAGE * 2 == plan.lds_bytes <= 160 * 1024
-    assert NT == 64 * WM * WN == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
+    assert NSTG * STAGE * 2 <= LDS_BYTES == plan.lds_bytes <= 160 * 1024
+    assert NT == 64 * WM * WN * KW == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
+    assert 1 <= KW <= T * (CS // (16 if ATOM == 32 else 32))
     assert MI * NI * NACC == plan.acc_per_lane <= 256
     CP = CS // 2
     NPAIR = PW // 2 + 1
@@ -83,7 +84,9 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         pg, pd0, pd1 = [], [], []
         for i in range(NPT):
             q = tid + i * NT
-            cp, jp, py, b = q % CP, (q // CP) % NPAIR, (q // (CP * NPAIR)) % PH, q // (CP * NPAIR * PH)
+            PAIRS = NPAIR * PH * NB2
+            pr, cp = (q // 4) % PAIRS, q // (4 * PAIRS) * 4 + q % 4
+            jp, py, b = pr % NPAIR, (pr // NPAIR) % PH, pr // (NPAIR * PH)
             y, x = yin0 + py, xs + 2 * jp
             px = x - xin0
             inside = (q < P_TASKS) & (y >= 0) & (y < HIN) & (x >= 0) & (x < WIN)
@@ -146,11 +149,13 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                 base = P_STAGE + (tap * BM + m) * PITCH
                 want = (m0 + m) * K + np.arange(CS) * T + tap
                 assert (asrc[base:base + CS] == want).all(), ("kernel-tensor value", bx, by, tap, m)
-        # ---- fragments: every lane's reads, and (with operands) the sum they form
+        # ---- fragments: every lane's reads, and (with operands) the sum they form.  Wave = (wk, wm, wn): the KW waves of a
+        # tile take the MFMA steps t = tap * KK + kk with t % KW == wk; their partial sums are added in the epilogue.
         lane = np.arange(64)
         lrow, lk = lane % ATOM, (lane // ATOM) * 8
-        for wave in range(WM * WN):
-            wm, wn = wave // WN, wave % WN
+        STEPS = T * KK
+        for wmn in range(WM * WN):
+            wm, wn = wmn // WN, wmn % WN
             a_lane = (wm * TM + lrow) * PITCH + lk
             for j in range(NI):
                 ct = j * ATOM + lrow
@@ -158,27 +163,30 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                 b, y, x = cn // (BH * BW), (cn // BW) % BH, cn % BW
                 b_lane = (b * IPIX + y * S * PWP + x * S) * PITCH + lk
                 for i in range(MI):
-                    accv = np.zeros((ATOM, ATOM)) if have else None   # [row][column]
-                    for s in range(KSTEPS if have else 1):
-                        for tap in range(T):
+                    accv = np.zeros((ATOM, ATOM)) if have else None   # [row][column], summed over the KW waves
+                    steps_done = np.zeros(STEPS, dtype=np.int32)
+                    for wk in range(KW):
+                        for t in range(wk, STEPS, KW):
+                            steps_done[t] += 1
+                            tap, kk = t // KK, t % KK
                             r, sx = tap // WK, tap % WK
-                            for kk in range(KK):
-                                ao = P_STAGE + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA
-                                bo = b_lane + (r * PWP + sx) * PITCH + kk * KA
-                                assert (ao % 8 == 0).all() and (bo % 8 == 0).all()
-                                assert (ao >= P_STAGE).all() and (ao + 8 <= P_STAGE + A_STAGE).all(), "A fragment outside its part"
-                                assert (bo >= 0).all() and (bo + 8 <= P_STAGE).all(), "B fragment outside the patch"
-                                if have:
-                                    # lane l supplies 8 reduction values of row / column l % ATOM; lanes with equal l / ATOM pair up
-                                    av = np.zeros((64, 8)); bv = np.zeros((64, 8))
-                                    for t in range(8):
-                                        sa, sb = asrc[ao + t], src[bo + t]
-                                        assert (sa >= 0).all(), "A fragment reads an unwritten element"
-                                        av[:, t] = ker_flat[sa + s * CS * T]
-                                        bv[:, t] = np.where(sb >= 0, img_flat[np.maximum(sb, 0) + s * CS * HIN * WIN], 0.0)
-                                    for grp in range(64 // ATOM):
-                                        sel = slice(grp * ATOM, (grp + 1) * ATOM)
-                                        accv += av[sel] @ bv[sel].T
+                            ao = P_STAGE + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA
+                            bo = b_lane + (r * PWP + sx) * PITCH + kk * KA
+                            assert (ao % 8 == 0).all() and (bo % 8 == 0).all()
+                            assert (ao >= P_STAGE).all() and (ao + 8 <= P_STAGE + A_STAGE).all(), "A fragment outside its part"
+                            assert (bo >= 0).all() and (bo + 8 <= P_STAGE).all(), "B fragment outside the patch"
+                            for s in range(KSTEPS if have else 0):
+                                # lane l supplies 8 reduction values of row / column l % ATOM; lanes with equal l / ATOM pair up
+                                av = np.zeros((64, 8)); bv = np.zeros((64, 8))
+                                for e in range(8):
+                                    sa, sb = asrc[ao + e], src[bo + e]
+                                    assert (sa >= 0).all(), "A fragment reads an unwritten element"
+                                    av[:, e] = ker_flat[sa + s * CS * T]
+                                    bv[:, e] = np.where(sb >= 0, img_flat[np.maximum(sb, 0) + s * CS * HIN * WIN], 0.0)
+                                for grp in range(64 // ATOM):
+                                    sel = slice(grp * ATOM, (grp + 1) * ATOM)
+                                    accv += av[sel] @ bv[sel].T
+                    assert (steps_done == 1).all()
                     # epilogue: lane l holds column l % ATOM; register r holds the row stated in the template
                     for l in range(64):
                         if ct[l] >= TN:
@@ -192,6 +200,24 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                             written[nb, gm, yy, xx] += 1
                             if have:
                                 out[nb, gm, yy, xx] = accv[row, l % ATOM]
+        # ---- more than one wave per tile: the passes of the final sum through LDS
+        if KW > 1:
+            NWAVES, ATOMS, Q = NT // 64, MI * NI, NACC // 4
+            APP = min(LDS_BYTES // (NWAVES * Q * 1024), ATOMS)
+            assert APP >= 1
+            owner = np.full(ATOMS, -1)
+            for a0 in range(0, ATOMS, APP):
+                top = min(a0 + APP, ATOMS)
+                for a in range(a0, top):
+                    for wave in range(NWAVES):
+                        for q in range(Q):
+                            word = (((a - a0) * NWAVES + wave) * Q + q) * 64 + 63      # 16-byte words; the last lane's
+                            assert (word + 1) * 16 <= LDS_BYTES
+                for wk in range(KW):
+                    for a in range(a0 + wk, top, KW):
+                        assert owner[a] == -1
+                        owner[a] = wk
+            assert (owner >= 0).all(), "an atom of the wave tile is never summed and stored"
     return out, written
 
 
@@ -211,13 +237,13 @@ def direct_conv(img, ker, stride, pad):
 
 SMALL = [
     # dims (B, Cin, H, W, Cout, Hk, Wk, stride, pad), configuration B(2) Cout(4) H(4) W(4) Cin(2) unroll layout
-    ("3x3 pad 1, 32x32 atoms, ragged pixel side", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 2, 16, 1, 2]),
-    ("3x3 pad 1, 16x16 atoms, two channel waves", (2, 64, 4, 8, 64, 3, 3, 1, 1), [2, 1, 2, 2, 1, 16, 1, 1, 2, 2, 2, 1, 1, 4, 2, 32, 1, 2]),
-    ("3x3 no padding, single stage", (1, 32, 6, 6, 32, 3, 3, 1, 0), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 2, 2, 2, 16, 0, 2]),
-    ("5x5 pad 1, 16x16 atoms", (1, 32, 8, 6, 32, 5, 5, 1, 1), [1, 1, 1, 2, 1, 16, 1, 2, 1, 3, 1, 1, 1, 4, 1, 32, 1, 2]),
-    ("5x5 pad 2, boxes of 3 columns", (1, 16, 6, 6, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 1, 1, 1, 6, 2, 1, 1, 3, 1, 16, 1, 2]),
-    ("3x3 stride 2 pad 1", (1, 32, 8, 8, 32, 3, 3, 2, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2]),
-    ("1x1", (2, 32, 4, 4, 64, 1, 1, 1, 0), [2, 1, 1, 2, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2]),
+    ("3x3 pad 1, 32x32 atoms, ragged pixel side", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 2, 16, 1, 2, 0]),
+    ("3x3 pad 1, 16x16 atoms, two channel waves", (2, 64, 4, 8, 64, 3, 3, 1, 1), [2, 1, 2, 2, 1, 16, 1, 1, 2, 2, 2, 1, 1, 4, 2, 32, 1, 2, 0]),
+    ("3x3 no padding, single stage", (1, 32, 6, 6, 32, 3, 3, 1, 0), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 2, 2, 2, 16, 0, 2, 0]),
+    ("5x5 pad 1, 16x16 atoms", (1, 32, 8, 6, 32, 5, 5, 1, 1), [1, 1, 1, 2, 1, 16, 1, 2, 1, 3, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
+    ("5x5 pad 2, boxes of 3 columns", (1, 16, 6, 6, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 1, 1, 1, 6, 2, 1, 1, 3, 1, 16, 1, 2, 0]),
+    ("3x3 stride 2 pad 1", (1, 32, 8, 8, 32, 3, 3, 2, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
+    ("1x1", (2, 32, 4, 4, 64, 1, 1, 1, 0), [2, 1, 1, 2, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
 ]
 
 
@@ -232,11 +258,34 @@ def test_the_patch_template_computes_the_convolution(label, dims, cfg):
     assert np.array_equal(out, direct_conv(img, ker, stride, pad))
 
 
+KWAVES = [
+    ("two waves split 9 taps x 2 steps", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 1, 32, 1, 2, 1]),
+    ("four waves, 16x16 atoms, 9 steps (3, 2, 2, 2)", (2, 64, 4, 8, 64, 3, 3, 1, 1), [2, 1, 2, 1, 2, 16, 1, 1, 2, 2, 1, 1, 1, 8, 2, 32, 1, 2, 2]),
+    ("eight waves of two tiles, single stage", (1, 64, 6, 6, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 1, 1, 1, 6, 1, 1, 1, 6, 2, 32, 0, 2, 2]),
+]
+
+
+@pytest.mark.parametrize("label,dims,cfg", KWAVES, ids=[c[0] for c in KWAVES])
+def test_waves_that_split_the_reduction(label, dims, cfg):
+    rng = np.random.default_rng(8)
+    nimg, cin, hin, win, cout, hk, wk, stride, pad = dims
+    img = rng.integers(-3, 4, size=(nimg, cin, hin, win)).astype(np.float64)
+    ker = rng.integers(-3, 4, size=(cout, cin, hk, wk)).astype(np.float64)
+    op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
+    assert "-DKW=%d" % (1, 2, 4, 8)[cfg[18]] in P.opevo_kernel_defines(op, V, cfg).split()
+    out, written = emulate(dims, cfg, img, ker)
+    assert (written == 1).all()
+    assert np.array_equal(out, direct_conv(img, ker, stride, pad))
+
+
 FULL = [
-    ("conv14, 32 channels x one image, 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
-    ("conv14, 64 channels x two rows", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2]),
-    ("conv14, 16x16 atoms, 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]),
-    ("conv56, 64 channels x 4 rows", (1, 64, 56, 56, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2]),
+    ("conv14, 32 channels x one image, 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
+    ("conv14, 64 channels x two rows", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2, 0]),
+    ("conv14, 16x16 atoms, 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
+    ("conv56, 64 channels x 4 rows", (1, 64, 56, 56, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 0]),
+    ("conv14, 64 channels x 7 rows shared by 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]),
+    ("conv14, 128 channels x 2 rows x 2 images shared by 4 waves, single stage", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 2, 1, 4, 32, 7, 1, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 2]),
+    ("conv14, 32 channels x 7 rows shared by 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 3]),
 ]
 
 
@@ -257,13 +306,13 @@ def test_members_outside_the_patch_template_run_as_layout_0():
     for cfg in ([32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 32, 8, 1],     # slabs of 8 channels
                 [32, 1, 256, 1, 1, 1, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1],    # one channel per workgroup
                 [1, 32, 1, 1, 2, 128, 1, 1, 1, 14, 1, 1, 1, 14, 8, 32, 1]): # 32 images in one box: no room in the LDS
-        p2 = P.opevo_kernel_plan(op, V, cfg + [2])
-        p0 = P.opevo_kernel_plan(op, V, cfg + [0])
+        p2 = P.opevo_kernel_plan(op, V, cfg + [2, 1])
+        p0 = P.opevo_kernel_plan(op, V, cfg + [0, 0])
         assert p2.path != 5
         assert (p2.status, p2.path, list(p2.grid), p2.block, p2.lds_bytes) == (p0.status, p0.path, list(p0.grid), p0.block, p0.lds_bytes)
     # odd image width
     op27 = P.opevo_op_create(P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2), P.OPEVO_BF16)
-    assert P.opevo_kernel_plan(op27, V, [4, 1, 2, 1, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 1, 2]).path != 5
+    assert P.opevo_kernel_plan(op27, V, [4, 1, 2, 1, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 1, 2, 0]).path != 5
     # fp32 inputs
     opf = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_F32)
-    assert P.opevo_kernel_plan(opf, V, [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2]).path != 5
+    assert P.opevo_kernel_plan(opf, V, [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]).path != 5
