@@ -66,7 +66,7 @@ def main() -> int:
     ap.add_argument("--split-reduction", action="store_true",
                     help="Conv2d only: tune in the space that splits C_in, H_k and W_k separately and has the discrete unroll bound")
     ap.add_argument("--space", default=None, choices=["TILE2", "TILE4", "TILE4X", "TILE4P", "TILE4K", "TILE4C", "TILE4T", "TILE4A", "TILE4L"],
-                    help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4C for Conv2d, TILE4A for the 16-bit 8192^3 MatMul, else TILE4)")
+                    help="configuration space to tune in (default: TILE2 for the 64^3 workload, TILE4L for Conv2d (TILE4C where no LDS-resident-patch member exists), TILE4A for the 16-bit 8192^3 MatMul, else TILE4)")
     ap.add_argument("--extended", action="store_true",
                     help="tune in the extended space (launch order as a permutation, group width as a discrete parameter)")
     ap.add_argument("--oracle-rows", type=int, default=32,
@@ -141,7 +141,9 @@ def main() -> int:
     if args.space:
         variant = names[args.space]
     elif w["kind"] == "conv2d" and variant == P.OPEVO_TILE4:
-        variant = P.OPEVO_TILE4C    # the conv space with the reduction split and the channels-last choice
+        # the conv space with the operand path as a choice (gather, channels-last copies, LDS-resident patch); images of odd
+        # width or fewer than 16 input channels have no patch member: the space with the reduction split instead
+        variant = P.OPEVO_TILE4L if (w["dims"][3] % 2 == 0 and w["dims"][1] % 16 == 0) else P.OPEVO_TILE4C
     elif args.workload.startswith("mm8192") and dtype != "f32" and variant == P.OPEVO_TILE4:
         variant = P.OPEVO_TILE4A    # the MatMul space with the MFMA atom as a choice (the power-limited size)
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])

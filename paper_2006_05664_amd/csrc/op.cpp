@@ -278,43 +278,58 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             // layout 2: the LDS-resident patch, for members it can hold (the others run as with layout 0).
             // 32x32x16 atoms need slabs of whole 16 channels, 16x16x32 atoms of 32; the wave's pixel side is
             // rounded up to whole atoms while that at most doubles the work; the atom that wastes less is taken.
-            // kwaves: that many waves share every wave tile and split the MFMA steps of a slab (taps x channel groups);
-            // where the workgroup cannot hold them the member runs with one
-            if (c[17] == 2 && op.dtype != OPEVO_F32) {
-                const int64_t cs = c[15];
+            // kwaves: that many waves share every wave tile and split the MFMA steps of a slab (taps x channel groups).
+            // A member that asks for what the template has not is folded rather than sent away (same workgroup tile,
+            // another division of it among the waves): slabs of fewer than 16 channels are merged; wave tiles of fewer
+            // than 16 output channels are merged along Cout; with more than 16 waves kwaves is halved, then the waves
+            // along the pixels are merged a prime at a time (their tiles grow).
+            if (c[17] == 2 && op.dtype != OPEVO_F32 && op.win % 2 == 0 && op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
                 auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
-                auto fits = [&](int64_t at) {
-                    return TM % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(TN, at) <= 2 * TN && TM * up(TN, at) <= 64 * kMaxAcc;
-                };
-                const int at = fits(32) && (!fits(16) || up(TN, 32) == up(TN, 16)) ? 32 : fits(16) ? 16 : 0;
+                auto prime = [](int64_t n) { for (int64_t q = 2; q * q <= n; ++q) if (n % q == 0) return q; return n; };
+                int64_t cs = c[15], tm = TM, wm = WM;
+                while (cs % 16 != 0 && cs < op.cin) cs *= prime(op.cin / cs);
+                const int64_t slabs = op.cin / cs;
                 const int64_t ph = (BH - 1) * op.stride + op.hk, pw = (BW - 1) * op.stride + op.wk;
-                const int st = (flagv && ksteps > 1) ? 2 : 1;
+                const int st = (flagv && slabs > 1) ? 2 : 1;
                 // the padded pitches if the LDS has room for them, else the plain ones
                 int64_t prow = 0, pimage = 0, lds_p = 0;
                 for (int padded = 1; padded >= 0; --padded) {
                     patch_pitches(op, BH, BW, padded == 1, prow, pimage);
-                    lds_p = st * ((nb2 * pimage + taps * WM * TM) * (cs + 8) + 64) * 2;   // + the dump words of a stage
+                    lds_p = st * ((nb2 * pimage + taps * wm * tm) * (cs + 8) + 64) * 2;   // + the dump words of a stage
                     if (lds_p <= kMaxLds) break;
                 }
-                for (int64_t kw = int64_t(kReductionWaves[c[18]]); kw >= 1 && at && !patch_cs; kw = kw > 1 ? 1 : 0) {
-                    const int64_t nw = WM * WN * kw, nt = 64 * nw;
-                    if (kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // more waves than steps
+                // the waves along Cout are merged, a prime at a time, until an atom fits the wave tile
+                for (; !patch_cs; ) {
+                for (int64_t kw = int64_t(kReductionWaves[c[18]]); kw >= 1 && !patch_cs && tm % 16 == 0; kw /= 2) {
+                    int64_t wn = WN, tn = TN;
+                    while (wm * wn * kw > kMaxThreads / 64 && wn > 1) { const int64_t q = prime(wn); wn /= q; tn *= q; }
+                    const int64_t nw = wm * wn * kw, nt = 64 * nw;
+                    if (nt > kMaxThreads) continue;
+                    auto fits = [&](int64_t at) {
+                        return tm % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(tn, at) <= 2 * tn && tm * up(tn, at) <= 64 * kMaxAcc;
+                    };
+                    const int at = fits(32) && (!fits(16) || up(tn, 32) == up(tn, 16)) ? 32 : fits(16) ? 16 : 0;
+                    if (!at || kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // no atom fits; more waves than steps
                     // the fill: per thread, tasks of two channels x two pixels (image) and of two channels x all taps (kernel tensor)
-                    const int64_t fill_p = (cs / 2 * (pw / 2 + 1) * ph * nb2 + nt - 1) / nt, fill_a = (WM * TM * cs / 2 + nt - 1) / nt;
+                    const int64_t fill_p = (cs / 2 * (pw / 2 + 1) * ph * nb2 + nt - 1) / nt, fill_a = (wm * tm * cs / 2 + nt - 1) / nt;
                     // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
                     // atom row and column), the fill (3 + 2 per image task, 2 + taps per kernel-tensor task: plan + data in
                     // flight), 24 for addresses, 40 more where waves share a tile (the final sum).  A member that spills all
                     // the same is refused when its kernel is loaded.
                     const int64_t fill = 5 * fill_p + (2 + taps) * fill_a;
-                    const int64_t need = TM * up(TN, at) / 64 + 8 * (TM / at + up(TN, at) / at) + 24 + fill + (kw > 1 ? 40 : 0);
+                    const int64_t need = tm * up(tn, at) / 64 + 8 * (tm / at + up(tn, at) / at) + 24 + fill + (kw > 1 ? 40 : 0);
                     const int64_t have = 512 / ((nw + 3) / 4);
                     // adding the partial sums of kw waves needs room for one atom of every wave
                     const int64_t lds_r = kw > 1 ? nw * (at == 32 ? 4 : 1) * 1024 : 0;
-                    if (nt <= kMaxThreads && lds_p <= kMaxLds && lds_r <= kMaxLds && op.win % 2 == 0 &&
-                        need <= have &&
-                        op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
+                    if (lds_p <= kMaxLds && lds_r <= kMaxLds && need <= have) {
                         patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage; patch_kw = int(kw);
+                        // the member as the template runs it
+                        WM = wm; TM = tm; WN = wn; TN = tn; FM = std::gcd(FM, TM); FN = std::gcd(FN, TN);
+                        ksteps = slabs; BK = cs * taps;
                     }
+                }
+                if (wm == 1) break;
+                const int64_t q = prime(wm); wm /= q; tm *= q;
                 }
             }
         } else {

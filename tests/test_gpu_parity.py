@@ -897,12 +897,14 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
             ("patch: one slab of 64 channels", [1, 1, 2, 1, 1, 32, 14, 2, 1, 2, 1, 2, 1, 28, 1, 64, 1, 2, 0], 32),
             ("patch: 64 channels x 2 rows of 56 shared by 4 waves (18 steps: 5, 5, 4, 4)", [1, 1, 1, 1, 2, 32, 28, 1, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 2], 16),
             ("patch: 2 tiles of 32 x 112 shared by 2 waves each, single stage", [1, 1, 2, 1, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 4, 16, 0, 2, 1], 32),
-            ("patch: 32 x 56 shared by 8 waves, slabs of 64", [1, 1, 2, 1, 1, 32, 56, 1, 1, 1, 1, 1, 1, 56, 1, 64, 1, 2, 3], None)]:
+            ("patch: 32 x 56 shared by 8 waves, slabs of 64", [1, 1, 2, 1, 1, 32, 56, 1, 1, 1, 1, 1, 1, 56, 1, 64, 1, 2, 3], None),
+            ("patch, folded: slabs of 8 channels run as slabs of 16", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None),
+            ("patch, folded: 4 waves of 8 output channels run as 2 of 16, kwaves 8 as what the workgroup holds", [1, 1, 2, 4, 2, 4, 14, 4, 1, 1, 1, 1, 1, 56, 2, 32, 1, 2, 3], None)]:
         patch(w, cfg, label, atom)
     # the other two layouts of the space are the gather and the channels-last members of TILE4 / TILE4C
     for label, cfg, path in [("layout 0: gather, slab = 8 channels x 9 taps", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 0, 0], None),
                              ("layout 1: channels last, slab = 32 channels of a tap", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 1, 0], None),
-                             ("layout 2 where no patch member exists (slabs of 8 channels): the gather", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None)]:
+                             ("layout 2 where no patch member exists (8 output channels per workgroup): the gather", [1, 1, 8, 1, 2, 4, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None)]:
         plan = P.opevo_kernel_plan(w.op, V, cfg)
         assert plan.status == P.OPEVO_OK and plan.path != 5 and (path is None or plan.path == path), (label, plan.path)
         assert ("-DCONV_NHWC=1" in P.opevo_kernel_defines(w.op, V, cfg)) == (cfg[17] == 1), label

@@ -278,6 +278,28 @@ def test_waves_that_split_the_reduction(label, dims, cfg):
     assert np.array_equal(out, direct_conv(img, ker, stride, pad))
 
 
+FOLDED = [
+    # members that ask for what the template has not, and the division of the same workgroup tile it runs instead
+    ("slabs of 8 channels -> 16", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 4, 8, 1, 2, 0], dict(CS=16, KSTEPS=2)),
+    ("4 waves of 8 output channels -> one of 32", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 4, 2, 4, 2, 1, 1, 3, 1, 2, 1, 4, 2, 16, 1, 2, 0], dict(WM=1, TM=32)),
+    ("8 x 4 x 2 waves -> 8 x 2 waves (kwaves 1, pixel waves merged)", (2, 32, 6, 8, 128, 3, 3, 1, 1), [2, 1, 1, 8, 1, 16, 1, 2, 1, 3, 1, 2, 1, 4, 1, 32, 1, 2, 1], dict(WM=8, WN=2, TN=24, KW=1)),
+]
+
+
+@pytest.mark.parametrize("label,dims,cfg,want", FOLDED, ids=[c[0] for c in FOLDED])
+def test_folded_members(label, dims, cfg, want):
+    rng = np.random.default_rng(9)
+    nimg, cin, hin, win, cout, hk, wk, stride, pad = dims
+    img = rng.integers(-3, 4, size=(nimg, cin, hin, win)).astype(np.float64)
+    ker = rng.integers(-3, 4, size=(cout, cin, hk, wk)).astype(np.float64)
+    op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
+    _, D = defines(op, cfg)
+    assert {k: D[k] for k in want} == want
+    out, written = emulate(dims, cfg, img, ker)
+    assert (written == 1).all()
+    assert np.array_equal(out, direct_conv(img, ker, stride, pad))
+
+
 FULL = [
     ("conv14, 32 channels x one image, 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
     ("conv14, 64 channels x two rows", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2, 0]),
@@ -303,7 +325,7 @@ def test_members_outside_the_patch_template_run_as_layout_0():
     """layout 2 is inert where the template cannot hold the member: the plan is the layout-0 member's."""
     dims = (32, 256, 14, 14, 256, 3, 3, 1, 1)
     op = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_BF16)
-    for cfg in ([32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 32, 8, 1],     # slabs of 8 channels
+    for cfg in ([32, 1, 32, 1, 1, 8, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1],     # 8 output channels per workgroup
                 [32, 1, 256, 1, 1, 1, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1],    # one channel per workgroup
                 [1, 32, 1, 1, 2, 128, 1, 1, 1, 14, 1, 1, 1, 14, 8, 32, 1]): # 32 images in one box: no room in the LDS
         p2 = P.opevo_kernel_plan(op, V, cfg + [2, 1])
