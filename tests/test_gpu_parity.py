@@ -904,7 +904,7 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
     # the other two layouts of the space are the gather and the channels-last members of TILE4 / TILE4C
     for label, cfg, path in [("layout 0: gather, slab = 8 channels x 9 taps", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 0, 0], None),
                              ("layout 1: channels last, slab = 32 channels of a tap", [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 1, 0], None),
-                             ("layout 2 where no patch member exists (8 output channels per workgroup): the gather", [1, 1, 8, 1, 2, 4, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None)]:
+                             ("layout 2 where no patch member exists (fewer than 16 output channels per workgroup): the gather", [1, 1, 16, 1, 1, 4, 14, 2, 1, 2, 1, 1, 1, 56, 8, 8, 1, 2, 0], None)]:
         plan = P.opevo_kernel_plan(w.op, V, cfg)
         assert plan.status == P.OPEVO_OK and plan.path != 5 and (path is None or plan.path == path), (label, plan.path)
         assert ("-DCONV_NHWC=1" in P.opevo_kernel_defines(w.op, V, cfg)) == (cfg[17] == 1), label
