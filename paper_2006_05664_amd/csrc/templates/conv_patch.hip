@@ -17,7 +17,7 @@
 //     patch is the same for every slab.
 //   * the kernel tensor's part, A[tap][BM][CS (+8)], so that an A fragment is 16 contiguous bytes too.
 // Both parts are transposed on the way in, two channels at a time: a thread loads 4-byte pairs of pixels of two
-// channels (rows of the NCHW image are contiguous in x; WIN is even, so aligned pairs never straddle a row), or the
+// channels (rows of the NCHW image are contiguous in x; with WIN even, aligned pairs never straddle a row), or the
 // 2*HK*WK contiguous values of two input channels of one output channel, swaps halves in registers and stores
 // 4-byte words (one pixel or tap, its two channels).  The padding of 8 elements per row makes 16 consecutive rows
 // start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
@@ -71,7 +71,7 @@ constexpr int KK = CS / KA;                                   // MFMA steps per 
 constexpr int STEPS = T * KK;                                 // MFMA steps of a slab
 constexpr int NWAVES = NT / 64;
 static_assert(NWAVES == WM * WN * KW && KW <= STEPS, "decoder and template disagree");
-static_assert(TM % ATOM == 0 && CS % KA == 0 && WIN % 2 == 0 && BK == CS * T && KSTEPS * CS == CIN, "decoder and template disagree");
+static_assert(TM % ATOM == 0 && CS % KA == 0 && BK == CS * T && KSTEPS * CS == CIN, "decoder and template disagree");
 static_assert(NSTG * STAGE * 2 <= 160 * 1024, "stages exceed the LDS");
 static_assert(NSTG == (FLAG && KSTEPS > 1 ? 2 : 1), "a pipelined member with more than one slab has two stages, every other member one");
 
@@ -80,8 +80,11 @@ static_assert(NSTG == (FLAG && KSTEPS > 1 ? 2 : 1), "a pipelined member with mor
 // channel pairs are fastest, then the pairs of pixels along the row, the rows and the images, then the remaining
 // channel pairs: 64 lanes load from 4 (or 8) channels, 64 contiguous bytes each, and store 16 pixels x 4 words,
 // which fall into different banks but for the stride of two pixels.
+// An image of odd width has no aligned pairs (a row starts at any 2-byte offset): there a task is two channels x
+// one pixel, two 2-byte loads and one 4-byte store.
+constexpr bool PAIRED = WIN % 2 == 0;
 constexpr int CP = CS / 2;                                    // channel pairs of a slab
-constexpr int NPAIR = PW / 2 + 1;                             // aligned pairs that cover PW columns from either parity
+constexpr int NPAIR = PAIRED ? PW / 2 + 1 : PW;               // aligned pairs that cover PW columns from either parity (odd width: pixels)
 constexpr int PAIRS = NPAIR * PH * NB2;
 constexpr int P_TASKS = CP * PAIRS;
 static_assert(CP % 4 == 0, "channel pairs are dealt to the lanes four at a time");
@@ -112,9 +115,9 @@ __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, i
         const int q = tid + i * NT;
         const int pr = (q / 4) % PAIRS, cp = q / (4 * PAIRS) * 4 + q % 4;
         const int jp = pr % NPAIR, py = (pr / NPAIR) % PH, b = pr / (NPAIR * PH);
-        const int y = yin0 + py, x = xs + 2 * jp, px = x - xin0;   // px: patch column of the pair's first pixel (-1 .. PW)
+        const int y = yin0 + py, x = PAIRED ? xs + 2 * jp : xin0 + jp, px = x - xin0;   // px: patch column of the task's first pixel (-1 .. PW)
         const bool in = (P_TASKS % NT == 0 || q < P_TASKS) && y >= 0 && y < HIN && x >= 0 && x < WIN;
-        const bool v0 = in && px >= 0 && px < PW, v1 = in && px + 1 >= 0 && px + 1 < PW;
+        const bool v0 = in && px >= 0 && px < PW, v1 = PAIRED && in && px + 1 >= 0 && px + 1 < PW;
         const int d0 = ((b * IPIX + py * PWP + px) * PITCH) / 2 + cp, dump = (STAGE - DUMP) / 2 + (tid & 31);
         f.pg[i] = (v0 || v1) ? 2u * (u32)((((cb.nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x) : 0u;
         f.pd0[i] = (u32)(v0 ? d0 : dump);
@@ -136,9 +139,14 @@ __device__ __forceinline__ void load_slab(Regs &r, const Fill &f, const u16 *__r
     const char *Bs = (const char *)(B + (long)s * CS * HIN * WIN);
     const char *As = (const char *)(A + (long)s * CS * T);
 #pragma unroll
-    for (int i = 0; i < NPT; ++i) {
-        r.p[i][0] = *(const u32 *)(Bs + f.pg[i]);
-        r.p[i][1] = *(const u32 *)(Bs + f.pg[i] + 2 * HIN * WIN);   // the next channel (offset 0 for an idle task: still inside the tensor)
+    for (int i = 0; i < NPT; ++i) {   // the second load is the next channel (offset 0 for an idle task: still inside the tensor)
+        if constexpr (PAIRED) {
+            r.p[i][0] = *(const u32 *)(Bs + f.pg[i]);
+            r.p[i][1] = *(const u32 *)(Bs + f.pg[i] + 2 * HIN * WIN);
+        } else {
+            r.p[i][0] = *(const u16 *)(Bs + f.pg[i]);
+            r.p[i][1] = *(const u16 *)(Bs + f.pg[i] + 2 * HIN * WIN);
+        }
     }
 #pragma unroll
     for (int i = 0; i < NAT; ++i)
@@ -152,7 +160,7 @@ __device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u32 *S)
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
         S[f.pd0[i]] = (r.p[i][0] & 0xffffu) | (r.p[i][1] << 16);         // first pixel: its two channels
-        S[f.pd1[i]] = (r.p[i][0] >> 16) | (r.p[i][1] & 0xffff0000u);     // second pixel
+        if constexpr (PAIRED) S[f.pd1[i]] = (r.p[i][0] >> 16) | (r.p[i][1] & 0xffff0000u);     // second pixel
     }
     u32 *SA = S + P_STAGE / 2;
 #pragma unroll

@@ -633,6 +633,10 @@ PAPER_SHAPES = [
     # the same operator in the space with the split reduction and channels-last operands: direct-to-LDS members
     ("C2 channels last", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (3,),
      [("6 waves of 32 x 243 -> 256, slabs of 32", [512, 1, 3, 2, 1, 32, 1, 3, 9, 1, 1, 1, 27, 1, 1, 50, 32, 1, 1])], "TILE4C"),
+    # the same operator with an LDS-resident image patch (odd image width: the fill loads pixel by pixel; 25 taps read each staged pixel)
+    ("C2 LDS-resident patch", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (5,),
+     [("64 channels x 9 rows of 27 -> 256 pixels, 2 channel waves x 2 waves per tile, single stage", [512, 1, 3, 2, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 2]),
+      ("32 channels x one image, 3 pixel waves of 243 -> 256", [512, 1, 6, 1, 1, 32, 1, 3, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 0])], "TILE4L"),
     # C1's reduction axis 3*11*11 = 363 has no factor 16: MFMA members stage zero-padded K slabs
     ("C1", "conv2d", (512, 3, 227, 227, 64, 11, 11, 4, 0), 1243, 2, (0, 1, 2),
      [("scalar, 16 x 484 tile", [128, 4, 4, 1, 4, 4, 5, 11, 1, 1, 5, 1, 11, 1, 11, 33, 1])]),
@@ -946,6 +950,19 @@ def test_conv_with_an_lds_resident_patch(torch_cuda):
     # 7x7 with padding 3: 49 taps, the loop over taps stays a loop
     w = Workload(torch_cuda, "conv2d", (2, 32, 12, 12, 32, 7, 7, 1, 3), "bf16", 49)
     patch(w, [2, 1, 1, 2, 1, 16, 1, 2, 1, 6, 1, 1, 1, 12, 1, 32, 1, 2, 0], "patch: 7x7, 4 waves of 16 x 72 -> 80, taps rolled", 16)
+    w.close()
+    # odd image width (no aligned pairs of pixels: the fill loads pixel by pixel), 3x3 and stride 2
+    w = Workload(torch_cuda, "conv2d", (4, 32, 11, 11, 32, 3, 3, 1, 1), "bf16", 50)
+    for label, cfg, atom in [("patch: 11 x 11, one image per box, 121 -> 128 pixels, 4 waves", [4, 1, 1, 1, 1, 32, 1, 1, 1, 11, 1, 1, 1, 11, 2, 16, 1, 2, 2], 32),
+                             ("patch: 11 x 11, 2 images x 11 rows x 1 column boxes of 16x16 atoms", [2, 2, 2, 1, 1, 16, 1, 1, 1, 11, 11, 1, 1, 1, 1, 32, 1, 2, 0], 16)]:
+        patch(w, cfg, label, atom)
+    for cfg in w.random_valid(V, 10, seed=1305, want_paths=(5,)):
+        w.check(V, cfg, "random")
+    w.close()
+    w = Workload(torch_cuda, "conv2d", (2, 32, 13, 13, 32, 3, 3, 2, 1), "bf16", 51)     # out 7x7
+    patch(w, [2, 1, 1, 1, 1, 32, 1, 1, 1, 7, 1, 1, 1, 7, 1, 32, 1, 2, 1], "patch: odd width, stride 2, 49 -> 64 pixels, 2 waves per tile", None)
+    for cfg in w.random_valid(V, 6, seed=1306, want_paths=(5,)):
+        w.check(V, cfg, "random")
     w.close()
     # 1x1 kernel without padding: the patch is the box itself
     w = Workload(torch_cuda, "conv2d", (2, 64, 8, 8, 64, 1, 1, 1, 0), "bf16", 48)

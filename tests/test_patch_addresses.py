@@ -53,13 +53,14 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     KA = 16 if ATOM == 32 else 32
     NACC = 16 if ATOM == 32 else 4
     MI, NI, KK = TM // ATOM, (TN + ATOM - 1) // ATOM, CS // KA
-    assert TM % ATOM == 0 and CS % KA == 0 and WIN % 2 == 0 and BK == CS * T and KSTEPS * CS == CIN and K == CIN * T
+    assert TM % ATOM == 0 and CS % KA == 0 and BK == CS * T and KSTEPS * CS == CIN and K == CIN * T
+    PAIRED = WIN % 2 == 0
     assert NSTG * STAGE * 2 <= LDS_BYTES == plan.lds_bytes <= 160 * 1024
     assert NT == 64 * WM * WN * KW == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
     assert 1 <= KW <= T * (CS // (16 if ATOM == 32 else 32))
     assert MI * NI * NACC == plan.acc_per_lane <= 256
     CP = CS // 2
-    NPAIR = PW // 2 + 1
+    NPAIR = PW // 2 + 1 if PAIRED else PW
     P_TASKS = CP * NPAIR * PH * NB2
     NPT = (P_TASKS + NT - 1) // NT
     A_TASKS = BM * CP
@@ -87,11 +88,11 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
             PAIRS = NPAIR * PH * NB2
             pr, cp = (q // 4) % PAIRS, q // (4 * PAIRS) * 4 + q % 4
             jp, py, b = pr % NPAIR, (pr // NPAIR) % PH, pr // (NPAIR * PH)
-            y, x = yin0 + py, xs + 2 * jp
+            y, x = yin0 + py, (xs + 2 * jp if PAIRED else xin0 + jp)
             px = x - xin0
             inside = (q < P_TASKS) & (y >= 0) & (y < HIN) & (x >= 0) & (x < WIN)
             v0 = inside & (px >= 0) & (px < PW)
-            v1 = inside & (px + 1 >= 0) & (px + 1 < PW)
+            v1 = inside & (px + 1 >= 0) & (px + 1 < PW) & PAIRED
             goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x), 0)
             d0 = ((b * IPIX + py * PWP + px) * PITCH) // 2 + cp      # 4-byte words
             dump = (STAGE - DUMP) // 2 + (tid & 31)
@@ -107,7 +108,8 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
             for i in range(NPT):
                 for ch in range(2):
                     o = 2 * s * CS * HIN * WIN + pg[i] + ch * 2 * HIN * WIN
-                    assert (o >= 0).all() and (o + 4 <= img_bytes).all() and (o % 4 == 0).all(), ("image load", bx, by, s, i)
+                    width = 4 if PAIRED else 2
+                    assert (o >= 0).all() and (o + width <= img_bytes).all() and (o % width == 0).all(), ("image load", bx, by, s, i)
             for i in range(NAT):
                 for t in range(T):
                     o = 2 * s * CS * T + ag[i] + 4 * t
@@ -116,7 +118,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         src = np.full(STAGE, -1, dtype=np.int64)   # which global element (of slab 0) each LDS element receives; -1: never written (zeros)
         hits = np.zeros(STAGE, dtype=np.int32)
         for i in range(NPT):
-            for dst, e in ((pd0[i], 0), (pd1[i], 1)):        # word of pixel e: low half = first channel, high half = second
+            for dst, e in (((pd0[i], 0), (pd1[i], 1)) if PAIRED else ((pd0[i], 0),)):   # word of pixel e: low half = first channel, high half = second
                 assert (dst >= 0).all() and (2 * dst + 1 < STAGE).all(), ("patch store", bx, by, i)
                 real = 2 * dst < STAGE - DUMP
                 assert (2 * dst[real] + 1 < P_STAGE).all()
@@ -244,6 +246,9 @@ SMALL = [
     ("5x5 pad 2, boxes of 3 columns", (1, 16, 6, 6, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 1, 1, 1, 6, 2, 1, 1, 3, 1, 16, 1, 2, 0]),
     ("3x3 stride 2 pad 1", (1, 32, 8, 8, 32, 3, 3, 2, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
     ("1x1", (2, 32, 4, 4, 64, 1, 1, 1, 0), [2, 1, 1, 2, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
+    ("odd width: 3x3 pad 1 on 5 x 7", (2, 32, 5, 7, 32, 3, 3, 1, 1), [2, 1, 1, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 7, 2, 16, 1, 2, 0]),
+    ("odd width: 5x5 pad 2 on 9 x 9, boxes of 3 rows", (1, 16, 9, 9, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 3, 1, 1, 3, 1, 1, 1, 9, 1, 16, 1, 2, 0]),
+    ("odd width: stride 2 on 7 x 7, two waves per tile", (2, 32, 7, 7, 32, 3, 3, 2, 1), [1, 2, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 1]),
 ]
 
 
@@ -305,6 +310,7 @@ FULL = [
     ("conv14, 64 channels x two rows", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 2, 1, 32, 7, 2, 1, 1, 1, 1, 1, 14, 8, 32, 1, 2, 0]),
     ("conv14, 16x16 atoms, 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
     ("conv56, 64 channels x 4 rows", (1, 64, 56, 56, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 0]),
+    ("C2 (27 x 27, 5x5, odd width), 64 channels x 9 rows, single stage", (512, 64, 27, 27, 192, 5, 5, 1, 2), [512, 1, 3, 2, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 2]),
     ("conv14, 64 channels x 7 rows shared by 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]),
     ("conv14, 128 channels x 2 rows x 2 images shared by 4 waves, single stage", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 2, 1, 4, 32, 7, 1, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 2]),
     ("conv14, 32 channels x 7 rows shared by 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 3]),
@@ -332,9 +338,6 @@ def test_members_outside_the_patch_template_run_as_layout_0():
         p0 = P.opevo_kernel_plan(op, V, cfg + [0, 0])
         assert p2.path != 5
         assert (p2.status, p2.path, list(p2.grid), p2.block, p2.lds_bytes) == (p0.status, p0.path, list(p0.grid), p0.block, p0.lds_bytes)
-    # odd image width
-    op27 = P.opevo_op_create(P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2), P.OPEVO_BF16)
-    assert P.opevo_kernel_plan(op27, V, [4, 1, 2, 1, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 1, 2, 0]).path != 5
     # fp32 inputs
     opf = P.opevo_op_create(P.OPEVO_CONV2D, dims, P.OPEVO_F32)
     assert P.opevo_kernel_plan(opf, V, [32, 1, 8, 1, 1, 32, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]).path != 5
