@@ -317,7 +317,8 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                     // flight), 24 for addresses, 40 more where waves share a tile (the final sum).  A member that spills all
                     // the same is refused when its kernel is loaded.
                     const int64_t fill = 5 * fill_p + (2 + taps) * fill_a;
-                    const int64_t need = tm * up(tn, at) / 64 + 8 * (tm / at + up(tn, at) / at) + 24 + fill + (kw > 1 ? 40 : 0);
+                    const int64_t frags = tm / at + up(tn, at) / at;   // fragments of a step: two sets of 4 registers each, three for small wave tiles
+                    const int64_t need = tm * up(tn, at) / 64 + (frags <= 3 ? 12 : 8) * frags + 24 + fill + (kw > 1 ? 40 : 0);
                     const int64_t have = 512 / ((nw + 3) / 4);
                     // adding the partial sums of kw waves needs room for one atom of every wave
                     const int64_t lds_r = kw > 1 ? nw * (at == 32 ? 4 : 1) * 1024 : 0;

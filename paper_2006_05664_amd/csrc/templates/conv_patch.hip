@@ -190,23 +190,33 @@ __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], c
         bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PWP + s) * PITCH + kk * KA));
 }
 
-// The MFMA steps WI, WI + KW, ... of a slab, fully unrolled; the fragments of the next step are read before the
-// MFMAs of this one are issued.
+// The MFMA steps WI, WI + KW, ... of a slab, fully unrolled; the fragments of step u + FRAG_AHEAD are read before the
+// MFMAs of step u are issued (a ring of FRAG_AHEAD + 1 sets of fragment registers).
+// Small wave tiles have too few MFMAs per step to cover the LDS latency of the next step's fragments: they read two steps
+// ahead (measured on the 14 x 14 convolution: 5 - 9 % for one-atom tiles, 1.6 % for two atoms, nothing beyond).
+#ifndef FRAG_AHEAD
+#define FRAG_AHEAD ((TM / ATOM) + (TN + ATOM - 1) / ATOM <= 3 ? 2 : 1)
+#endif
 template <int WI>
 __device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
 {
     constexpr int NS = (STEPS - WI + KW - 1) / KW;
-    frag_t af[2][MI], bf[2][NI];
-    load_frags(af[0], bf[0], As, P, a_lane, b_lane, WI / KK, WI % KK);
+    constexpr int RING = FRAG_AHEAD + 1;
+    frag_t af[RING][MI], bf[RING][NI];
+#pragma unroll
+    for (int u = 0; u < FRAG_AHEAD && u < NS; ++u) {
+        const int t = WI + u * KW;
+        load_frags(af[u], bf[u], As, P, a_lane, b_lane, t / KK, t % KK);
+    }
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
-        const int t = WI + (u + 1) * KW;
-        if (u + 1 < NS) load_frags(af[(u + 1) & 1], bf[(u + 1) & 1], As, P, a_lane, b_lane, t / KK, t % KK);
+        const int t = WI + (u + FRAG_AHEAD) * KW;
+        if (u + FRAG_AHEAD < NS) load_frags(af[(u + FRAG_AHEAD) % RING], bf[(u + FRAG_AHEAD) % RING], As, P, a_lane, b_lane, t / KK, t % KK);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[u & 1][i], bf[u & 1][j], acc[i][j]);
-        __builtin_amdgcn_sched_barrier(0);             // no more than two sets of fragments alive
+            for (int j = 0; j < NI; ++j) acc[i][j] = MFMA(af[u % RING][i], bf[u % RING][j], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);             // no more sets of fragments alive than the ring has
     }
 }
 template <int WI>
