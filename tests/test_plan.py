@@ -510,6 +510,89 @@ def test_conv_split_channels_last_templates_compile(label, kd, cfg, path):
     P.opevo_kernel_destroy(kernel)
 
 
+
+# ---------------------------------------------------------------- Conv2d: the operand path as a choice, LDS-resident patch (TILE4L)
+def test_conv_patch_space_and_its_decoding():
+    op = _op(CONV14, P.OPEVO_BF16)
+    V = P.OPEVO_TILE4L
+    sp = P.opevo_op_space(op, V)
+    names = [P.opevo_space_param_name(sp, i) for i in range(P.opevo_space_num_params(sp))]
+    assert names == ["B", "Cout", "H", "W", "Cin", "unroll", "layout", "kwaves"] and P.opevo_space_width(sp) == 19
+    assert P.opevo_space_param_size(sp, 4) == 9 and P.opevo_space_param_size(sp, 6) == 3 and P.opevo_space_param_size(sp, 7) == 4
+    P.opevo_space_destroy(sp)
+    for kd in (MM1, BMM):
+        with pytest.raises(P.OpevoError):
+            P.opevo_op_space(_op(kd, P.OPEVO_BF16), V)
+    # 32 output channels x one image, 7 pixel waves of 28 -> 32 x 2 waves per tile, slabs of 32 channels, single stage
+    cfg = [32, 1, 8, 1, 1, 32, 1, 7, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 1]
+    plan = P.opevo_kernel_plan(op, V, cfg)
+    d = P.opevo_kernel_defines(op, V, cfg)
+    assert d.startswith("conv_patch:")
+    assert plan.status == P.OPEVO_OK and plan.path == 5 and list(plan.grid) == [32, 8, 1] and plan.block == 64 * 7 * 2
+    assert list(plan.tile) == [32, 196, 32 * 9] and list(plan.wave_tile) == [32, 28] and plan.acc_per_lane == 16
+    # patch of 16 rows, row pitch 30 (16 raised to be congruent to 14 modulo 16), image pitch 480 + 4 (congruent to 196)
+    for want in ("-DATOM=32", "-DCS=32", "-DKSTEPS=8", "-DKW=2", "-DNSTG=1", "-DPWP=30", "-DIPIX=484", "-DWM=1", "-DWN=7"):
+        assert want in d.split(), (want, d)
+    assert plan.lds_bytes == ((484 + 9 * 32) * 40 + 64) * 2
+    # the other two layouts of the same member: the gather walks (ci, r, s) in slabs of 32 * 9, the channels-last
+    # member (r, s, ci) in slabs of 32, with its pre-pass; kwaves is inert there
+    d0 = P.opevo_kernel_defines(op, V, cfg[:17] + [0, 1])
+    assert not d0.startswith("conv_patch:") and "-DBK=288" in d0.split() and "-DKSTEPS=8" in d0.split() and "CONV_NHWC" not in d0 and "-DKW" not in d0
+    d1 = P.opevo_kernel_defines(op, V, cfg[:17] + [1, 1])
+    assert "-DBK=32" in d1.split() and "-DKSTEPS=72" in d1.split() and "-DCONV_NHWC=1" in d1.split()
+    with pytest.raises(P.OpevoError):                          # 8 * 16 != 256
+        P.opevo_kernel_plan(op, V, cfg[:14] + [8, 16, 0, 2, 1])
+    with pytest.raises(P.OpevoError):                          # layout has three values
+        P.opevo_kernel_plan(op, V, cfg[:17] + [3, 1])
+    # 16x16x32 atoms where they pad the pixel side less (98 -> 112 instead of 128) and the slab has whole 32 channels
+    assert "-DATOM=16" in P.opevo_kernel_defines(op, V, [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]).split()
+    # an image of odd width is filled pixel by pixel: same template
+    c27 = _op((P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2)), P.OPEVO_BF16)
+    assert P.opevo_kernel_plan(c27, V, [4, 1, 1, 2, 1, 32, 3, 3, 1, 3, 1, 1, 1, 27, 4, 16, 0, 2, 0]).path == 5
+    # three input channels (the paper's C1): no slab of 16 channels, no patch member
+    c1 = _op((P.OPEVO_CONV2D, (16, 3, 35, 35, 16, 11, 11, 4, 0)), P.OPEVO_BF16)
+    assert P.opevo_kernel_plan(c1, V, [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 3, 1, 2, 0]).path != 5
+
+
+def test_conv_patch_space_is_not_mostly_invalid_and_the_patch_template_has_a_share_of_it():
+    for kd, share in ((CONV14, 0.05), (CONV56, 0.08)):
+        op = _op(kd, P.OPEVO_BF16)
+        V = P.OPEVO_TILE4L
+        sp = P.opevo_op_space(op, V)
+        rng = P.opevo_rng_create(5)
+        paths, valid, total = {}, 0, 3000
+        for _ in range(total):
+            cfg = P.opevo_space_random(sp, rng)
+            plan = P.opevo_kernel_plan(op, V, cfg)
+            if plan.status == P.OPEVO_OK:
+                valid += 1
+                paths[plan.path] = paths.get(plan.path, 0) + 1
+                assert plan.lds_bytes <= 160 * 1024 and plan.block <= 1024 and plan.acc_per_lane <= 256 and plan.grid[2] == 1
+                if plan.path == 5:
+                    assert cfg[17] == 2
+        assert valid > 0.5 * total and set(paths) == {0, 1, 2, 3, 5} and paths[5] > share * total, (valid, paths)
+        P.opevo_rng_destroy(rng); P.opevo_space_destroy(sp)
+
+
+TILE4L_COMPILE_CASES = [
+    ("patch, 14 waves (7 pixel waves x 2 per tile), single stage", CONV14, [32, 1, 8, 1, 1, 32, 1, 7, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 1], 5),
+    ("patch, 16x16 atoms, 64 x 98 -> 112 shared by 4 waves, two stages", CONV14, [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2], 5),
+    ("patch, folded: slabs of 8 channels, 4 waves of 8 output channels", CONV56, [1, 1, 2, 4, 2, 4, 14, 4, 1, 1, 1, 1, 1, 56, 8, 8, 1, 2, 3], 5),
+    ("patch, odd width, 25 taps", (P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2)), [4, 1, 1, 2, 1, 32, 3, 3, 1, 3, 1, 1, 1, 27, 4, 16, 0, 2, 0], 5),
+    ("patch, 49 taps: the loop over the steps stays a loop", (P.OPEVO_CONV2D, (2, 32, 12, 12, 32, 7, 7, 1, 3)), [2, 1, 1, 2, 1, 16, 1, 2, 1, 6, 1, 1, 1, 12, 1, 32, 1, 2, 0], 5),
+    ("channels last in this space (direct-to-LDS)", CONV56, [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 1, 0], 3),
+]
+
+
+@pytest.mark.parametrize("label,kd,cfg,path", TILE4L_COMPILE_CASES, ids=[c[0] for c in TILE4L_COMPILE_CASES])
+def test_conv_patch_templates_compile(label, kd, cfg, path):
+    op = _op(kd, P.OPEVO_BF16)
+    plan = P.opevo_kernel_plan(op, P.OPEVO_TILE4L, cfg)
+    assert plan.status == P.OPEVO_OK and plan.path == path, (plan.reason, plan.path)
+    kernel, _ = P.opevo_kernel_build(op, P.OPEVO_TILE4L, cfg)
+    assert 1000 < P.opevo_kernel_code_size(kernel) < (128 << 10)
+    P.opevo_kernel_destroy(kernel)
+
 # ---------------------------------------------------------------- MatMul: second operand transposed by a pre-pass (TILE4T)
 def test_packed_second_operand_space_and_its_decoding():
     op = _op((P.OPEVO_MATMUL, (8192, 8192, 8192)), P.OPEVO_BF16)
