@@ -141,9 +141,9 @@ def main() -> int:
     if args.space:
         variant = names[args.space]
     elif w["kind"] == "conv2d" and variant == P.OPEVO_TILE4:
-        # the conv space with the operand path as a choice (gather, channels-last copies, LDS-resident patch); images of odd
-        # width or fewer than 16 input channels have no patch member: the space with the reduction split instead
-        variant = P.OPEVO_TILE4L if (w["dims"][3] % 2 == 0 and w["dims"][1] % 16 == 0) else P.OPEVO_TILE4C
+        # the conv space with the operand path as a choice (gather, channels-last copies, LDS-resident patch); with fewer than
+        # 16 input channels there is no patch member: the space with the reduction split instead
+        variant = P.OPEVO_TILE4L if w["dims"][1] % 16 == 0 else P.OPEVO_TILE4C
     elif args.workload.startswith("mm8192") and dtype != "f32" and variant == P.OPEVO_TILE4:
         variant = P.OPEVO_TILE4A    # the MatMul space with the MFMA atom as a choice (the power-limited size)
     op = P.opevo_op_create(kind, w["dims"], synth.DTYPE_CODE[dtype])
