@@ -264,13 +264,20 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
     const int wmn = wave % (WM * WN), wm = wmn / WN, wn = wmn % WN;
     const int m0 = bid.m * BM;
 
-    // zeros everywhere first: the patch positions that lie outside the image are never written again
-    {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < NSTG * STAGE / 8; i += NT) ((u32x4 *)smem)[i] = zero;
-    }
     Fill fill;
     plan_fill(fill, cb, m0, tid);
+    Regs regs;
+#if FLAG
+    load_slab(regs, fill, A, B, 0);
+#endif
+    // (pipelined members: while the first slab is on its way) zeros in the patch part of every stage: the patch positions
+    // that lie outside the image are never written again
+    {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int st = 0; st < NSTG; ++st)
+            for (int i = tid; i < P_STAGE / 8; i += NT) ((u32x4 *)(smem + st * STAGE))[i] = zero;
+    }
 
     // this lane's place in the fragments: its row of the A part, and per column of atoms its output pixel's
     // patch pixel under tap (0, 0) (columns past the wave tile read the tile's last pixel and are not stored)
@@ -292,13 +299,11 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 #pragma unroll
             for (int r = 0; r < NACC; ++r) acc[i][j][r] = 0.f;
 
-    Regs regs;
 #if FLAG
     // Two stages: while slab s is multiplied the loads of slab s+1 are in flight; they are written to the other stage
     // afterwards (one barrier per slab).  Branch-free body (the loads must not sink below the MFMAs): past the last slab
     // the last one is loaded and stored once more, into the stage nobody reads any longer.  (Loading two slabs ahead
     // into a second register set was measured: no faster, and the registers cost members their place on this template.)
-    load_slab(regs, fill, A, B, 0);
     __syncthreads();                                   // the zeros are in place
     store_slab(regs, fill, (u32 *)smem);
     __syncthreads();

@@ -287,7 +287,7 @@ FOLDED = [
     # members that ask for what the template has not, and the division of the same workgroup tile it runs instead
     ("slabs of 8 channels -> 16", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 1, 1, 32, 2, 1, 1, 3, 1, 2, 1, 4, 4, 8, 1, 2, 0], dict(CS=16, KSTEPS=2)),
     ("4 waves of 8 output channels -> one of 32", (2, 32, 6, 8, 32, 3, 3, 1, 1), [1, 2, 1, 4, 2, 4, 2, 1, 1, 3, 1, 2, 1, 4, 2, 16, 1, 2, 0], dict(WM=1, TM=32)),
-    ("8 x 4 x 2 waves -> 8 x 2 waves (kwaves 1, pixel waves merged)", (2, 32, 6, 8, 128, 3, 3, 1, 1), [2, 1, 1, 8, 1, 16, 1, 2, 1, 3, 1, 2, 1, 4, 1, 32, 1, 2, 1], dict(WM=8, WN=2, TN=24, KW=1)),
+    ("8 x 4 x 2 waves -> 8 x 1 x 2 waves (pixel waves merged)", (2, 32, 6, 8, 128, 3, 3, 1, 1), [2, 1, 1, 8, 1, 16, 1, 2, 1, 3, 1, 2, 1, 4, 1, 32, 1, 2, 1], dict(WM=8, WN=1, TN=48, KW=2)),
 ]
 
 
