@@ -295,7 +295,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                 int64_t prow = 0, pimage = 0, lds_p = 0;
                 for (int padded = 1; padded >= 0; --padded) {
                     patch_pitches(op, BH, BW, padded == 1, prow, pimage);
-                    lds_p = st * ((nb2 * pimage + taps * wm * tm) * (cs + 8) + 64) * 2;   // + the dump words of a stage
+                    lds_p = st * (nb2 * pimage * (cs + 8) + taps * wm * tm * cs + 64) * 2;   // patch (padded pixels), kernel tensor's part, dump words
                     if (lds_p <= kMaxLds) break;
                 }
                 // the waves along Cout are merged, a prime at a time, until an atom fits the wave tile
@@ -535,7 +535,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
     else if (path == 4) lds = nstage * ((op.trans_a ? BK * (BM + 4) : BM * (BK + 4)) + BK * (BN + 4)) * 4;
     else if (path == 3) lds = nstage * (anr + (b_kmajor ? bnr : BN)) * BK * 2;
     else if (path == 5)   // the stages, or (more than one wave per tile) one atom of every wave if that is more
-        lds = std::max<int64_t>(nstage * ((nb2 * patch_image + op.hk * op.wk * BM) * (patch_cs + 8) + 64) * 2,
+        lds = std::max<int64_t>(nstage * (nb2 * patch_image * (patch_cs + 8) + op.hk * op.wk * BM * patch_cs + 64) * 2,
                                 patch_kw > 1 ? nwr * (patch_atom == 32 ? 4 : 1) * 1024 : 0);
     else if (stage_lds) lds = nstage * (BM + BN) * (BKP + kPad) * 2 + (ragged ? 16 * (BKP + kPad) * 2 : 0);   // overhang rows stay inside the allocation
 

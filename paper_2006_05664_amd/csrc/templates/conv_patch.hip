@@ -15,11 +15,11 @@
 //     staged pixel serves all the taps that touch it.  Positions outside the image (padding) are zeros: both
 //     stages are cleared once, and the fill only ever writes positions inside the image, whose place in the
 //     patch is the same for every slab.
-//   * the kernel tensor's part, A[tap][BM][CS (+8)], so that an A fragment is 16 contiguous bytes too.
+//   * the kernel tensor's part, A[tap][BM][CS] (16-byte chunks permuted by row), so that an A fragment is 16 contiguous bytes too.
 // Both parts are transposed on the way in, two channels at a time: a thread loads 4-byte pairs of pixels of two
 // channels (rows of the NCHW image are contiguous in x; with WIN even, aligned pairs never straddle a row), or the
 // 2*HK*WK contiguous values of two input channels of one output channel, swaps halves in registers and stores
-// 4-byte words (one pixel or tap, its two channels).  The padding of 8 elements per row makes 16 consecutive rows
+// 4-byte words (one pixel or tap, its two channels).  The padding of 8 elements per patch pixel makes 16 consecutive pixels
 // start in 16 different groups of 4 banks, which is what conflict-free 16-byte reads need.
 //
 // KW > 1: KW waves share every wave tile and split the reduction: of the HK*WK*(CS/KA) MFMA steps of a slab, wave k of the
@@ -60,9 +60,19 @@ constexpr int PH = (BH - 1) * STRIDE + HK, PW = (BW - 1) * STRIDE + WK;
 // n modulo 16 and any 16 lanes served together start in 16 different groups of banks (PITCH / 8 is odd).
 static_assert(PWP >= PW && IPIX >= PH * PWP, "patch pitches too small");
 constexpr int NPIX = NB2 * IPIX;
-constexpr int PITCH = CS + 8;                                 // elements per patch pixel / per kernel-tensor row
+constexpr int PITCH = CS + 8;                                 // elements per patch pixel
+// The kernel tensor's part has no padding: a row is CS elements = NCH 16-byte chunks, and chunk c of row r is stored at
+// chunk c ^ a_swz(r).  16 consecutive rows read the same chunk c together; without the permutation rows 16 / NCH apart
+// would start in the same group of banks, with it they take NCH different chunks.  (The patch cannot do the same: which
+// rows are read together depends on the tap, while a stored pixel has one place.)
+constexpr int NCH = CS / 8;
+// (An exclusive-or stays inside the row only for a power of two of chunks: other slab lengths are stored unpermuted.)
+__device__ __forceinline__ int a_swz(int row)
+{
+    return (NCH & (NCH - 1)) != 0 ? 0 : NCH <= 16 ? (row * NCH / 16) % NCH : row % 16;
+}
 constexpr int DUMP = 64;                                      // elements at the end of a stage that take the stores of pixels outside the patch
-constexpr int P_STAGE = NPIX * PITCH, A_STAGE = T * BM * PITCH, STAGE = P_STAGE + A_STAGE + DUMP;   // elements
+constexpr int P_STAGE = NPIX * PITCH, A_STAGE = T * BM * CS, STAGE = P_STAGE + A_STAGE + DUMP;   // elements
 constexpr int MI = TM / ATOM, NI = (TN + ATOM - 1) / ATOM;    // atoms per wave tile (the last column of atoms may hang over)
 constexpr int KK = CS / KA;                                   // MFMA steps per tap
 #ifndef KW
@@ -129,7 +139,7 @@ __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, i
         const int cp = q % CP, m = q / CP;
         const bool on = A_TASKS % NT == 0 || q < A_TASKS;
         f.ag[i] = on ? 2u * (u32)((m0 + m) * K + 2 * cp * T) : 0u;
-        f.ad[i] = on ? (u32)(m * PITCH / 2 + cp) : ~0u;
+        f.ad[i] = on ? (u32)(m * (CS / 2) + (((cp >> 2) ^ a_swz(m)) << 2) + (cp & 3)) : ~0u;   // BM is a multiple of 16: the tap does not change the permutation
     }
 }
 
@@ -172,19 +182,24 @@ __device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u32 *S)
             const u32 lo = r.a[i][t / 2], hi = r.a[i][(T + t) / 2];
             const u32 l16 = (t % 2) ? (lo >> 16) : (lo & 0xffffu);
             const u32 h16 = ((T + t) % 2) ? (hi & 0xffff0000u) : (hi << 16);
-            SA[f.ad[i] + t * (BM * PITCH / 2)] = l16 | h16;
+            SA[f.ad[i] + t * (BM * CS / 2)] = l16 | h16;
         }
     }
 }
 
+// a lane's place in the A part: its row of the wave tile's first atom (element offset), which 16-byte chunk of a K step it
+// supplies, and its row's chunk permutation
+struct ALane { int row, chunk, perm; };
+
 // fragments of step (tap, kk): MI rows of atoms from the A part, NI columns of atoms from the patch
 __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], const u16 *As, const u16 *P,
-                                           int a_lane, const int (&b_lane)[NI], int tap, int kk)
+                                           const ALane &al, const int (&b_lane)[NI], int tap, int kk)
 {
     const int r = tap / WK, s = tap % WK;
+    const int a_row = al.row, a_chunk = al.chunk, a_perm = al.perm;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
-        af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA));
+        af[i] = __builtin_bit_cast(frag_t, *(const u32x4 *)(As + a_row + (((kk * (KA / 8) + a_chunk) ^ a_perm) << 3) + (tap * BM + i * ATOM) * CS));
 #pragma unroll
     for (int j = 0; j < NI; ++j)
         bf[j] = __builtin_bit_cast(frag_t, *(const u32x4 *)(P + b_lane[j] + (r * PWP + s) * PITCH + kk * KA));
@@ -198,7 +213,7 @@ __device__ __forceinline__ void load_frags(frag_t (&af)[MI], frag_t (&bf)[NI], c
 #define FRAG_AHEAD ((TM / ATOM) + (TN + ATOM - 1) / ATOM <= 3 ? 2 : 1)
 #endif
 template <int WI>
-__device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
+__device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, const ALane &al, const int (&b_lane)[NI])
 {
     constexpr int NS = (STEPS - WI + KW - 1) / KW;
     constexpr int RING = FRAG_AHEAD + 1;
@@ -206,12 +221,12 @@ __device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *A
 #pragma unroll
     for (int u = 0; u < FRAG_AHEAD && u < NS; ++u) {
         const int t = WI + u * KW;
-        load_frags(af[u], bf[u], As, P, a_lane, b_lane, t / KK, t % KK);
+        load_frags(af[u], bf[u], As, P, al, b_lane, t / KK, t % KK);
     }
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
         const int t = WI + (u + FRAG_AHEAD) * KW;
-        if (u + FRAG_AHEAD < NS) load_frags(af[(u + FRAG_AHEAD) % RING], bf[(u + FRAG_AHEAD) % RING], As, P, a_lane, b_lane, t / KK, t % KK);
+        if (u + FRAG_AHEAD < NS) load_frags(af[(u + FRAG_AHEAD) % RING], bf[(u + FRAG_AHEAD) % RING], As, P, al, b_lane, t / KK, t % KK);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -220,28 +235,28 @@ __device__ __forceinline__ void compute_steps(acc_t (&acc)[MI][NI], const u16 *A
     }
 }
 template <int WI>
-__device__ __forceinline__ void compute_for_wave(int wk, acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI])
+__device__ __forceinline__ void compute_for_wave(int wk, acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, const ALane &al, const int (&b_lane)[NI])
 {
     if constexpr (WI + 1 < KW) {
-        if (wk == WI) compute_steps<WI>(acc, As, P, a_lane, b_lane);
-        else compute_for_wave<WI + 1>(wk, acc, As, P, a_lane, b_lane);
+        if (wk == WI) compute_steps<WI>(acc, As, P, al, b_lane);
+        else compute_for_wave<WI + 1>(wk, acc, As, P, al, b_lane);
     } else {
-        compute_steps<WI>(acc, As, P, a_lane, b_lane);
+        compute_steps<WI>(acc, As, P, al, b_lane);
     }
 }
 
 // wk: which of the KW waves of its tile this wave is (wave-uniform)
-__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, int a_lane, const int (&b_lane)[NI], int wk)
+__device__ __forceinline__ void compute_slab(acc_t (&acc)[MI][NI], const u16 *As, const u16 *P, const ALane &al, const int (&b_lane)[NI], int wk)
 {
     if constexpr (STEPS * (MI * NI + MI + NI) <= 512) {
-        compute_for_wave<0>(wk, acc, As, P, a_lane, b_lane);
+        compute_for_wave<0>(wk, acc, As, P, al, b_lane);
     } else {
         // long slabs (many taps): the loop over the steps stays a loop
 #pragma unroll 1
         for (int t = wk; t < STEPS; t += KW) {
             const int tap = t / KK, kk = t % KK;
             frag_t af[MI], bf[NI];
-            load_frags(af, bf, As, P, a_lane, b_lane, tap, kk);
+            load_frags(af, bf, As, P, al, b_lane, tap, kk);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -281,7 +296,8 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
 
     // this lane's place in the fragments: its row of the A part, and per column of atoms its output pixel's
     // patch pixel under tap (0, 0) (columns past the wave tile read the tile's last pixel and are not stored)
-    const int a_lane = (wm * TM + lrow) * PITCH + lk;
+    // (whole atoms of 16 or 32 rows lie between a lane's rows: they all have this row's permutation)
+    const ALane al = {(wm * TM + lrow) * CS, lane / ATOM, a_swz(lrow)};
     int b_lane[NI];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
@@ -312,7 +328,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         u16 *cur = smem + (s & 1) * STAGE, *nxt = smem + (NSTG == 2 ? (s + 1) & 1 : 0) * STAGE;
         load_slab(regs, fill, A, B, s + 1 < KSTEPS ? s + 1 : KSTEPS - 1);
         __builtin_amdgcn_sched_barrier(0);             // all loads are issued before the first MFMA ...
-        compute_slab(acc, cur + P_STAGE, cur, a_lane, b_lane, wk);
+        compute_slab(acc, cur + P_STAGE, cur, al, b_lane, wk);
         __builtin_amdgcn_sched_barrier(0);             // ... and the stores follow the last
         if (NSTG == 2) store_slab(regs, fill, (u32 *)nxt);
         __syncthreads();
@@ -324,7 +340,7 @@ void KERNEL_NAME(const u16 *__restrict__ A, const u16 *__restrict__ B, float *__
         __syncthreads();                               // slab s-1 has been multiplied (first pass: the zeros are in place)
         store_slab(regs, fill, (u32 *)smem);
         __syncthreads();
-        compute_slab(acc, smem + P_STAGE, smem, a_lane, b_lane, wk);
+        compute_slab(acc, smem + P_STAGE, smem, al, b_lane, wk);
     }
 #endif
 

@@ -48,7 +48,11 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     assert PWP >= PW and IPIX >= PH * PWP
     NPIX = NB2 * IPIX
     PITCH, DUMP = CS + 8, 64
-    P_STAGE, A_STAGE = NPIX * PITCH, T * BM * PITCH
+    P_STAGE, A_STAGE = NPIX * PITCH, T * BM * CS
+    NCH = CS // 8
+
+    def a_swz(row):    # chunk permutation of a row of the kernel tensor's part
+        return 0 * row if NCH & (NCH - 1) else ((row * NCH // 16) % NCH if NCH <= 16 else row % 16)
     STAGE = P_STAGE + A_STAGE + DUMP
     KA = 16 if ATOM == 32 else 32
     NACC = 16 if ATOM == 32 else 4
@@ -102,7 +106,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
             q = tid + i * NT
             cp, m = q % CP, q // CP
             on = q < A_TASKS
-            ag.append(np.where(on, 2 * ((m0 + m) * K + 2 * cp * T), 0)); ad.append(m * PITCH // 2 + cp); aon.append(on)
+            ag.append(np.where(on, 2 * ((m0 + m) * K + 2 * cp * T), 0)); ad.append(m * (CS // 2) + (((cp >> 2) ^ a_swz(m)) << 2) + (cp & 3)); aon.append(on)
         # ---- bounds and alignment of every global load, for every slab
         for s in range(KSTEPS):
             for i in range(NPT):
@@ -128,7 +132,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         asrc = np.full(STAGE, -1, dtype=np.int64)
         for i in range(NAT):
             for t in range(T):
-                dd = P_STAGE + 2 * (ad[i][aon[i]] + t * (BM * PITCH // 2))
+                dd = P_STAGE + 2 * (ad[i][aon[i]] + t * (BM * CS // 2))
                 assert (dd >= P_STAGE).all() and (dd + 1 < P_STAGE + A_STAGE).all(), ("kernel-tensor store", bx, by, i, t)
                 for ch in range(2):                            # value t of the run of 2*T, value T + t
                     np.add.at(hits, dd + ch, 1)
@@ -148,9 +152,11 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                     assert (hits[base + CS:base + PITCH] == 0).all()
         for tap in range(T):
             for m in range(BM):
-                base = P_STAGE + (tap * BM + m) * PITCH
-                want = (m0 + m) * K + np.arange(CS) * T + tap
-                assert (asrc[base:base + CS] == want).all(), ("kernel-tensor value", bx, by, tap, m)
+                base = P_STAGE + (tap * BM + m) * CS
+                ch = np.arange(CS)
+                want = (m0 + m) * K + ch * T + tap
+                where = base + (((ch >> 3) ^ int(a_swz(m))) << 3) + (ch & 7)     # channel ch sits in chunk (ch / 8) ^ a_swz(m)
+                assert (asrc[where] == want).all(), ("kernel-tensor value", bx, by, tap, m)
         # ---- fragments: every lane's reads, and (with operands) the sum they form.  Wave = (wk, wm, wn): the KW waves of a
         # tile take the MFMA steps t = tap * KK + kk with t % KW == wk; their partial sums are added in the epilogue.
         lane = np.arange(64)
@@ -158,7 +164,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         STEPS = T * KK
         for wmn in range(WM * WN):
             wm, wn = wmn // WN, wmn % WN
-            a_lane = (wm * TM + lrow) * PITCH + lk
+            a_row, a_chunk, a_perm = (wm * TM + lrow) * CS, lane // ATOM, a_swz(lrow)
             for j in range(NI):
                 ct = j * ATOM + lrow
                 cn = wn * TN + np.minimum(ct, TN - 1)
@@ -172,7 +178,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                             steps_done[t] += 1
                             tap, kk = t // KK, t % KK
                             r, sx = tap // WK, tap % WK
-                            ao = P_STAGE + a_lane + (tap * BM + i * ATOM) * PITCH + kk * KA
+                            ao = P_STAGE + a_row + (((kk * (KA // 8) + a_chunk) ^ a_perm) << 3) + (tap * BM + i * ATOM) * CS
                             bo = b_lane + (r * PWP + sx) * PITCH + kk * KA
                             assert (ao % 8 == 0).all() and (bo % 8 == 0).all()
                             assert (ao >= P_STAGE).all() and (ao + 8 <= P_STAGE + A_STAGE).all(), "A fragment outside its part"
@@ -246,6 +252,8 @@ SMALL = [
     ("5x5 pad 2, boxes of 3 columns", (1, 16, 6, 6, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 1, 1, 1, 6, 2, 1, 1, 3, 1, 16, 1, 2, 0]),
     ("3x3 stride 2 pad 1", (1, 32, 8, 8, 32, 3, 3, 2, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
     ("1x1", (2, 32, 4, 4, 64, 1, 1, 1, 0), [2, 1, 1, 2, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 0]),
+    ("slabs of 48 channels (6 chunks per row: stored unpermuted)", (1, 48, 6, 6, 32, 3, 3, 1, 1), [1, 1, 1, 1, 1, 32, 1, 2, 1, 3, 1, 1, 1, 6, 1, 48, 1, 2, 0]),
+    ("slabs of 64 channels (8 chunks per row)", (1, 64, 4, 8, 32, 3, 3, 1, 1), [1, 1, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 8, 1, 64, 1, 2, 1]),
     ("odd width: 3x3 pad 1 on 5 x 7", (2, 32, 5, 7, 32, 3, 3, 1, 1), [2, 1, 1, 1, 1, 32, 1, 1, 1, 5, 1, 1, 1, 7, 2, 16, 1, 2, 0]),
     ("odd width: 5x5 pad 2 on 9 x 9, boxes of 3 rows", (1, 16, 9, 9, 32, 5, 5, 1, 2), [1, 1, 1, 1, 1, 32, 3, 1, 1, 3, 1, 1, 1, 9, 1, 16, 1, 2, 0]),
     ("odd width: stride 2 on 7 x 7, two waves per tile", (2, 32, 7, 7, 32, 3, 3, 2, 1), [1, 2, 1, 1, 1, 32, 1, 1, 1, 4, 1, 1, 1, 4, 1, 32, 1, 2, 1]),
