@@ -280,14 +280,22 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             // rounded up to whole atoms while that at most doubles the work; the atom that wastes less is taken.
             // kwaves: that many waves share every wave tile and split the MFMA steps of a slab (taps x channel groups).
             // A member that asks for what the template has not is folded rather than sent away (same workgroup tile,
-            // another division of it among the waves): slabs of fewer than 16 channels are merged; wave tiles of fewer
-            // than 16 output channels are merged along Cout; with more than 16 waves kwaves is halved, then the waves
-            // along the pixels are merged a prime at a time (their tiles grow).
+            // another division of it among the waves): slabs of fewer than 16 channels are merged, slabs too long for the
+            // LDS halved; wave tiles of fewer than 16 output channels are merged along Cout; with more than 16 waves kwaves
+            // is halved, then the waves along the pixels are merged a prime at a time (their tiles grow).
             if (c[17] == 2 && op.dtype != OPEVO_F32 && op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
                 auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
                 auto prime = [](int64_t n) { for (int64_t q = 2; q * q <= n; ++q) if (n % q == 0) return q; return n; };
                 int64_t cs = c[15], tm = TM, wm = WM;
                 while (cs % 16 != 0 && cs < op.cin) cs *= prime(op.cin / cs);
+                // ... and slabs too long for the LDS (the kernel tensor's part holds all taps of a slab) are halved while they
+                // stay whole 16 channels
+                {
+                    int64_t prow0 = 0, pimage0 = 0;
+                    patch_pitches(op, BH, BW, false, prow0, pimage0);
+                    auto stage_bytes = [&](int64_t v) { return (nb2 * pimage0 * (v + 8) + taps * WM * TM * v + 64) * 2; };
+                    while (cs % 32 == 0 && stage_bytes(cs) * ((flagv && op.cin / cs > 1) ? 2 : 1) > kMaxLds) cs /= 2;
+                }
                 const int64_t slabs = op.cin / cs;
                 const int64_t ph = (BH - 1) * op.stride + op.hk, pw = (BW - 1) * op.stride + op.wk;
                 const int st = (flagv && slabs > 1) ? 2 : 1;
@@ -378,6 +386,10 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
         const int stages = (flagv && ksteps > 1) ? 2 : 1;
         auto lds_need = [&]() { return (BM + BN) * std::max<int64_t>((BK + kPad) * elem * stages, BK * 4); };
         const int64_t lds_cap = kMaxLds - 16;   // room for the deadline flag word of folded members
+        // (TILE4L's gather members walk (ci, r, s) in slabs of whole channels with all their taps, rarely a multiple of 64:
+        // there a slab too long is divided by its smallest prime factor; the gather pads any slab to the MFMA step)
+        if (variant == OPEVO_TILE4L && layout != 1)
+            while (lds_need() > lds_cap && BK > 32) { const int64_t q = smallest_prime(BK); BK /= q; ksteps *= q; }
         while (lds_need() > lds_cap && BK % 64 == 0 && !tap_box) { BK /= 2; ksteps *= 2; }
         // (the scalar template: 1024 threads have 128 registers per lane each; 16 outputs per thread fit with its unrolled loop)
         const int64_t out_cap = BM * BN > int64_t(kMaxThreads) * kMaxAcc ? int64_t(kMaxThreads) * 16 : INT64_MAX;

@@ -535,10 +535,11 @@ def test_conv_patch_space_and_its_decoding():
         assert want in d.split(), (want, d)
     # padded patch pixels, unpadded kernel-tensor rows, dump words; or, if more, one 32x32 atom of each of the 14 waves for the final sum
     assert plan.lds_bytes == max((484 * 40 + 9 * 32 * 32 + 64) * 2, 14 * 4 * 1024)
-    # the other two layouts of the same member: the gather walks (ci, r, s) in slabs of 32 * 9, the channels-last
-    # member (r, s, ci) in slabs of 32, with its pre-pass; kwaves is inert there
+    # the other two layouts of the same member: the gather walks (ci, r, s) in slabs of 32 * 9, too long for the LDS beside
+    # a tile of 32 x 196 and so halved to 16 * 9; the channels-last member (r, s, ci) in slabs of 32, with its pre-pass;
+    # kwaves is inert there
     d0 = P.opevo_kernel_defines(op, V, cfg[:17] + [0, 1])
-    assert not d0.startswith("conv_patch:") and "-DBK=288" in d0.split() and "-DKSTEPS=8" in d0.split() and "CONV_NHWC" not in d0 and "-DKW" not in d0
+    assert not d0.startswith("conv_patch:") and "-DBK=144" in d0.split() and "-DKSTEPS=16" in d0.split() and "CONV_NHWC" not in d0 and "-DKW" not in d0
     d1 = P.opevo_kernel_defines(op, V, cfg[:17] + [1, 1])
     assert "-DBK=32" in d1.split() and "-DKSTEPS=72" in d1.split() and "-DCONV_NHWC=1" in d1.split()
     with pytest.raises(P.OpevoError):                          # 8 * 16 != 256
