@@ -90,9 +90,14 @@ static_assert(NSTG == (FLAG && KSTEPS > 1 ? 2 : 1), "a pipelined member with mor
 // channel pairs are fastest, then the pairs of pixels along the row, the rows and the images, then the remaining
 // channel pairs: 64 lanes load from 4 (or 8) channels, 64 contiguous bytes each, and store 16 pixels x 4 words,
 // which fall into different banks but for the stride of two pixels.
-// An image of odd width has no aligned pairs (a row starts at any 2-byte offset): there a task is two channels x
-// one pixel, two 2-byte loads and one 4-byte store.
-constexpr bool PAIRED = WIN % 2 == 0;
+// An image of odd width has its rows at any 2-byte offset: the same pairs (even x, odd x) are loaded with 4-byte
+// loads that are only 2-byte aligned.  The last pixel of a row has no partner there; its load starts one pixel
+// to the left, so that no load reaches beyond the row (the last row ends the tensor), and the words are shifted
+// down by one pixel before the transposition (bit 0 of the task's byte offset says so).
+// An image one pixel wide: a task is two channels x one pixel, two 2-byte loads and one 4-byte store.
+constexpr bool ALIGNED = WIN % 2 == 0;
+constexpr bool PAIRED = ALIGNED || WIN >= 3;
+typedef u32 __attribute__((aligned(2))) u32_a2;
 constexpr int CP = CS / 2;                                    // channel pairs of a slab
 constexpr int NPAIR = PAIRED ? PW / 2 + 1 : PW;               // aligned pairs that cover PW columns from either parity (odd width: pixels)
 constexpr int PAIRS = NPAIR * PH * NB2;
@@ -127,9 +132,10 @@ __device__ __forceinline__ void plan_fill(Fill &f, const ColBlock &cb, int m0, i
         const int jp = pr % NPAIR, py = (pr / NPAIR) % PH, b = pr / (NPAIR * PH);
         const int y = yin0 + py, x = PAIRED ? xs + 2 * jp : xin0 + jp, px = x - xin0;   // px: patch column of the task's first pixel (-1 .. PW)
         const bool in = (P_TASKS % NT == 0 || q < P_TASKS) && y >= 0 && y < HIN && x >= 0 && x < WIN;
-        const bool v0 = in && px >= 0 && px < PW, v1 = PAIRED && in && px + 1 >= 0 && px + 1 < PW;
+        const bool v0 = in && px >= 0 && px < PW, v1 = PAIRED && in && px + 1 >= 0 && px + 1 < PW && (ALIGNED || x + 1 < WIN);
+        const int left = (PAIRED && !ALIGNED && x == WIN - 1) ? 1 : 0;
         const int d0 = ((b * IPIX + py * PWP + px) * PITCH) / 2 + cp, dump = (STAGE - DUMP) / 2 + (tid & 31);
-        f.pg[i] = (v0 || v1) ? 2u * (u32)((((cb.nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x) : 0u;
+        f.pg[i] = (v0 || v1) ? (2u * (u32)((((cb.nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x - left) | (u32)left) : 0u;
         f.pd0[i] = (u32)(v0 ? d0 : dump);
         f.pd1[i] = (u32)(v1 ? d0 + PITCH / 2 : dump);
     }
@@ -150,9 +156,13 @@ __device__ __forceinline__ void load_slab(Regs &r, const Fill &f, const u16 *__r
     const char *As = (const char *)(A + (long)s * CS * T);
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {   // the second load is the next channel (offset 0 for an idle task: still inside the tensor)
-        if constexpr (PAIRED) {
+        if constexpr (ALIGNED) {
             r.p[i][0] = *(const u32 *)(Bs + f.pg[i]);
             r.p[i][1] = *(const u32 *)(Bs + f.pg[i] + 2 * HIN * WIN);
+        } else if constexpr (PAIRED) {
+            const u32 o = f.pg[i] & ~1u;
+            r.p[i][0] = *(const u32_a2 *)(Bs + o);
+            r.p[i][1] = *(const u32_a2 *)(Bs + o + 2 * HIN * WIN);
         } else {
             r.p[i][0] = *(const u16 *)(Bs + f.pg[i]);
             r.p[i][1] = *(const u16 *)(Bs + f.pg[i] + 2 * HIN * WIN);
@@ -169,8 +179,14 @@ __device__ __forceinline__ void store_slab(const Regs &r, const Fill &f, u32 *S)
 {
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
-        S[f.pd0[i]] = (r.p[i][0] & 0xffffu) | (r.p[i][1] << 16);         // first pixel: its two channels
-        if constexpr (PAIRED) S[f.pd1[i]] = (r.p[i][0] >> 16) | (r.p[i][1] & 0xffff0000u);     // second pixel
+        u32 p0 = r.p[i][0], p1 = r.p[i][1];
+        if constexpr (PAIRED && !ALIGNED) {
+            const u32 sh = (f.pg[i] & 1u) << 4;                   // a pair loaded one pixel to the left: the pixel wanted is the upper one
+            p0 >>= sh;
+            p1 >>= sh;
+        }
+        S[f.pd0[i]] = (p0 & 0xffffu) | (p1 << 16);                // first pixel: its two channels
+        if constexpr (PAIRED) S[f.pd1[i]] = (p0 >> 16) | (p1 & 0xffff0000u);      // second pixel
     }
     u32 *SA = S + P_STAGE / 2;
 #pragma unroll

@@ -58,7 +58,8 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
     NACC = 16 if ATOM == 32 else 4
     MI, NI, KK = TM // ATOM, (TN + ATOM - 1) // ATOM, CS // KA
     assert TM % ATOM == 0 and CS % KA == 0 and BK == CS * T and KSTEPS * CS == CIN and K == CIN * T
-    PAIRED = WIN % 2 == 0
+    ALIGNED = WIN % 2 == 0
+    PAIRED = ALIGNED or WIN >= 3     # odd widths: the same pairs, loads 2-byte aligned, a row's last pixel loaded from one pixel to the left
     assert NSTG * STAGE * 2 <= LDS_BYTES == plan.lds_bytes <= 160 * 1024
     assert NT == 64 * WM * WN * KW == plan.block <= 1024 and BM == WM * TM and WN * TN == NB2 * BH * BW
     assert 1 <= KW <= T * (CS // (16 if ATOM == 32 else 32))
@@ -96,8 +97,9 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
             px = x - xin0
             inside = (q < P_TASKS) & (y >= 0) & (y < HIN) & (x >= 0) & (x < WIN)
             v0 = inside & (px >= 0) & (px < PW)
-            v1 = inside & (px + 1 >= 0) & (px + 1 < PW) & PAIRED
-            goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x), 0)
+            v1 = inside & (px + 1 >= 0) & (px + 1 < PW) & PAIRED & (ALIGNED | (x + 1 < WIN))
+            left = np.where((x == WIN - 1) & PAIRED & (not ALIGNED), 1, 0)
+            goff = np.where(v0 | v1, 2 * ((((nb0 + b) * CIN + 2 * cp) * HIN + y) * WIN + x - left) | left, 0)
             d0 = ((b * IPIX + py * PWP + px) * PITCH) // 2 + cp      # 4-byte words
             dump = (STAGE - DUMP) // 2 + (tid & 31)
             pg.append(goff); pd0.append(np.where(v0, d0, dump)); pd1.append(np.where(v1, d0 + PITCH // 2, dump))
@@ -111,9 +113,12 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
         for s in range(KSTEPS):
             for i in range(NPT):
                 for ch in range(2):
-                    o = 2 * s * CS * HIN * WIN + pg[i] + ch * 2 * HIN * WIN
-                    width = 4 if PAIRED else 2
-                    assert (o >= 0).all() and (o + width <= img_bytes).all() and (o % width == 0).all(), ("image load", bx, by, s, i)
+                    o = 2 * s * CS * HIN * WIN + (pg[i] & ~1) + ch * 2 * HIN * WIN
+                    width, align = (4 if PAIRED else 2), (4 if ALIGNED else 2)
+                    assert ALIGNED or PAIRED or (pg[i] & 1 == 0).all()
+                    assert (o >= 0).all() and (o + width <= img_bytes).all() and (o % align == 0).all(), ("image load", bx, by, s, i)
+                    # a 4-byte load stays inside its row of the image: a pair never reaches into the next row (or past the tensor)
+                    assert not PAIRED or ((o // 2) % WIN + 1 < WIN).all(), ("pair across a row end", bx, by, s, i)
             for i in range(NAT):
                 for t in range(T):
                     o = 2 * s * CS * T + ag[i] + 4 * t
@@ -128,7 +133,7 @@ def emulate(dims, cfg, img=None, ker=None, blocks=None):
                 assert (2 * dst[real] + 1 < P_STAGE).all()
                 for ch in range(2):
                     np.add.at(hits, 2 * dst[real] + ch, 1)
-                    src[2 * dst[real] + ch] = pg[i][real] // 2 + ch * HIN * WIN + e
+                    src[2 * dst[real] + ch] = (pg[i][real] & ~1) // 2 + ch * HIN * WIN + e + (pg[i][real] & 1)
         asrc = np.full(STAGE, -1, dtype=np.int64)
         for i in range(NAT):
             for t in range(T):
