@@ -318,7 +318,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                     };
                     const int at = fits(32) && (!fits(16) || up(tn, 32) == up(tn, 16)) ? 32 : fits(16) ? 16 : 0;
                     if (!at || kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // no atom fits; more waves than steps
-                    // the fill: per thread, tasks of two channels x two pixels (one pixel in an image of odd width) and of two channels x all taps (kernel tensor)
+                    // the fill: per thread, tasks of two channels x two pixels (one pixel in an image one pixel wide) and of two channels x all taps (kernel tensor)
                     const int64_t fill_p = (cs / 2 * (op.win >= 2 ? pw / 2 + 1 : pw) * ph * nb2 + nt - 1) / nt, fill_a = (wm * tm * cs / 2 + nt - 1) / nt;
                     // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
                     // atom row and column; three sets for small wave tiles), the fill (3 + 2 per image task, 2 + taps per

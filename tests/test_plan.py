@@ -548,7 +548,7 @@ def test_conv_patch_space_and_its_decoding():
         P.opevo_kernel_plan(op, V, cfg[:17] + [3, 1])
     # 16x16x32 atoms where they pad the pixel side less (98 -> 112 instead of 128) and the slab has whole 32 channels
     assert "-DATOM=16" in P.opevo_kernel_defines(op, V, [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]).split()
-    # an image of odd width is filled pixel by pixel: same template
+    # an image of odd width is filled by pairs of pixels at 2-byte alignment: same template
     c27 = _op((P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2)), P.OPEVO_BF16)
     assert P.opevo_kernel_plan(c27, V, [4, 1, 1, 2, 1, 32, 3, 3, 1, 3, 1, 1, 1, 27, 4, 16, 0, 2, 0]).path == 5
     # three input channels (the paper's C1): no slab of 16 channels, no patch member
