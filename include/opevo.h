@@ -265,9 +265,13 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         workgroup stages the input pixels under its box of output pixels once, channels fastest, straight from
  *         the NCHW image, and the slab's part of the OIHW kernel tensor re-ordered tap by tap; every tap then
  *         reads its operands from that patch at a fixed offset from the output pixel.  One launch, no pre-pass,
- *         each staged pixel re-used by all taps that touch it.  16-bit inputs, an even image width, slabs of
- *         whole 16 channels (32 on 16x16x32 atoms), at most 16 waves, and patch + kernel-tensor part within the
- *         LDS; elsewhere layout = 2 runs the layout = 0 kernel.  Same sum in another order.
+ *         each staged pixel re-used by all taps that touch it.  16-bit inputs, slabs of whole 16 channels (32 on
+ *         16x16x32 atoms), at most 16 waves, and patch + kernel-tensor part within the LDS.  A member that asks
+ *         for something else keeps its workgroup tile and is divided among the waves another way: shorter slabs
+ *         are merged and slabs too long for the LDS halved, wave tiles of fewer than 16 output channels merged
+ *         along Cout, waves beyond 16 merged along the pixels.  Where that does not help (fp32 inputs, fewer than
+ *         16 input channels, a patch too large for the LDS) layout = 2 runs the layout = 0 kernel.  Same sum in
+ *         another order.
  *         kwaves (DISCRETE, layout = 2 only, inert elsewhere): that many waves share every wave tile and deal the
  *         slab's MFMA steps (taps x groups of channels) round-robin among themselves; their partial sums are added
  *         through LDS after the last slab, in the order of the waves (deterministic).  The workgroup then has

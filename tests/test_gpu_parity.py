@@ -633,7 +633,7 @@ PAPER_SHAPES = [
     # the same operator in the space with the split reduction and channels-last operands: direct-to-LDS members
     ("C2 channels last", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (3,),
      [("6 waves of 32 x 243 -> 256, slabs of 32", [512, 1, 3, 2, 1, 32, 1, 3, 9, 1, 1, 1, 27, 1, 1, 50, 32, 1, 1])], "TILE4C"),
-    # the same operator with an LDS-resident image patch (odd image width: the fill loads pixel by pixel; 25 taps read each staged pixel)
+    # the same operator with an LDS-resident image patch (odd image width: the fill loads pairs of pixels at 2-byte alignment; 25 taps read each staged pixel)
     ("C2 LDS-resident patch", "conv2d", (512, 64, 27, 27, 192, 5, 5, 1, 2), 1244, 2, (5,),
      [("64 channels x 9 rows of 27 -> 256 pixels, 2 channel waves x 2 waves per tile, single stage", [512, 1, 3, 2, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 2]),
       ("32 channels x one image, 3 pixel waves of 243 -> 256", [512, 1, 6, 1, 1, 32, 1, 3, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 0])], "TILE4L"),
