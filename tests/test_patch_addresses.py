@@ -324,6 +324,7 @@ FULL = [
     ("conv14, 16x16 atoms, 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 8, 2, 1, 16, 1, 2, 1, 7, 1, 2, 1, 7, 8, 32, 1, 2, 0]),
     ("conv56, 64 channels x 4 rows", (1, 64, 56, 56, 64, 3, 3, 1, 1), [1, 1, 1, 2, 1, 32, 14, 2, 1, 2, 1, 1, 1, 56, 2, 32, 1, 2, 0]),
     ("C2 (27 x 27, 5x5, odd width), 64 channels x 9 rows, single stage", (512, 64, 27, 27, 192, 5, 5, 1, 2), [512, 1, 3, 2, 1, 32, 3, 1, 1, 9, 1, 1, 1, 27, 4, 16, 0, 2, 2]),
+    ("C2, 64 channels x 9 rows, folded to 2 waves of 32 x 243 (the last workgroup's last pair ends the image tensor)", (512, 64, 27, 27, 192, 5, 5, 1, 2), [512, 1, 3, 4, 1, 16, 3, 1, 3, 3, 1, 1, 1, 27, 4, 16, 0, 2, 0]),
     ("conv14, 64 channels x 7 rows shared by 4 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 4, 1, 2, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 2]),
     ("conv14, 128 channels x 2 rows x 2 images shared by 4 waves, single stage", (32, 256, 14, 14, 256, 3, 3, 1, 1), [16, 2, 2, 1, 4, 32, 7, 1, 1, 2, 1, 1, 1, 14, 8, 32, 0, 2, 2]),
     ("conv14, 32 channels x 7 rows shared by 8 waves", (32, 256, 14, 14, 256, 3, 3, 1, 1), [32, 1, 8, 1, 1, 32, 2, 1, 1, 7, 1, 1, 1, 14, 8, 32, 1, 2, 3]),
