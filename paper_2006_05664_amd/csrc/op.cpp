@@ -308,41 +308,41 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                 }
                 // the waves along Cout are merged, a prime at a time, until an atom fits the wave tile
                 for (; !patch_cs; ) {
-                for (int64_t kw = int64_t(kReductionWaves[c[18]]); kw >= 1 && !patch_cs && tm % 16 == 0; kw /= 2) {
-                    int64_t wn = WN, tn = TN;
-                    while (wm * wn * kw > kMaxThreads / 64 && wn > 1) { const int64_t q = prime(wn); wn /= q; tn *= q; }
-                    const int64_t nw = wm * wn * kw, nt = 64 * nw;
-                    if (nt > kMaxThreads) continue;
-                    auto fits = [&](int64_t at) {
-                        return tm % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(tn, at) <= 2 * tn && tm * up(tn, at) <= 64 * kMaxAcc;
-                    };
-                    const int at = fits(32) && (!fits(16) || up(tn, 32) == up(tn, 16)) ? 32 : fits(16) ? 16 : 0;
-                    if (!at || kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // no atom fits; more waves than steps
-                    // the fill: per thread, tasks of two channels x two pixels (one pixel in an image one pixel wide) and of two channels x all taps (kernel tensor)
-                    const int64_t fill_p = (cs / 2 * (op.win >= 2 ? pw / 2 + 1 : pw) * ph * nb2 + nt - 1) / nt, fill_a = (wm * tm * cs / 2 + nt - 1) / nt;
-                    // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
-                    // atom row and column; three sets for small wave tiles), the fill (3 + 2 per image task, 2 + taps per
-                    // kernel-tensor task: plan + data in flight), 24 for addresses, and where waves share a tile 40 + three
-                    // quarters of the accumulators again (the final sum moves them through ordinary registers).  An eighth
-                    // over is let through: the compiler fits such members.  Calibrated on compiled members: of 150 random
-                    // eligible ones the rule lets no spilling member through and turns away 3 that would have fitted; a
-                    // member that spills all the same is refused when its kernel is loaded.
-                    const int64_t fill = 5 * fill_p + (2 + taps) * fill_a;
-                    const int64_t accs = tm * up(tn, at) / 64;
-                    const int64_t frags = tm / at + up(tn, at) / at;
-                    const int64_t need = accs + (frags <= 3 ? 12 : 8) * frags + 24 + fill + (kw > 1 ? 40 + accs * 3 / 4 : 0);
-                    const int64_t have = 512 / ((nw + 3) / 4);
-                    // adding the partial sums of kw waves needs room for one atom of every wave
-                    const int64_t lds_r = kw > 1 ? nw * (at == 32 ? 4 : 1) * 1024 : 0;
-                    if (lds_p <= kMaxLds && lds_r <= kMaxLds && need <= have + have / 8) {
-                        patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage; patch_kw = int(kw);
-                        // the member as the template runs it
-                        WM = wm; TM = tm; WN = wn; TN = tn; FM = std::gcd(FM, TM); FN = std::gcd(FN, TN);
-                        ksteps = slabs; BK = cs * taps;
+                    for (int64_t kw = int64_t(kReductionWaves[c[18]]); kw >= 1 && !patch_cs && tm % 16 == 0; kw /= 2) {
+                        int64_t wn = WN, tn = TN;
+                        while (wm * wn * kw > kMaxThreads / 64 && wn > 1) { const int64_t q = prime(wn); wn /= q; tn *= q; }
+                        const int64_t nw = wm * wn * kw, nt = 64 * nw;
+                        if (nt > kMaxThreads) continue;
+                        auto fits = [&](int64_t at) {
+                            return tm % at == 0 && cs % (at == 32 ? 16 : 32) == 0 && up(tn, at) <= 2 * tn && tm * up(tn, at) <= 64 * kMaxAcc;
+                        };
+                        const int at = fits(32) && (!fits(16) || up(tn, 32) == up(tn, 16)) ? 32 : fits(16) ? 16 : 0;
+                        if (!at || kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // no atom fits; more waves than steps
+                        // the fill: per thread, tasks of two channels x two pixels (one pixel in an image one pixel wide) and of two channels x all taps (kernel tensor)
+                        const int64_t fill_p = (cs / 2 * (op.win >= 2 ? pw / 2 + 1 : pw) * ph * nb2 + nt - 1) / nt, fill_a = (wm * tm * cs / 2 + nt - 1) / nt;
+                        // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
+                        // atom row and column; three sets for small wave tiles), the fill (3 + 2 per image task, 2 + taps per
+                        // kernel-tensor task: plan + data in flight), 24 for addresses, and where waves share a tile 40 + three
+                        // quarters of the accumulators again (the final sum moves them through ordinary registers).  An eighth
+                        // over is let through: the compiler fits such members.  Calibrated on compiled members: of 150 random
+                        // eligible ones the rule lets no spilling member through and turns away 3 that would have fitted; a
+                        // member that spills all the same is refused when its kernel is loaded.
+                        const int64_t fill = 5 * fill_p + (2 + taps) * fill_a;
+                        const int64_t accs = tm * up(tn, at) / 64;
+                        const int64_t frags = tm / at + up(tn, at) / at;
+                        const int64_t need = accs + (frags <= 3 ? 12 : 8) * frags + 24 + fill + (kw > 1 ? 40 + accs * 3 / 4 : 0);
+                        const int64_t have = 512 / ((nw + 3) / 4);
+                        // adding the partial sums of kw waves needs room for one atom of every wave
+                        const int64_t lds_r = kw > 1 ? nw * (at == 32 ? 4 : 1) * 1024 : 0;
+                        if (lds_p <= kMaxLds && lds_r <= kMaxLds && need <= have + have / 8) {
+                            patch_cs = cs; patch_atom = at; patch_stages = st; patch_row = prow; patch_image = pimage; patch_kw = int(kw);
+                            // the member as the template runs it
+                            WM = wm; TM = tm; WN = wn; TN = tn; FM = std::gcd(FM, TM); FN = std::gcd(FN, TN);
+                            ksteps = slabs; BK = cs * taps;
+                        }
                     }
-                }
-                if (wm == 1) break;
-                const int64_t q = prime(wm); wm /= q; tm *= q;
+                    if (wm == 1) break;
+                    const int64_t q = prime(wm); wm /= q; tm *= q;
                 }
             }
         } else {
