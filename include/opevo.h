@@ -270,7 +270,7 @@ typedef enum { OPEVO_F32 = 0, OPEVO_BF16 = 1, OPEVO_F16 = 2 } opevo_dtype;
  *         for something else keeps its workgroup tile and is divided among the waves another way: shorter slabs
  *         are merged and slabs too long for the LDS halved, wave tiles of fewer than 16 output channels merged
  *         along Cout, waves beyond 16 merged along the pixels.  Where that does not help (fp32 inputs, fewer than
- *         16 input channels, a patch too large for the LDS) layout = 2 runs the layout = 0 kernel.  Same sum in
+ *         16 input channels, an image one pixel wide, a patch too large for the LDS) layout = 2 runs the layout = 0 kernel.  Same sum in
  *         another order.
  *         kwaves (DISCRETE, layout = 2 only, inert elsewhere): that many waves share every wave tile and deal the
  *         slab's MFMA steps (taps x groups of channels) round-robin among themselves; their partial sums are added

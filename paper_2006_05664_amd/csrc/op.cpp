@@ -283,7 +283,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
             // another division of it among the waves): slabs of fewer than 16 channels are merged, slabs too long for the
             // LDS halved; wave tiles of fewer than 16 output channels are merged along Cout; with more than 16 waves kwaves
             // is halved, then the waves along the pixels are merged a prime at a time (their tiles grow).
-            if (c[17] == 2 && op.dtype != OPEVO_F32 && op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
+            if (c[17] == 2 && op.dtype != OPEVO_F32 && op.win >= 2 && op.b_elems() < (int64_t(1) << 30) && op.a_elems() < (int64_t(1) << 30)) {
                 auto up = [](int64_t v, int64_t a) { return (v + a - 1) / a * a; };
                 auto prime = [](int64_t n) { for (int64_t q = 2; q * q <= n; ++q) if (n % q == 0) return q; return n; };
                 int64_t cs = c[15], tm = TM, wm = WM;
@@ -318,7 +318,7 @@ int decode(const opevo_op &op, int variant, const int32_t *cfg, Decoded &out)
                         };
                         const int at = fits(32) && (!fits(16) || up(tn, 32) == up(tn, 16)) ? 32 : fits(16) ? 16 : 0;
                         if (!at || kw > taps * (cs / (at == 32 ? 16 : 32))) continue;   // no atom fits; more waves than steps
-                        // the fill: per thread, tasks of two channels x two pixels (one pixel in an image one pixel wide) and of two channels x all taps (kernel tensor)
+                        // the fill: per thread, tasks of two channels x two pixels (images one pixel wide, which the template would fill pixel by pixel, stay with layout 0) and of two channels x all taps (kernel tensor)
                         const int64_t fill_p = (cs / 2 * (op.win >= 2 ? pw / 2 + 1 : pw) * ph * nb2 + nt - 1) / nt, fill_a = (wm * tm * cs / 2 + nt - 1) / nt;
                         // Registers: a lane has 512 / (waves per SIMD).  Counted: the accumulators, two sets of fragments (4 per
                         // atom row and column; three sets for small wave tiles), the fill (3 + 2 per image task, 2 + taps per

@@ -551,6 +551,10 @@ def test_conv_patch_space_and_its_decoding():
     # an image of odd width is filled by pairs of pixels at 2-byte alignment: same template
     c27 = _op((P.OPEVO_CONV2D, (4, 64, 27, 27, 64, 5, 5, 1, 2)), P.OPEVO_BF16)
     assert P.opevo_kernel_plan(c27, V, [4, 1, 1, 2, 1, 32, 3, 3, 1, 3, 1, 1, 1, 27, 4, 16, 0, 2, 0]).path == 5
+    # an image one pixel wide has no pairs of pixels: layout 0
+    c1w = _op((P.OPEVO_CONV2D, (4, 32, 8, 1, 32, 3, 1, 1, 0)), P.OPEVO_BF16)
+    assert P.opevo_kernel_plan(c1w, V, [4, 1, 1, 1, 1, 32, 1, 1, 1, 6, 1, 1, 1, 1, 1, 32, 0, 2, 0]).path != 5
+    assert P.opevo_kernel_plan(_op((P.OPEVO_CONV2D, (4, 32, 8, 2, 32, 3, 1, 1, 0)), P.OPEVO_BF16), V, [4, 1, 1, 1, 1, 32, 1, 1, 1, 6, 1, 1, 1, 2, 1, 32, 0, 2, 0]).path == 5
     # three input channels (the paper's C1): no slab of 16 channels, no patch member
     c1 = _op((P.OPEVO_CONV2D, (16, 3, 35, 35, 16, 11, 11, 4, 0)), P.OPEVO_BF16)
     assert P.opevo_kernel_plan(c1, V, [1, 16, 1, 1, 1, 16, 7, 1, 1, 1, 7, 1, 1, 1, 1, 3, 1, 2, 0]).path != 5
